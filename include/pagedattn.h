@@ -1,0 +1,165 @@
+/*
+ * pagedattn.h -- C ABI of the MI355X (gfx950) paged-KV attention library.
+ *
+ * The library implements the hot path of "Paged Attention Meets FlexAttention"
+ * (arXiv 2506.07311): the KV cache of every sequence lives in fixed-size
+ * physical pages of two global pools (K and V, Sec. III-B "Paged KV-Manager"),
+ * a per-sequence block table of 32-bit entries maps logical block b to a
+ * physical page (Algorithm 1), and attention reads the scattered pages in place
+ * -- no contiguous copy (Sec. I-A, challenge 2) -- under the length mask of
+ * Sec. III-B "FlexAttention Kernel".
+ *
+ * Conventions common to every entry point
+ *   - Every array pointer is a DEVICE pointer owned by the caller.  The
+ *     descriptor struct itself and all scalars are host values.
+ *   - The library allocates no device memory and never synchronises: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and results are valid once the caller has synchronised it.
+ *   - Host-checkable violations (NULL pointer, unsupported shape, workspace too
+ *     small, ...) are rejected before anything is launched and reported through
+ *     the returned pa_status.  Device-side CONTENTS are caller preconditions and
+ *     are not checked: block-table entries that are dereferenced lie in
+ *     [0, num_pages); positions and lengths fit max_blocks * page_size; one
+ *     append call never writes a slot twice.
+ *   - batch == 0, T == 0 or total_q == 0 returns PA_OK without launching.
+ *   - Index arithmetic is 64-bit: pools beyond 2^31 elements are fine.
+ */
+#ifndef PAGEDATTN_H
+#define PAGEDATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PA_OK = 0,
+    PA_ERR_INVALID_ARG = 1,          /* NULL pointer, negative size, Hq % Hkv != 0, page size not a power of two */
+    PA_ERR_UNSUPPORTED = 2,          /* dtype / head_dim / stride combination no kernel is written for            */
+    PA_ERR_WORKSPACE_TOO_SMALL = 3,  /* workspace_bytes < paged_attention_workspace_bytes(...)                    */
+    PA_ERR_HIP = 4                   /* a HIP launch reported an error                                            */
+} pa_status;
+
+typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
+
+/*
+ * The two global pools (Sec. III-B: "two global buffers store K and V pages").
+ * Algorithm 1 addresses them by the flat slot p = page * P + o; the literal
+ * layout is therefore token-major [num_pages, page_size, num_kv_heads, head_dim]
+ * with page_stride = P*Hkv*d, token_stride = Hkv*d, head_stride = d.  Strides
+ * are in ELEMENTS and let a head-major pool [NP, Hkv, P, d] be described too.
+ * head_dim is innermost and contiguous; every stride must be a multiple of
+ * 16 bytes.  page_size must be a power of two (Algorithm 1, Require).
+ * Supported: head_dim a multiple of 8 (bf16) / 4 (fp32), at most 256.
+ */
+typedef struct {
+    void*    k_cache;
+    void*    v_cache;
+    int64_t  page_stride;
+    int64_t  token_stride;
+    int64_t  head_stride;
+    int32_t  num_pages;
+    int32_t  page_size;
+    int32_t  num_kv_heads;
+    int32_t  head_dim;
+    pa_dtype dtype;
+} pa_kv_cache_desc;
+
+/*
+ * Algorithm 1, Assign.  For every appended token i in [0, T):
+ *     s = seq_ids[i], t = positions[i], b = floor(t / P), o = t mod P,
+ *     p = block_table[s][b] * P + o,   K[p] <- k_new[i],   V[p] <- v_new[i].
+ * k_new, v_new : [T, Hkv, d] contiguous, cache dtype.  seq_ids, positions :
+ * int32[T].  block_table : int32[batch, max_blocks] row-major.  The copy is
+ * bytewise (bit-exact).  Writing one slot twice in a call is undefined.
+ */
+pa_status paged_kv_append(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new,
+                          const int32_t* seq_ids, const int32_t* positions, int32_t T,
+                          const int32_t* block_table, int32_t batch, int32_t max_blocks, void* stream);
+
+/*
+ * Algorithm 1, Gather -- a verification utility; attention itself never makes
+ * this copy.  For sequence s and t in [0, seq_lens[s]) the slot's Hkv*d
+ * elements are copied bytewise to row cu_seq_lens[s] + t of out_k / out_v
+ * ([sum(seq_lens), Hkv, d] contiguous).  cu_seq_lens : int32[batch + 1]
+ * exclusive prefix sum of seq_lens.  max_seq_len : host upper bound of
+ * seq_lens (sizes the grid without a device read).
+ */
+pa_status paged_kv_gather(const pa_kv_cache_desc* cache, void* out_k, void* out_v,
+                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* cu_seq_lens,
+                          int32_t batch, int32_t max_blocks, int32_t max_seq_len, void* stream);
+
+/*
+ * Upper bound (pure host function) of the split-KV workspace the two attention
+ * entry points need for these sizes: fp32 partial outputs and (max, sum)
+ * statistics per (query, head, context chunk).  Pass total_q = batch for
+ * decode.  Always a multiple of 256; never 0.
+ */
+size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim,
+                                       int32_t total_q, int32_t max_seq_len);
+
+/*
+ * Decode: one query token per sequence attends to its whole context.
+ *     out[s,h,:] = sum_{j < len_s} softmax_j( scale * <q[s,h,:], K_s[j, floor(h/G), :]> ) V_s[j, floor(h/G), :]
+ * where K_s[j] is the slot Algorithm 1 maps (s, j) to and G = Hq / Hkv.  Keys
+ * j >= seq_lens[s] are masked by selection (Sec. III-B mask, read 0-based), so
+ * unused slots may hold anything, NaN included.  seq_lens counts the tokens
+ * already appended for this step.  seq_lens[s] == 0 gives out = 0, lse = -inf.
+ * q, out : [batch, Hq, d] contiguous, cache dtype (fp32 accumulation, bf16
+ * outputs rounded to nearest even).  lse : NULL or float[batch, Hq], natural
+ * log-sum-exp of the scaled scores.  max_seq_len : host upper bound of
+ * seq_lens, used to size the grid.  workspace : at least
+ * paged_attention_workspace_bytes(batch, Hq, d, batch, max_seq_len) bytes,
+ * 256-byte aligned; its contents need not be initialised.
+ */
+pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                 const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                 int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Prefill / general ragged form: sequence s contributes q_len_s =
+ * cu_q_lens[s+1] - cu_q_lens[s] packed queries (cu_q_lens : int32[batch + 1],
+ * the prefix-sum vector of Sec. III-B).  Query i of sequence s sits at absolute
+ * position pos = seq_lens[s] - q_len_s + i and attends to keys
+ *     j < seq_lens[s]            (causal == 0)
+ *     j <= pos                   (causal != 0).
+ * q, out : [total_q, Hq, d]; lse : NULL or float[total_q, Hq].  max_q_len :
+ * host upper bound of q_len_s.  Other arguments as for decode (workspace sized
+ * with this call's total_q).
+ */
+pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                  const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len,
+                                  const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                  int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                  int32_t causal, void* workspace, size_t workspace_bytes, void* stream);
+
+const char* pa_status_string(pa_status status);
+
+/*
+ * Tuning knobs (host state, process-wide, not thread-safe against concurrent
+ * launches).  name is one of
+ *   "decode_chunk_tokens"  context tokens per split-KV workgroup (0 = heuristic)
+ *   "force_generic"        1 = always take the portable VALU kernels
+ * Returns PA_ERR_INVALID_ARG for an unknown name or a value out of range.
+ */
+pa_status pa_set_option(const char* name, int64_t value);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
+ * library is bracketed by a pair of HIP events recorded on the launch stream.
+ * pa_profile_read synchronises those events and returns, for the kernel whose
+ * name starts with `kernel_prefix`, the number of launches and their summed
+ * duration in milliseconds since the last pa_profile_reset.  Not for use under
+ * graph capture.
+ */
+pa_status pa_profile_enable(int32_t on);
+pa_status pa_profile_reset(void);
+pa_status pa_profile_read(const char* kernel_prefix, int32_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PAGEDATTN_H */

@@ -1,0 +1,221 @@
+"""ctypes binding of libpagedattn.so -- argument marshalling only.
+
+Every function has the name and argument meaning of its C entry point in
+``include/pagedattn.h``; torch tensors supply device pointers and the current
+HIP stream, nothing else.  There is no CPU fallback: if the HIP library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libpagedattn.so"
+_lib = None
+
+PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1}
+
+EXPORTS = (
+    "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
+    "paged_attention_prefill", "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
+    "pa_profile_read",
+)
+
+
+class PagedAttnError(RuntimeError):
+    pass
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("page_stride", ctypes.c_int64), ("token_stride", ctypes.c_int64),
+                ("head_stride", ctypes.c_int64),
+                ("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load the HIP library built in-tree (``python -m paper_2506_07311_amd.build``)."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise PagedAttnError(
+                f"{path} is missing: build the HIP library first (python -m paper_2506_07311_amd.build). "
+                "There is no CPU fallback.")
+        lib = ctypes.CDLL(path)
+        lib.paged_attention_workspace_bytes.restype = ctypes.c_size_t
+        lib.pa_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("paged_attention_workspace_bytes", "pa_status_string"):
+                getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        msg = load_library().pa_status_string(status).decode()
+        raise PagedAttnError(f"{what}: {msg} (status {status})")
+
+
+def _p(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _i32(t: torch.Tensor, what: str) -> torch.Tensor:
+    if t.dtype != torch.int32 or not t.is_contiguous() or not t.is_cuda:
+        raise PagedAttnError(f"{what} must be a contiguous int32 device tensor")
+    return t
+
+
+def cache_desc(k_cache: torch.Tensor, v_cache: torch.Tensor, head_major: bool = False) -> _Desc:
+    """Descriptor of the pools.  Token-major ``[NP, P, Hkv, d]`` unless head_major (``[NP, Hkv, P, d]``).
+    Either may be a strided view as long as head_dim is contiguous and K and V share strides."""
+    if k_cache.dtype not in PA_DTYPE or v_cache.dtype != k_cache.dtype:
+        raise PagedAttnError(f"unsupported cache dtype {k_cache.dtype}")
+    if k_cache.dim() != 4 or k_cache.shape != v_cache.shape or k_cache.stride() != v_cache.stride():
+        raise PagedAttnError("k_cache and v_cache must be 4-d with equal shapes and strides")
+    if not (k_cache.is_cuda and v_cache.is_cuda) or k_cache.stride(3) != 1:
+        raise PagedAttnError("caches must be device tensors with a contiguous head_dim")
+    if head_major:
+        NP, Hkv, P, d = k_cache.shape
+        sp, sh, st, _ = k_cache.stride()
+    else:
+        NP, P, Hkv, d = k_cache.shape
+        sp, st, sh, _ = k_cache.stride()
+    return _Desc(k_cache.data_ptr(), v_cache.data_ptr(), sp, st, sh, NP, P, Hkv, d, PA_DTYPE[k_cache.dtype])
+
+
+def _dense(t: torch.Tensor, what: str, dtype) -> torch.Tensor:
+    if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise PagedAttnError(f"{what} must be a contiguous device tensor of dtype {dtype}")
+    return t
+
+
+def paged_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table, *, head_major=False,
+                    stream=None) -> None:
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    T = int(seq_ids.shape[0])
+    _dense(k_new, "k_new", k_cache.dtype), _dense(v_new, "v_new", k_cache.dtype)
+    if tuple(k_new.shape) != (T, d.num_kv_heads, d.head_dim) or k_new.shape != v_new.shape:
+        raise PagedAttnError("k_new/v_new must be [T, Hkv, d]")
+    _i32(seq_ids, "seq_ids"), _i32(positions, "positions"), _i32(block_table, "block_table")
+    st = lib.paged_kv_append(ctypes.byref(d), _p(k_new), _p(v_new), _p(seq_ids), _p(positions), ctypes.c_int32(T),
+                             _p(block_table), ctypes.c_int32(block_table.shape[0]),
+                             ctypes.c_int32(block_table.shape[1]), _stream(stream))
+    _check(st, "paged_kv_append")
+
+
+def paged_kv_gather(k_cache, v_cache, block_table, seq_lens, cu_seq_lens, total_tokens: int, max_seq_len: int, *,
+                    head_major=False, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens"), _i32(cu_seq_lens, "cu_seq_lens")
+    out_k = torch.empty((total_tokens, d.num_kv_heads, d.head_dim), dtype=k_cache.dtype, device=k_cache.device)
+    out_v = torch.empty_like(out_k)
+    st = lib.paged_kv_gather(ctypes.byref(d), _p(out_k), _p(out_v), _p(block_table), _p(seq_lens), _p(cu_seq_lens),
+                             ctypes.c_int32(seq_lens.shape[0]), ctypes.c_int32(block_table.shape[1]),
+                             ctypes.c_int32(max_seq_len), _stream(stream))
+    _check(st, "paged_kv_gather")
+    return out_k, out_v
+
+
+def paged_attention_workspace_bytes(batch: int, num_q_heads: int, head_dim: int, total_q: int,
+                                    max_seq_len: int) -> int:
+    return int(load_library().paged_attention_workspace_bytes(
+        ctypes.c_int32(batch), ctypes.c_int32(num_q_heads), ctypes.c_int32(head_dim), ctypes.c_int32(total_q),
+        ctypes.c_int32(max_seq_len)))
+
+
+def _workspace(workspace, nbytes, device):
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def paged_attention_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
+                           out=None, lse=None, workspace=None, head_major=False, stream=None):
+    """Returns ``out`` ([B, Hq, d], dtype of q).  ``lse`` (float32 [B, Hq]) is filled when given."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    B, Hq, hd = q.shape
+    if hd != d.head_dim or seq_lens.shape[0] != B or block_table.shape[0] != B:
+        raise PagedAttnError("q must be [B, Hq, d] with B matching seq_lens and block_table")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens")
+    out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    need = paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len)
+    workspace = _workspace(workspace, need, q.device)
+    st = lib.paged_attention_decode(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
+                                    ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]),
+                                    ctypes.c_int32(max_seq_len), ctypes.c_float(scale), _p(workspace),
+                                    ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(st, "paged_attention_decode")
+    return out
+
+
+def paged_attention_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,
+                            max_seq_len: int, scale: float, causal: bool, *, out=None, lse=None, workspace=None,
+                            head_major=False, stream=None):
+    """Returns ``out`` ([total_q, Hq, d], dtype of q).  ``lse`` (float32 [total_q, Hq]) is filled when given."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    total_q, Hq, hd = q.shape
+    B = int(seq_lens.shape[0])
+    if hd != d.head_dim or block_table.shape[0] != B or cu_q_lens.shape[0] != B + 1:
+        raise PagedAttnError("q must be [total_q, Hq, d]; cu_q_lens int32[B+1]")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens"), _i32(cu_q_lens, "cu_q_lens")
+    out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    need = paged_attention_workspace_bytes(B, Hq, hd, total_q, max_seq_len)
+    workspace = _workspace(workspace, need, q.device)
+    st = lib.paged_attention_prefill(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(cu_q_lens),
+                                     ctypes.c_int32(total_q), ctypes.c_int32(max_q_len), _p(block_table),
+                                     _p(seq_lens), ctypes.c_int32(B), ctypes.c_int32(Hq),
+                                     ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
+                                     ctypes.c_float(scale), ctypes.c_int32(1 if causal else 0), _p(workspace),
+                                     ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                     _stream(stream))
+    _check(st, "paged_attention_prefill")
+    return out
+
+
+def pa_set_option(name: str, value: int) -> None:
+    _check(load_library().pa_set_option(name.encode(), ctypes.c_int64(value)), f"pa_set_option({name})")
+
+
+def pa_profile_enable(on: bool) -> None:
+    _check(load_library().pa_profile_enable(ctypes.c_int32(1 if on else 0)), "pa_profile_enable")
+
+
+def pa_profile_reset() -> None:
+    _check(load_library().pa_profile_reset(), "pa_profile_reset")
+
+
+def pa_profile_read(kernel_prefix: str) -> Tuple[int, float]:
+    n = ctypes.c_int32(0)
+    ms = ctypes.c_double(0.0)
+    _check(load_library().pa_profile_read(kernel_prefix.encode(), ctypes.byref(n), ctypes.byref(ms)),
+           "pa_profile_read")
+    return n.value, ms.value
