@@ -1,0 +1,302 @@
+// C ABI of the paged-attention library: argument validation, split planning and kernel dispatch.
+// Nothing here touches device memory; every check is a host check made before the first launch.
+#include <string.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace pa {
+
+namespace {
+
+struct Options {
+    int64_t decode_chunk_tokens = 0;
+    int64_t force_generic = 0;
+} g_opt;
+
+struct ProfileRecord {
+    std::string kernel;
+    hipEvent_t start;
+    hipEvent_t stop;
+};
+bool g_profile_on = false;
+std::vector<ProfileRecord> g_records;
+std::mutex g_profile_mutex;
+
+inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
+
+bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+pa_status check_cache(const pa_kv_cache_desc* c)
+{
+    if (!c || !c->k_cache || !c->v_cache) return PA_ERR_INVALID_ARG;
+    if (c->dtype != PA_DTYPE_F32 && c->dtype != PA_DTYPE_BF16) return PA_ERR_UNSUPPORTED;
+    if (c->num_pages <= 0 || c->num_kv_heads <= 0 || c->head_dim <= 0) return PA_ERR_INVALID_ARG;
+    if (!is_pow2(c->page_size)) return PA_ERR_INVALID_ARG;   // Algorithm 1 requires a power of two
+    const int epv = 16 / elem_bytes(c->dtype);
+    if (c->head_dim % epv != 0 || c->head_dim > 256) return PA_ERR_UNSUPPORTED;
+    if (c->page_stride <= 0 || c->token_stride <= 0 || c->head_stride <= 0) return PA_ERR_INVALID_ARG;
+    if (c->page_stride % epv || c->token_stride % epv || c->head_stride % epv) return PA_ERR_UNSUPPORTED;
+    if (((uintptr_t)c->k_cache | (uintptr_t)c->v_cache) & 15) return PA_ERR_UNSUPPORTED;
+    return PA_OK;
+}
+
+int32_t nsplit_bound(int32_t max_seq_len)
+{
+    int64_t n = ((int64_t)max_seq_len + kMinChunk - 1) / kMinChunk;
+    if (n < 1) n = 1;
+    if (n > kMaxSplits) n = kMaxSplits;
+    return (int32_t)n;
+}
+
+// Context tokens per split-KV workgroup.  Chunks are a multiple of max(P, 32) so that a chunk starts on a
+// page boundary and on a 32-key MFMA tile; their number never exceeds the bound the workspace is sized by.
+SplitPlan plan_decode(int32_t batch, int32_t max_seq_len, int32_t page_size)
+{
+    const int32_t unit = page_size > 32 ? page_size : 32;
+    int64_t chunk = g_opt.decode_chunk_tokens;
+    if (chunk <= 0) {
+        // aim at a few thousand (sequence, chunk) work items so that 256 CUs stay busy and ragged
+        // batches balance, but keep chunks long enough to amortise a workgroup's start-up
+        const int64_t tokens = (int64_t)batch * max_seq_len;
+        chunk = kMinChunk;
+        while (chunk < 2048 && tokens / chunk > 4096) chunk *= 2;
+    }
+    chunk = (chunk + unit - 1) / unit * unit;
+    const int32_t bound = nsplit_bound(max_seq_len);
+    while (((int64_t)max_seq_len + chunk - 1) / chunk > bound) chunk *= 2;
+    SplitPlan p;
+    p.chunk = (int32_t)chunk;
+    p.nsplit = (int32_t)(((int64_t)max_seq_len + chunk - 1) / chunk);
+    if (p.nsplit < 1) p.nsplit = 1;
+    return p;
+}
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+size_t part_o_bytes(int64_t rows, int32_t hq, int32_t d, int32_t nsplit)
+{
+    return align256((size_t)rows * hq * nsplit * d * sizeof(float));
+}
+
+size_t part_lse_bytes(int64_t rows, int32_t hq, int32_t nsplit)
+{
+    return align256((size_t)rows * hq * nsplit * sizeof(float));
+}
+
+pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                        const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len, const int32_t* block_table,
+                        const int32_t* seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks,
+                        int32_t max_seq_len, float scale, int32_t causal, void* workspace, size_t workspace_bytes,
+                        void* stream, bool decode)
+{
+    pa_status st = check_cache(cache);
+    if (st != PA_OK) return st;
+    if (batch < 0 || total_q < 0 || max_blocks < 0 || max_seq_len < 0 || max_q_len < 0) return PA_ERR_INVALID_ARG;
+    if (num_q_heads <= 0 || num_q_heads % cache->num_kv_heads != 0) return PA_ERR_INVALID_ARG;
+    if (batch == 0 || total_q == 0) return PA_OK;
+    if (!q || !out || !block_table || !seq_lens || (!decode && !cu_q_lens)) return PA_ERR_INVALID_ARG;
+    if (((uintptr_t)q | (uintptr_t)out) & 15) return PA_ERR_UNSUPPORTED;
+    if ((int64_t)max_blocks * cache->page_size < max_seq_len) return PA_ERR_INVALID_ARG;
+    if (!(scale == scale)) return PA_ERR_INVALID_ARG;
+    const size_t need = paged_attention_workspace_bytes(batch, num_q_heads, cache->head_dim, total_q, max_seq_len);
+    if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)workspace & 255) return PA_ERR_INVALID_ARG;
+
+    AttnArgs a;
+    a.cache = make_view(cache);
+    a.dtype = cache->dtype;
+    a.q = q;
+    a.out = out;
+    a.lse = lse;
+    a.cu_q_lens = decode ? nullptr : cu_q_lens;
+    a.block_table = block_table;
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.total_q = total_q;
+    a.max_q_len = max_q_len;
+    a.num_q_heads = num_q_heads;
+    a.max_blocks = max_blocks;
+    a.max_seq_len = max_seq_len;
+    a.scale = scale;
+    a.causal = causal ? 1 : 0;
+    a.plan.chunk = max_seq_len > 0 ? max_seq_len : 1;
+    a.plan.nsplit = 1;
+    if (decode) a.plan = plan_decode(batch, max_seq_len, cache->page_size);
+    a.part_o = reinterpret_cast<float*>(workspace);
+    a.part_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) +
+                                          part_o_bytes(total_q, num_q_heads, cache->head_dim, a.plan.nsplit));
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    if (decode) {
+        if (!g_opt.force_generic && decode_mfma_supported(a))
+            st = launch_decode_mfma(a, s);
+        else
+            st = launch_attention_generic(a, s);
+        if (st != PA_OK) return st;
+        if (a.plan.nsplit > 1) st = launch_merge(a, s);
+        return st;
+    }
+    if (!g_opt.force_generic && prefill_mfma_supported(a)) return launch_prefill_mfma(a, s);
+    return launch_attention_generic(a, s);
+}
+
+}  // namespace
+
+int64_t option_decode_chunk_tokens() { return g_opt.decode_chunk_tokens; }
+int64_t option_force_generic() { return g_opt.force_generic; }
+
+void profile_begin(const char* kernel, hipStream_t stream)
+{
+    if (!g_profile_on) return;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    ProfileRecord r;
+    r.kernel = kernel;
+    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+    (void)hipEventRecord(r.start, stream);
+    g_records.push_back(r);
+}
+
+void profile_end(hipStream_t stream)
+{
+    if (!g_profile_on) return;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    if (!g_records.empty()) (void)hipEventRecord(g_records.back().stop, stream);
+}
+
+}  // namespace pa
+
+using namespace pa;
+
+extern "C" {
+
+pa_status paged_kv_append(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new,
+                          const int32_t* seq_ids, const int32_t* positions, int32_t T, const int32_t* block_table,
+                          int32_t batch, int32_t max_blocks, void* stream)
+{
+    pa_status st = check_cache(cache);
+    if (st != PA_OK) return st;
+    if (T < 0 || batch < 0 || max_blocks < 0) return PA_ERR_INVALID_ARG;
+    if (T == 0) return PA_OK;
+    if (!k_new || !v_new || !seq_ids || !positions || !block_table || batch == 0 || max_blocks == 0)
+        return PA_ERR_INVALID_ARG;
+    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return PA_ERR_UNSUPPORTED;
+    return launch_kv_append(cache, k_new, v_new, seq_ids, positions, T, block_table, max_blocks,
+                            reinterpret_cast<hipStream_t>(stream));
+}
+
+pa_status paged_kv_gather(const pa_kv_cache_desc* cache, void* out_k, void* out_v, const int32_t* block_table,
+                          const int32_t* seq_lens, const int32_t* cu_seq_lens, int32_t batch, int32_t max_blocks,
+                          int32_t max_seq_len, void* stream)
+{
+    pa_status st = check_cache(cache);
+    if (st != PA_OK) return st;
+    if (batch < 0 || max_blocks < 0 || max_seq_len < 0) return PA_ERR_INVALID_ARG;
+    if (batch == 0 || max_seq_len == 0) return PA_OK;
+    if (!out_k || !out_v || !block_table || !seq_lens || !cu_seq_lens) return PA_ERR_INVALID_ARG;
+    if ((int64_t)max_blocks * cache->page_size < max_seq_len) return PA_ERR_INVALID_ARG;
+    if (((uintptr_t)out_k | (uintptr_t)out_v) & 15) return PA_ERR_UNSUPPORTED;
+    return launch_kv_gather(cache, out_k, out_v, block_table, seq_lens, cu_seq_lens, batch, max_blocks, max_seq_len,
+                            reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t total_q,
+                                       int32_t max_seq_len)
+{
+    if (batch <= 0 || num_q_heads <= 0 || head_dim <= 0 || total_q <= 0) return 256;
+    // Only the decode entry point splits the context; the prefill kernels write their outputs directly.
+    if (total_q > batch) return 256;
+    const int32_t ns = nsplit_bound(max_seq_len);
+    return part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
+}
+
+pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                 const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                 int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
+                         max_seq_len, scale, 0, workspace, workspace_bytes, stream, true);
+}
+
+pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                  const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len,
+                                  const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                  int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                  int32_t causal, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_attention(cache, q, out, lse, cu_q_lens, total_q, max_q_len, block_table, seq_lens, batch, num_q_heads,
+                         max_blocks, max_seq_len, scale, causal, workspace, workspace_bytes, stream, false);
+}
+
+const char* pa_status_string(pa_status status)
+{
+    switch (status) {
+        case PA_OK: return "ok";
+        case PA_ERR_INVALID_ARG: return "invalid argument";
+        case PA_ERR_UNSUPPORTED: return "unsupported dtype, shape or alignment";
+        case PA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case PA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+pa_status pa_set_option(const char* name, int64_t value)
+{
+    if (!name) return PA_ERR_INVALID_ARG;
+    if (!strcmp(name, "decode_chunk_tokens")) {
+        if (value < 0 || value > (1 << 24)) return PA_ERR_INVALID_ARG;
+        g_opt.decode_chunk_tokens = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "force_generic")) {
+        if (value != 0 && value != 1) return PA_ERR_INVALID_ARG;
+        g_opt.force_generic = value;
+        return PA_OK;
+    }
+    return PA_ERR_INVALID_ARG;
+}
+
+pa_status pa_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    g_profile_on = on != 0;
+    return PA_OK;
+}
+
+pa_status pa_profile_reset(void)
+{
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    for (auto& r : g_records) {
+        (void)hipEventSynchronize(r.stop);
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_records.clear();
+    return PA_OK;
+}
+
+pa_status pa_profile_read(const char* kernel_prefix, int32_t* launches, double* total_ms)
+{
+    if (!kernel_prefix || !launches || !total_ms) return PA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
+    const size_t n = strlen(kernel_prefix);
+    int32_t count = 0;
+    double sum = 0.0;
+    for (auto& r : g_records) {
+        if (r.kernel.compare(0, n, kernel_prefix) != 0) continue;
+        if (hipEventSynchronize(r.stop) != hipSuccess) return PA_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return PA_ERR_HIP;
+        sum += ms;
+        ++count;
+    }
+    *launches = count;
+    *total_ms = sum;
+    return PA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,220 @@
+// Portable paged attention kernel (VALU, fp32 accumulation) for every shape the MFMA kernels do not
+// cover: fp32 pools, head_dim other than 128, page sizes below 16, group sizes above 16.  One workgroup
+// computes one (query row, query head, context chunk) by flash-style tiles of 1024 keys:
+//   scores  s_j = scale * <q, K[j]>            one key per thread, 16-byte loads along head_dim
+//   mask    keys >= n_keys are never touched   (length mask / causal bound, Sec. III-B)
+//   online softmax over tiles (running max m, sum l, rescaled accumulator)
+//   PV      16 lanes (bf16, d=128) share one V row, key groups are reduced through LDS at the end
+// Page translation follows Algorithm 1 for every key: page = block_table[s][j >> log2 P], o = j & (P-1).
+#include "common.h"
+
+namespace pa {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTile = 1024;
+constexpr int kMaxD = 256;
+
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const void* p, float* f)
+    {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static float load1(const void* base, int64_t i) { return reinterpret_cast<const float*>(base)[i]; }
+    __device__ static void store1(void* base, int64_t i, float v) { reinterpret_cast<float*>(base)[i] = v; }
+};
+struct bf16_tag {};
+template <> struct Vec<bf16_tag> {
+    static constexpr int N = 8;
+    __device__ static void load(const void* p, float* f)
+    {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static float load1(const void* base, int64_t i)
+    {
+        return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(base)[i]);
+    }
+    __device__ static void store1(void* base, int64_t i, float v)
+    {
+        reinterpret_cast<uint16_t*>(base)[i] = (uint16_t)float_to_bf16_bits(v);
+    }
+};
+
+__device__ __forceinline__ float block_max(float v, float* red)
+{
+    v = wave_max(v);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+__device__ __forceinline__ float block_sum(float v, float* red)
+{
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
+    CacheView cache, const void* __restrict__ q, void* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks, float scale,
+    int32_t causal, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk, int32_t nsplit)
+{
+    using V = Vec<T>;
+    constexpr int N = V::N;
+    constexpr int EB = 16 / N;   // bytes per element
+    __shared__ float q_s[kMaxD];
+    __shared__ float sc[kTile];
+    __shared__ float red[4];
+    __shared__ float acc_s[kThreads * 8];
+
+    const int tid = threadIdx.x;
+    const int32_t d = cache.head_dim;
+    const int32_t split = blockIdx.x % nsplit;
+    const int64_t rh = blockIdx.x / nsplit;
+    const int32_t h = (int32_t)(rh % num_q_heads);
+    const int32_t row = (int32_t)(rh / num_q_heads);
+
+    const RowInfo ri = locate_row(cu_q_lens, seq_lens, batch, row, causal);
+    const int32_t s = ri.seq;
+    const int32_t n_keys = ri.n_keys;
+    const int32_t c0 = split * chunk;
+    const int32_t c1 = min(n_keys, c0 + chunk);
+    const int64_t o_idx = (int64_t)row * num_q_heads + h;
+
+    if (c0 >= c1) {
+        if (nsplit == 1) {   // empty context: out = 0, lse = -inf
+            for (int e = tid; e < d; e += kThreads) V::store1(out, o_idx * d + e, 0.f);
+            if (lse && tid == 0) lse[o_idx] = -INFINITY;
+        }
+        return;             // with nsplit > 1 the merge never reads chunks at or beyond n_keys
+    }
+
+    const int32_t G = num_q_heads / cache.num_kv_heads;
+    const int32_t kvh = h / G;
+    for (int e = tid; e < d; e += kThreads) q_s[e] = V::load1(q, o_idx * d + e);
+    __syncthreads();
+
+    const int32_t vpr = d / N;                 // 16-byte vectors per row
+    const int32_t kgroups = kThreads / vpr;    // rows processed concurrently in PV
+    const int32_t kg = tid / vpr;
+    const int32_t vc = tid % vpr;
+    const bool pv_active = kg < kgroups;
+    const int32_t pmask = cache.page_size - 1;
+    const int32_t* table = block_table + (int64_t)s * max_blocks;
+    const char* kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * EB;
+    const char* vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * EB;
+
+    float m = -INFINITY, l = 0.f;
+    float acc[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] = 0.f;
+
+    for (int32_t t0 = c0; t0 < c1; t0 += kTile) {
+        const int32_t tn = min(kTile, c1 - t0);
+        // scores: one key per thread
+        float lmax = -INFINITY;
+        for (int32_t jj = tid; jj < tn; jj += kThreads) {
+            const int32_t j = t0 + jj;
+            const int64_t page = table[j >> cache.log2_page];
+            const char* kr = kbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
+            float dot = 0.f;
+            for (int32_t c = 0; c < vpr; ++c) {
+                float kv[N];
+                V::load(kr + c * 16, kv);
+#pragma unroll
+                for (int e = 0; e < N; ++e) dot = fmaf(q_s[c * N + e], kv[e], dot);
+            }
+            const float sj = dot * scale;
+            sc[jj] = sj;
+            lmax = fmaxf(lmax, sj);
+        }
+        const float m_new = fmaxf(m, block_max(lmax, red));
+        const float alpha = expf(m - m_new);       // m = -inf on the first tile gives 0
+        float lsum = 0.f;
+        for (int32_t jj = tid; jj < tn; jj += kThreads) {
+            const float p = expf(sc[jj] - m_new);
+            sc[jj] = p;
+            lsum += p;
+        }
+        l = l * alpha + block_sum(lsum, red);     // the barriers inside also publish sc[]
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] *= alpha;
+        if (pv_active) {
+            for (int32_t jj = kg; jj < tn; jj += kgroups) {
+                const int32_t j = t0 + jj;
+                const int64_t page = table[j >> cache.log2_page];
+                const char* vr = vbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
+                float vv[N];
+                V::load(vr + vc * 16, vv);
+                const float p = sc[jj];
+#pragma unroll
+                for (int e = 0; e < N; ++e) acc[e] = fmaf(p, vv[e], acc[e]);
+            }
+        }
+        __syncthreads();                           // sc[] is rewritten by the next tile
+    }
+
+    // reduce the key groups: acc_s[kg][d]
+    if (pv_active) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc_s[kg * d + vc * N + e] = acc[e];
+    }
+    __syncthreads();
+    const float inv_l = 1.f / l;
+    for (int e = tid; e < d; e += kThreads) {
+        float sum = 0.f;
+        for (int g = 0; g < kgroups; ++g) sum += acc_s[g * d + e];
+        const float o = sum * inv_l;
+        if (nsplit == 1)
+            V::store1(out, o_idx * d + e, o);
+        else
+            part_o[(o_idx * nsplit + split) * d + e] = o;
+    }
+    if (tid == 0) {
+        const float r = m + logf(l);
+        if (nsplit == 1) { if (lse) lse[o_idx] = r; }
+        else part_lse[o_idx * nsplit + split] = r;
+    }
+}
+
+}  // namespace
+
+pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream)
+{
+    const int64_t blocks = (int64_t)a.total_q * a.num_q_heads * a.plan.nsplit;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    ProfileScope prof("paged_attention_generic_kernel", stream);
+    if (a.dtype == PA_DTYPE_F32) {
+        hipLaunchKernelGGL(paged_attention_generic_kernel<float>, dim3((uint32_t)blocks), dim3(kThreads), 0, stream,
+                           a.cache, a.q, a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch,
+                           a.num_q_heads, a.max_blocks, a.scale, a.causal, a.part_o, a.part_lse, a.plan.chunk,
+                           a.plan.nsplit);
+    } else {
+        hipLaunchKernelGGL(paged_attention_generic_kernel<bf16_tag>, dim3((uint32_t)blocks), dim3(kThreads), 0,
+                           stream, a.cache, a.q, a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch,
+                           a.num_q_heads, a.max_blocks, a.scale, a.causal, a.part_o, a.part_lse, a.plan.chunk,
+                           a.plan.nsplit);
+    }
+    return launch_status();
+}
+
+}  // namespace pa

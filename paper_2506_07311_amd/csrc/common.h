@@ -1,0 +1,185 @@
+// Shared host/device helpers of the gfx950 paged-attention library (internal header).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pagedattn.h"
+
+namespace pa {
+
+// ---------------------------------------------------------------------------------------------
+// Device-side view of the pools and the block table (Algorithm 1's operands).
+// ---------------------------------------------------------------------------------------------
+struct CacheView {
+    const void* k;
+    const void* v;
+    int64_t page_stride;   // elements
+    int64_t token_stride;  // elements
+    int64_t head_stride;   // elements
+    int32_t page_size;     // P (power of two)
+    int32_t log2_page;     // log2(P)
+    int32_t num_kv_heads;
+    int32_t head_dim;
+};
+
+inline CacheView make_view(const pa_kv_cache_desc* c)
+{
+    CacheView v;
+    v.k = c->k_cache;
+    v.v = c->v_cache;
+    v.page_stride = c->page_stride;
+    v.token_stride = c->token_stride;
+    v.head_stride = c->head_stride;
+    v.page_size = c->page_size;
+    int l = 0;
+    while ((1 << l) < c->page_size) ++l;
+    v.log2_page = l;
+    v.num_kv_heads = c->num_kv_heads;
+    v.head_dim = c->head_dim;
+    return v;
+}
+
+// Split-KV plan shared by the decode kernels and the merge kernel.  A sequence of length len is cut
+// into ceil(len / chunk) chunks of `chunk` tokens; partial c of (row, head) lives at
+// part_o[((row * Hq + head) * nsplit + c) * d .. + d) (fp32, normalised) and
+// part_lse[(row * Hq + head) * nsplit + c] (natural-log LSE of the chunk's scaled scores).
+struct SplitPlan {
+    int32_t chunk;   // tokens per chunk; a multiple of max(P, 32)
+    int32_t nsplit;  // grid extent = ceil(max_seq_len / chunk)
+};
+
+constexpr int32_t kMinChunk = 256;     // smallest chunk the planner will pick
+constexpr int32_t kMaxSplits = 512;    // bound of nsplit used to size the workspace
+
+// ---------------------------------------------------------------------------------------------
+// Launch bookkeeping: error capture and optional per-kernel event timing.
+// ---------------------------------------------------------------------------------------------
+void profile_begin(const char* kernel, hipStream_t stream);
+void profile_end(hipStream_t stream);
+
+struct ProfileScope {
+    hipStream_t s;
+    ProfileScope(const char* kernel, hipStream_t stream) : s(stream) { profile_begin(kernel, stream); }
+    ~ProfileScope() { profile_end(s); }
+};
+
+inline pa_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
+}
+
+int64_t option_decode_chunk_tokens();
+int64_t option_force_generic();
+
+// ---------------------------------------------------------------------------------------------
+// Kernel launchers (each defined in its own .hip file).  All take validated arguments.
+// ---------------------------------------------------------------------------------------------
+pa_status launch_kv_append(const pa_kv_cache_desc* c, const void* k_new, const void* v_new, const int32_t* seq_ids,
+                           const int32_t* positions, int32_t T, const int32_t* block_table, int32_t max_blocks,
+                           hipStream_t stream);
+pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, const int32_t* block_table,
+                           const int32_t* seq_lens, const int32_t* cu_seq_lens, int32_t batch, int32_t max_blocks,
+                           int32_t max_seq_len, hipStream_t stream);
+
+struct AttnArgs {
+    CacheView cache;
+    pa_dtype dtype;
+    const void* q;           // [total_q, Hq, d]
+    void* out;               // [total_q, Hq, d]
+    float* lse;              // [total_q, Hq] or null
+    const int32_t* cu_q_lens;  // [batch + 1] or null (decode: row == sequence)
+    const int32_t* block_table;
+    const int32_t* seq_lens;
+    int32_t batch;
+    int32_t total_q;
+    int32_t max_q_len;
+    int32_t num_q_heads;
+    int32_t max_blocks;
+    int32_t max_seq_len;
+    float scale;
+    int32_t causal;
+    float* part_o;           // workspace: partial outputs
+    float* part_lse;         // workspace: partial LSEs
+    SplitPlan plan;
+};
+
+// Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.
+pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream);
+// MFMA decode kernel: bf16, head_dim 128, group size <= 16.
+bool decode_mfma_supported(const AttnArgs& a);
+pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
+// MFMA prefill kernel: bf16, head_dim 128.
+bool prefill_mfma_supported(const AttnArgs& a);
+pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream);
+// LSE merge of the split partials into out / lse.
+pa_status launch_merge(const AttnArgs& a, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// Small device helpers.
+// ---------------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
+{
+    return __uint_as_float(bits16 << 16);
+}
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (NaN stays NaN).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// Which sequence a packed query row belongs to and how many keys it may see.  cu_q_lens is the
+// prefix-sum vector of Sec. III-B (null for decode, where row == sequence).  Query i of a sequence with
+// q_len queries sits at position len - q_len + i; keys 0 .. n_keys-1 are allowed: n_keys = len under the
+// length mask alone, min(len, position + 1) with the causal bound.
+struct RowInfo {
+    int32_t seq;
+    int32_t n_keys;
+};
+
+__device__ __forceinline__ RowInfo locate_row(const int32_t* __restrict__ cu_q_lens,
+                                              const int32_t* __restrict__ seq_lens, int32_t batch, int32_t row,
+                                              int32_t causal)
+{
+    RowInfo r;
+    int32_t q_len = 1, qi = 0;
+    if (cu_q_lens == nullptr) {
+        r.seq = row;
+    } else {
+        int32_t lo = 0, hi = batch;   // largest s with cu_q_lens[s] <= row
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (cu_q_lens[mid] <= row) lo = mid; else hi = mid;
+        }
+        r.seq = lo;
+        q_len = cu_q_lens[lo + 1] - cu_q_lens[lo];
+        qi = row - cu_q_lens[lo];
+    }
+    const int32_t len = seq_lens[r.seq];
+    int32_t n = len;
+    if (causal) n = min(len, len - q_len + qi + 1);
+    r.n_keys = max(n, 0);
+    return r;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+#endif
+
+}  // namespace pa

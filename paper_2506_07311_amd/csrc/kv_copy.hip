@@ -1,0 +1,109 @@
+// Algorithm 1's Assign (append) and Gather as pure 16-byte data movement on gfx950.
+//
+// Both kernels translate a logical token position t of sequence s exactly as Algorithm 1 states:
+//   b = floor(t / P), o = t mod P, slot = block_table[s][b] * P + o,
+// with the slot's element offset taken from the descriptor strides (64-bit arithmetic).  One thread moves
+// one 16-byte piece of one (token, kv head) row, so consecutive lanes cover a row contiguously.
+#include "common.h"
+
+namespace pa {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// vec_per_head = head_dim * elem_size / 16.
+__global__ __launch_bounds__(kThreads) void paged_kv_append_kernel(
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, const uint4* __restrict__ k_new,
+    const uint4* __restrict__ v_new, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ positions,
+    const int32_t* __restrict__ block_table, int64_t total_vec, int32_t vec_per_head, int32_t num_kv_heads,
+    int32_t max_blocks, int32_t log2_page, int64_t page_stride_v, int64_t token_stride_v, int64_t head_stride_v)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total_vec) return;
+    const int32_t vec = (int32_t)(idx % vec_per_head);
+    const int64_t th = idx / vec_per_head;
+    const int32_t h = (int32_t)(th % num_kv_heads);
+    const int64_t i = th / num_kv_heads;                 // appended token
+    const int32_t s = seq_ids[i];
+    const int32_t t = positions[i];
+    const int32_t b = t >> log2_page;                    // floor(t / P)
+    const int32_t o = t & ((1 << log2_page) - 1);        // t mod P
+    const int64_t page = block_table[(int64_t)s * max_blocks + b];
+    const int64_t dst = page * page_stride_v + (int64_t)o * token_stride_v + (int64_t)h * head_stride_v + vec;
+    if (blockIdx.y == 0)
+        k_cache[dst] = k_new[idx];
+    else
+        v_cache[dst] = v_new[idx];
+}
+
+__global__ __launch_bounds__(kThreads) void paged_kv_gather_kernel(
+    const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, uint4* __restrict__ out_k,
+    uint4* __restrict__ out_v, const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
+    const int32_t* __restrict__ cu_seq_lens, int32_t vec_per_head, int32_t num_kv_heads, int32_t max_blocks,
+    int32_t log2_page, int64_t page_stride_v, int64_t token_stride_v, int64_t head_stride_v)
+{
+    const int32_t s = blockIdx.y;
+    const int32_t len = seq_lens[s];
+    const int64_t vec_per_token = (int64_t)vec_per_head * num_kv_heads;
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // over (t, h, vec) of this sequence
+    if (idx >= (int64_t)len * vec_per_token) return;
+    const int32_t vec = (int32_t)(idx % vec_per_head);
+    const int64_t th = idx / vec_per_head;
+    const int32_t h = (int32_t)(th % num_kv_heads);
+    const int32_t t = (int32_t)(th / num_kv_heads);
+    const int32_t b = t >> log2_page;
+    const int32_t o = t & ((1 << log2_page) - 1);
+    const int64_t page = block_table[(int64_t)s * max_blocks + b];
+    const int64_t src = page * page_stride_v + (int64_t)o * token_stride_v + (int64_t)h * head_stride_v + vec;
+    const int64_t dst = (int64_t)cu_seq_lens[s] * vec_per_token + idx;
+    if (blockIdx.z == 0)
+        out_k[dst] = k_cache[src];
+    else
+        out_v[dst] = v_cache[src];
+}
+
+inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
+
+}  // namespace
+
+pa_status launch_kv_append(const pa_kv_cache_desc* c, const void* k_new, const void* v_new, const int32_t* seq_ids,
+                           const int32_t* positions, int32_t T, const int32_t* block_table, int32_t max_blocks,
+                           hipStream_t stream)
+{
+    const CacheView v = make_view(c);
+    const int eb = elem_bytes(c->dtype);
+    const int32_t epv = 16 / eb;                               // elements per 16-byte vector
+    const int32_t vec_per_head = c->head_dim / epv;
+    const int64_t total_vec = (int64_t)T * c->num_kv_heads * vec_per_head;
+    const int64_t blocks = (total_vec + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    ProfileScope prof("paged_kv_append_kernel", stream);
+    hipLaunchKernelGGL(paged_kv_append_kernel, dim3((uint32_t)blocks, 2, 1), dim3(kThreads), 0, stream,
+                       (uint4*)c->k_cache, (uint4*)c->v_cache, (const uint4*)k_new, (const uint4*)v_new, seq_ids,
+                       positions, block_table, total_vec, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
+                       c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
+    return launch_status();
+}
+
+pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, const int32_t* block_table,
+                           const int32_t* seq_lens, const int32_t* cu_seq_lens, int32_t batch, int32_t max_blocks,
+                           int32_t max_seq_len, hipStream_t stream)
+{
+    const CacheView v = make_view(c);
+    const int eb = elem_bytes(c->dtype);
+    const int32_t epv = 16 / eb;
+    const int32_t vec_per_head = c->head_dim / epv;
+    const int64_t per_seq = (int64_t)max_seq_len * c->num_kv_heads * vec_per_head;
+    const int64_t blocks = (per_seq + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL || batch > 65535) return PA_ERR_UNSUPPORTED;
+    if (blocks == 0) return PA_OK;
+    ProfileScope prof("paged_kv_gather_kernel", stream);
+    hipLaunchKernelGGL(paged_kv_gather_kernel, dim3((uint32_t)blocks, (uint32_t)batch, 2), dim3(kThreads), 0, stream,
+                       (const uint4*)c->k_cache, (const uint4*)c->v_cache, (uint4*)out_k, (uint4*)out_v, block_table,
+                       seq_lens, cu_seq_lens, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
+                       c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
+    return launch_status();
+}
+
+}  // namespace pa

@@ -1,0 +1,62 @@
+// Split-KV merge: combines the per-chunk softmax partials of one (query row, head) exactly.
+// With partial c holding the normalised output o_c and lse_c = log sum_j exp(score_j) over its keys,
+//   M = max_c lse_c,  w_c = exp(lse_c - M),  out = sum_c w_c o_c / sum_c w_c,  lse = M + log sum_c w_c.
+// Only the ceil(n_keys / chunk) chunks that hold keys are read; a row without keys gets out = 0, lse = -inf.
+#include "common.h"
+
+namespace pa {
+
+namespace {
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void paged_attention_merge_kernel(
+    const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
+    float* __restrict__ lse, const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ seq_lens,
+    int32_t batch, int32_t num_q_heads, int32_t d, int32_t causal, int32_t chunk, int32_t nsplit)
+{
+    const int32_t row = blockIdx.x / num_q_heads;
+    const int64_t o_idx = blockIdx.x;
+    const RowInfo ri = locate_row(cu_q_lens, seq_lens, batch, row, causal);
+    const int32_t n = (ri.n_keys + chunk - 1) / chunk;   // chunks that hold keys
+    const float* pl = part_lse + o_idx * nsplit;
+    const float* po = part_o + o_idx * nsplit * d;
+    const int e = threadIdx.x;
+
+    float M = -INFINITY;
+    for (int32_t c = 0; c < n; ++c) M = fmaxf(M, pl[c]);
+    float wsum = 0.f, acc = 0.f;
+    for (int32_t c = 0; c < n; ++c) {
+        const float w = expf(pl[c] - M);
+        wsum += w;
+        if (e < d) acc = fmaf(w, po[(int64_t)c * d + e], acc);
+    }
+    const float r = n > 0 ? acc / wsum : 0.f;
+    if (e < d) {
+        if (BF16)
+            reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
+        else
+            reinterpret_cast<float*>(out)[o_idx * d + e] = r;
+    }
+    if (lse && e == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
+}
+
+}  // namespace
+
+pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
+{
+    const int64_t blocks = (int64_t)a.total_q * a.num_q_heads;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    const int threads = ((a.cache.head_dim + 63) / 64) * 64;
+    ProfileScope prof("paged_attention_merge_kernel", stream);
+    if (a.dtype == PA_DTYPE_BF16)
+        hipLaunchKernelGGL(paged_attention_merge_kernel<true>, dim3((uint32_t)blocks), dim3(threads), 0, stream,
+                           a.part_o, a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads,
+                           a.cache.head_dim, a.causal, a.plan.chunk, a.plan.nsplit);
+    else
+        hipLaunchKernelGGL(paged_attention_merge_kernel<false>, dim3((uint32_t)blocks), dim3(threads), 0, stream,
+                           a.part_o, a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads,
+                           a.cache.head_dim, a.causal, a.plan.chunk, a.plan.nsplit);
+    return launch_status();
+}
+
+}  // namespace pa

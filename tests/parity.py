@@ -1,0 +1,99 @@
+"""Helpers shared by the GPU parity tests: run one workload through the C-ABI library and through
+the CPU oracle, and compare under the stated tolerances."""
+import numpy as np
+import torch
+
+from paper_2506_07311_amd import workloads as W
+
+# Tolerances (both measures must hold):
+#   max-abs  = max |g - r|
+#   max-rel  = max |g - r| / max(|r|, rms(r))   -- floored at the reference tensor's RMS so that zero
+#              crossings do not blow the ratio up and an all-zero output cannot pass on max-abs alone
+# bf16 I/O with fp32 accumulation: 1e-2 / 2e-2.  fp32 I/O: 1e-5 / 1e-5.
+TOL = {torch.bfloat16: (1e-2, 2e-2), torch.float32: (1e-5, 1e-5)}
+
+
+def errors(got: np.ndarray, ref: np.ndarray):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(got - ref)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    denom = np.maximum(np.abs(ref), max(rms, 1e-30))
+    return (float(diff.max()) if diff.size else 0.0), (float((diff / denom).max()) if diff.size else 0.0)
+
+
+def assert_close(got, ref, dtype, what=""):
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), f"{what}: non-finite GPU output"
+    max_abs, max_rel = errors(got, ref)
+    tol_abs, tol_rel = TOL[dtype]
+    assert max_abs <= tol_abs and max_rel <= tol_rel, \
+        f"{what}: max-abs {max_abs:.3e} (tol {tol_abs}), max-rel {max_rel:.3e} (tol {tol_rel})"
+    return max_abs, max_rel
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().double().cpu().numpy()
+
+
+def oracle_step(oracle, w: W.PagedWorkload, append=True, seqs=None):
+    """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse).
+    ``seqs`` restricts attention to a subset of sequences (rows of out follow that subset's queries)."""
+    k, v = W.to_numpy(w.k_cache).copy(), W.to_numpy(w.v_cache).copy()
+    bt = W.to_numpy(w.block_table)
+    if append and w.seq_ids.numel():
+        oracle.kv_append(k, v, W.to_numpy(w.k_new), W.to_numpy(w.v_new), W.to_numpy(w.seq_ids),
+                         W.to_numpy(w.positions), bt)
+    lens = W.to_numpy(w.seq_lens)
+    cu = W.to_numpy(w.cu_q_lens)
+    q = W.to_numpy(w.q)
+    if seqs is not None:
+        seqs = list(seqs)
+        rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in seqs])
+        q = q[rows]
+        ql = [int(cu[s + 1] - cu[s]) for s in seqs]
+        cu = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+        bt, lens = bt[seqs], lens[seqs]
+    out, lse = oracle.attention(k, v, q, bt, lens, w.scale, causal=w.causal, cu_q_lens=cu)
+    return k, v, out, lse
+
+
+def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True):
+    """Append then attention through the C-ABI binding, in place on the workload's pools."""
+    if append and w.seq_ids.numel():
+        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+    if prefill is None:
+        prefill = w.causal or w.max_q_len > 1 or w.total_q != w.batch
+    lse = torch.full((w.total_q, w.num_q_heads), float("nan"), dtype=torch.float32, device=w.q.device) \
+        if with_lse else None
+    if prefill:
+        out = pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
+                                         w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse)
+    else:
+        out = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+                                        w.scale, lse=lse)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None):
+    """Full parity of one step: pools bit-exact after the append, attention within tolerance."""
+    # the oracle runs first, on host copies taken before the GPU path touches the pools
+    k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, w, seqs=seqs)
+    out, lse = gpu_step(pa, w, prefill=prefill)
+    # NaN-poisoned slots compare by bit pattern
+    def bits(a):
+        return a.view(np.uint32) if a.dtype == np.float32 else a
+    assert np.array_equal(bits(W.to_numpy(w.k_cache)), bits(k_ref)), f"{what}: K pool differs after append"
+    assert np.array_equal(bits(W.to_numpy(w.v_cache)), bits(v_ref)), f"{what}: V pool differs after append"
+    got, got_lse = to_f64(out), to_f64(lse)
+    if seqs is not None:
+        cu = W.to_numpy(w.cu_q_lens)
+        rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in seqs])
+        got, got_lse = got[rows], got_lse[rows]
+    res = assert_close(got, o_ref, w.dtype, what + " out")
+    empty = ~np.isfinite(lse_ref)
+    assert (got_lse[empty] == -np.inf).all(), f"{what}: lse of empty rows must be -inf"
+    if (~empty).any():
+        lse_tol = 1e-4 if w.dtype == torch.float32 else 1e-3
+        assert np.abs(got_lse[~empty] - lse_ref[~empty]).max() <= lse_tol, f"{what}: lse"
+    return res

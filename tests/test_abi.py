@@ -1,0 +1,102 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the header declares, and
+rejects host-checkable argument errors before touching the GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_07311_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        from paper_2506_07311_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pagedattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(paged_\w+|pa_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_three_hot_path_calls():
+    names = declared_functions()
+    for n in ("paged_kv_append", "paged_attention_decode", "paged_attention_prefill", "paged_kv_gather",
+              "paged_attention_workspace_bytes"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in pagedattn.h but not exported"
+    assert set(binding.EXPORTS) == set(declared_functions())
+
+
+def test_status_strings(lib):
+    assert lib.pa_status_string(0) == b"ok"
+    assert b"workspace" in lib.pa_status_string(3)
+
+
+def _desc(**kw):
+    d = dict(k_cache=0x1000, v_cache=0x2000, page_stride=16 * 8 * 128, token_stride=8 * 128, head_stride=128,
+             num_pages=4, page_size=16, num_kv_heads=8, head_dim=128, dtype=1)
+    d.update(kw)
+    return binding._Desc(**d)
+
+
+def test_workspace_bytes_is_positive_multiple_of_256(lib):
+    for args in [(16, 64, 128, 16, 131072), (1, 8, 64, 1, 128), (4, 32, 128, 8192, 2048), (0, 8, 64, 0, 0)]:
+        n = binding.paged_attention_workspace_bytes(*args)
+        assert n > 0 and n % 256 == 0
+    a = binding.paged_attention_workspace_bytes(16, 64, 128, 16, 131072)
+    b = binding.paged_attention_workspace_bytes(16, 64, 128, 16, 1024)
+    assert a >= b
+
+
+def test_host_validation_rejects_before_launch(lib):
+    null = ctypes.c_void_p(0)
+    p = ctypes.c_void_p(0x4000)
+    i32 = ctypes.c_int32
+    # append: NULL descriptor, bad page size, T == 0 is a no-op
+    assert lib.paged_kv_append(null, p, p, p, p, i32(1), p, i32(1), i32(1), null) == 1
+    d = _desc(page_size=12)
+    assert lib.paged_kv_append(ctypes.byref(d), p, p, p, p, i32(1), p, i32(1), i32(1), null) == 1
+    d = _desc()
+    assert lib.paged_kv_append(ctypes.byref(d), p, p, p, p, i32(0), p, i32(1), i32(1), null) == 0
+    assert lib.paged_kv_append(ctypes.byref(d), null, p, p, p, i32(1), p, i32(1), i32(1), null) == 1
+    d = _desc(head_dim=100)
+    assert lib.paged_kv_append(ctypes.byref(d), p, p, p, p, i32(1), p, i32(1), i32(1), null) == 2
+    d = _desc(dtype=7)
+    assert lib.paged_kv_append(ctypes.byref(d), p, p, p, p, i32(1), p, i32(1), i32(1), null) == 2
+    # decode: Hq not a multiple of Hkv, workspace too small, batch == 0 no-op, table too short
+    d = _desc()
+    f = ctypes.c_float(0.1)
+    big = ctypes.c_size_t(1 << 40)
+    ws = ctypes.c_void_p(0x10000)
+    assert lib.paged_attention_decode(ctypes.byref(d), p, p, null, p, p, i32(2), i32(12), i32(4), i32(64), f, ws,
+                                      big, null) == 1
+    assert lib.paged_attention_decode(ctypes.byref(d), p, p, null, p, p, i32(2), i32(32), i32(4), i32(64), f, ws,
+                                      ctypes.c_size_t(16), null) == 3
+    assert lib.paged_attention_decode(ctypes.byref(d), p, p, null, p, p, i32(0), i32(32), i32(4), i32(64), f, ws,
+                                      big, null) == 0
+    assert lib.paged_attention_decode(ctypes.byref(d), p, p, null, p, p, i32(2), i32(32), i32(3), i32(64), f, ws,
+                                      big, null) == 1
+    # prefill: missing cu_q_lens
+    assert lib.paged_attention_prefill(ctypes.byref(d), p, p, null, null, i32(8), i32(4), p, p, i32(2), i32(32),
+                                       i32(4), i32(64), f, i32(1), ws, big, null) == 1
+    # options
+    assert lib.pa_set_option(b"no_such_knob", ctypes.c_int64(1)) == 1
+    assert lib.pa_set_option(b"decode_chunk_tokens", ctypes.c_int64(0)) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(binding.PagedAttnError):
+        binding.load_library()

@@ -1,0 +1,216 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the same
+seeded inputs.  Append / gather are bit-exact; attention is within the tolerances in tests/parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_07311_amd import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pa():
+    import paper_2506_07311_amd as pa_mod
+    pa_mod.load_library()
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return pa_mod
+
+
+def bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+# ----------------------------------------------------------------------------- append / gather (bit-exact)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("P,Hkv,d", [(16, 8, 128), (1, 2, 64), (64, 8, 128), (4, 3, 32), (128, 1, 256)])
+def test_append_and_gather_bit_exact(pa, oracle, dtype, P, Hkv, d):
+    lens = [1, 37, 2 * P + 3, 5 * P, 129]
+    w = W.make_workload("t", seq_lens=lens, q_lens=lens, num_q_heads=Hkv, num_kv_heads=Hkv, head_dim=d,
+                        page_size=P, dtype=dtype, seed=21, device=DEV, poison=False)
+    # sentinel pool: bytes no append writes must survive
+    w.k_cache.fill_(-7.25)
+    w.v_cache.fill_(3.5)
+    k_ref, v_ref = W.to_numpy(w.k_cache).copy(), W.to_numpy(w.v_cache).copy()
+    bt = W.to_numpy(w.block_table)
+    oracle.kv_append(k_ref, v_ref, W.to_numpy(w.k_new), W.to_numpy(w.v_new), W.to_numpy(w.seq_ids),
+                     W.to_numpy(w.positions), bt)
+    pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(W.to_numpy(w.k_cache)), bits(k_ref))
+    assert np.array_equal(bits(W.to_numpy(w.v_cache)), bits(v_ref))
+    # gather of the (oracle-written) pool
+    gk_ref, gv_ref = oracle.kv_gather(k_ref, v_ref, bt, lens)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=DEV)
+    gk, gv = pa.paged_kv_gather(w.k_cache, w.v_cache, w.block_table, w.seq_lens, cu, sum(lens), max(lens))
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(W.to_numpy(gk)), bits(gk_ref))
+    assert np.array_equal(bits(W.to_numpy(gv)), bits(gv_ref))
+    assert np.array_equal(bits(W.to_numpy(gk)), bits(W.to_numpy(w.k_new)))   # gather o append = identity
+
+
+def test_append_nothing_and_gather_empty(pa):
+    w = W.make_workload("t", seq_lens=[0, 0], q_lens=[0, 0], num_q_heads=2, num_kv_heads=2, head_dim=64,
+                        page_size=16, dtype=torch.float32, seed=1, device=DEV, num_pages=4, poison=False)
+    before = w.k_cache.clone()
+    pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+    cu = torch.zeros(3, dtype=torch.int32, device=DEV)
+    gk, gv = pa.paged_kv_gather(w.k_cache, w.v_cache, w.block_table, w.seq_lens, cu, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(before, w.k_cache) and gk.numel() == 0
+
+
+def test_head_major_pool_through_strides(pa, oracle):
+    """A [NP, Hkv, P, d] pool described by strides holds the same logical cache."""
+    w = W.make_workload("t", seq_lens=[50, 17], num_q_heads=8, num_kv_heads=4, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=22, device=DEV)
+    _, _, o_ref, _ = parity.oracle_step(oracle, w)
+    kh = w.k_cache.permute(0, 2, 1, 3).contiguous()
+    vh = w.v_cache.permute(0, 2, 1, 3).contiguous()
+    pa.paged_kv_append(kh, vh, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table, head_major=True)
+    out = pa.paged_attention_decode(kh, vh, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale, head_major=True)
+    torch.cuda.synchronize()
+    parity.assert_close(parity.to_f64(out), o_ref, w.dtype, "head-major decode")
+
+
+# ----------------------------------------------------------------------------- the five workloads, small
+def test_config1_fp32_single_sequence_decode(pa, oracle):
+    parity.check_step(pa, oracle, W.config(1, device=DEV), "config 1")
+
+
+@pytest.mark.parametrize("L", [128, 256, 512, 1024, 2048])
+def test_config2_bf16_gqa_decode(pa, oracle, L):
+    parity.check_step(pa, oracle, W.config(2, device=DEV, context=L), f"config 2 L={L}")
+
+
+@pytest.mark.parametrize("S", [256, 333])
+def test_config3_bf16_causal_prefill_small(pa, oracle, S):
+    parity.check_step(pa, oracle, W.config(3, device=DEV, context=S), f"config 3 S={S}")
+
+
+def test_config4_mixed_lengths_shared_prefix_small(pa, oracle):
+    w = W.config(4, device=DEV, shrink=16)
+    bt = W.to_numpy(w.block_table)
+    assert (bt[1, :2] == bt[0, :2]).all()      # prefix pages really are aliased
+    parity.check_step(pa, oracle, w, "config 4 / 16")
+
+
+@pytest.mark.parametrize("P", [16, 64])
+def test_config5_long_context_small(pa, oracle, P):
+    parity.check_step(pa, oracle, W.config(5, device=DEV, shrink=32, page_size=P), f"config 5 / 32 P={P}")
+
+
+# ----------------------------------------------------------------------------- edge cases and shape sweep
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64),
+                                     (torch.float32, 128), (torch.bfloat16, 256)])
+@pytest.mark.parametrize("P", [1, 2, 8, 16, 32, 128])
+def test_decode_ragged_lengths_and_page_sizes(pa, oracle, dtype, d, P):
+    lens = [0, 1, 2, 15, 16, 17, 31, 33, 255, 257, 700, 1500]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=P, dtype=dtype,
+                        seed=23 + P, device=DEV)
+    parity.check_step(pa, oracle, w, f"ragged decode P={P} d={d} {dtype}")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (8, 8), (16, 8), (32, 8), (64, 8), (16, 1), (24, 8), (40, 2)])
+def test_decode_group_sizes(pa, oracle, Hq, Hkv):
+    w = W.make_workload("t", seq_lens=[300, 77, 1025], num_q_heads=Hq, num_kv_heads=Hkv, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, seed=31, device=DEV)
+    parity.check_step(pa, oracle, w, f"decode Hq={Hq} Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("chunk", [32, 64, 256, 4096])
+def test_decode_split_schedules(pa, oracle, chunk):
+    """Every split schedule merges to the same answer (the LSE merge is exact)."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[2049, 64, 31, 1000, 4096], num_q_heads=32, num_kv_heads=8, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, seed=32, device=DEV)
+    binding.pa_set_option("decode_chunk_tokens", chunk)
+    try:
+        parity.check_step(pa, oracle, w, f"decode chunk={chunk}")
+    finally:
+        binding.pa_set_option("decode_chunk_tokens", 0)
+
+
+@pytest.mark.parametrize("dtype,d,P", [(torch.bfloat16, 128, 16), (torch.float32, 64, 16), (torch.bfloat16, 128, 64),
+                                       (torch.bfloat16, 64, 4), (torch.bfloat16, 128, 2)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_prefill_ragged(pa, oracle, dtype, d, P, causal):
+    """Ragged packed queries, including chunked prefill (fewer queries than keys) and empty sequences."""
+    lens = [130, 64, 1, 0, 257, 40]
+    q_lens = [130, 10, 1, 0, 129, 40]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=8, num_kv_heads=2, head_dim=d,
+                        page_size=P, dtype=dtype, causal=causal, seed=41, device=DEV)
+    parity.check_step(pa, oracle, w, f"ragged prefill {dtype} d={d} P={P} causal={causal}")
+
+
+def test_prefill_row_equals_decode_at_that_length(pa):
+    """Bottom-right causal alignment: row i of a causal prefill is the decode result at length i + 1."""
+    S = 200
+    w = W.make_workload("t", seq_lens=[S], q_lens=[S], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, causal=True, seed=42, device=DEV)
+    out, _ = parity.gpu_step(pa, w)
+    for i in [0, 15, 16, 100, S - 1]:
+        lens = torch.tensor([i + 1], dtype=torch.int32, device=DEV)
+        o = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q[i:i + 1].contiguous(), w.block_table, lens, i + 1,
+                                      w.scale)
+        torch.cuda.synchronize()
+        parity.assert_close(parity.to_f64(o[0]), parity.to_f64(out[i]), w.dtype, f"row {i}")
+
+
+# ----------------------------------------------------------------------------- invariants on the GPU
+def test_one_token_context_returns_v_exactly(pa):
+    w = W.make_workload("t", seq_lens=[1] * 5, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=51, device=DEV)
+    out, _ = parity.gpu_step(pa, w)
+    v = w.v_new.repeat_interleave(4, dim=1)           # the single token's V per query head
+    assert torch.equal(out, v)
+
+
+def test_permuted_pages_equal_contiguous_layout_bitwise(pa, oracle):
+    """Paging changes where bytes live, not what is computed: same logical cache, two physical layouts."""
+    kw = dict(seq_lens=[513, 90, 2048], num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+              dtype=torch.bfloat16, device=DEV, poison=False)
+    a = W.make_workload("perm", seed=52, **kw)
+    out_a, _ = parity.gpu_step(pa, a)
+    # re-house the same tokens contiguously: gather with the oracle, lay out in identity order
+    k, v = W.to_numpy(a.k_cache), W.to_numpy(a.v_cache)
+    gk, gv = oracle.kv_gather(k, v, W.to_numpy(a.block_table), a.seq_lens_host)
+    b = W.make_workload("ident", seed=52, identity_pages=True, **kw)
+    P = 16
+    row = 0
+    kb, vb = W.to_numpy(b.k_cache).copy(), W.to_numpy(b.v_cache).copy()
+    btb = W.to_numpy(b.block_table)
+    for s, L in enumerate(a.seq_lens_host):
+        for blk in range((L + P - 1) // P):
+            n = min(P, L - blk * P)
+            kb[btb[s, blk], :n] = gk[row + blk * P: row + blk * P + n]
+            vb[btb[s, blk], :n] = gv[row + blk * P: row + blk * P + n]
+        row += L
+    b.k_cache = torch.from_numpy(kb.view(np.int16)).view(torch.bfloat16).to(DEV)
+    b.v_cache = torch.from_numpy(vb.view(np.int16)).view(torch.bfloat16).to(DEV)
+    out_b = pa.paged_attention_decode(b.k_cache, b.v_cache, a.q, b.block_table, b.seq_lens, b.max_seq_len, a.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b)
+
+
+def test_aliased_prefix_pages_equal_copied_pages_bitwise(pa):
+    w = W.make_workload("t", seq_lens=[700, 300, 1100, 512], num_q_heads=32, num_kv_heads=8, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, seed=53, device=DEV, share_group=4,
+                        share_prefix_tokens=256, pool_factor=3.0)
+    out_alias, _ = parity.gpu_step(pa, w)
+    # give every sequence private copies of the 16 shared prefix pages, in pages the pool left unused
+    bt = W.to_numpy(w.block_table).copy()
+    used = set(bt[bt >= 0].tolist())
+    free = [p for p in range(w.num_pages) if p not in used]
+    for s in range(1, 4):
+        for b in range(16):
+            dst = free.pop()
+            w.k_cache[dst] = w.k_cache[int(bt[0, b])]
+            w.v_cache[dst] = w.v_cache[int(bt[0, b])]
+            bt[s, b] = dst
+    out_copy = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, torch.from_numpy(bt).to(DEV), w.seq_lens,
+                                         w.max_seq_len, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(out_alias, out_copy)
