@@ -1,5 +1,317 @@
+// Split-KV paged decode for bf16 pools with head_dim 128 on gfx950 (CDNA4), group size G = Hq/Hkv <= 16.
+//
+// Decode is bound by streaming every resident K/V byte once from HBM, so the design is about memory:
+//   * one wave owns one KV head of one (sequence, context chunk); the NW waves of a workgroup own NW
+//     adjacent KV heads, so that together they read whole contiguous token rows of a page;
+//   * each wave walks its chunk in tiles of 32 keys; every K/V byte is fetched by one 16-byte load per
+//     lane straight into the registers the MFMA reads -- no LDS round trip -- and the next tile's 16
+//     loads (16 KB per wave) are in flight while the current tile is computed;
+//   * page translation (Algorithm 1: page = block_table[s][j >> log2 P], slot = j & (P-1)) is wave-uniform
+//     for P >= 16, i.e. scalar: page base in SGPRs plus loop-invariant per-lane offsets.
+// The G grouped query heads turn q.K^T and P.V into small dense contractions, which run on the matrix
+// cores (v_mfma_f32_16x16x32_bf16, G padded to 16 columns):
+//   S^T[key, head] = K[key, :] . Q[head, :]^T    A = K rows exactly as loaded (lane%16 = key)
+//   O^T[dcol, head] += V^T[dcol, key] . P^T[key, head]
+// For P.V the contraction index is the key, while memory is contiguous along head_dim.  Each lane loads
+// 8 keys x 8 head_dim columns and transposes that 8x8 block of 16-bit values in its own registers with
+// 32 byte-permutes; since any key order is valid for a sum, the 8 keys a lane holds are chosen to be the
+// ones whose probabilities the S^T accumulator layout already left in the matching lanes.
+// Softmax statistics are lane-local per head (lane%16 = head in both accumulators); the only cross-lane
+// traffic is a 4-way max per tile and one 4-way sum at the end.
 #include "common.h"
+
 namespace pa {
-bool decode_mfma_supported(const AttnArgs&) { return false; }
-pa_status launch_decode_mfma(const AttnArgs&, hipStream_t) { return PA_ERR_UNSUPPORTED; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int kD = 128;
+constexpr int kTileKeys = 32;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));   // v_cvt_pk_bf16_f32, RNE
 }
+
+__device__ __forceinline__ uint4 load16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
+
+__device__ __forceinline__ uint32_t word(const uint4& v, int w)
+{
+    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+}
+
+struct Tile {
+    uint4 k[2][4];   // [16-key block][32-element step of head_dim]: lane%16 = key, lane/16 = 8-element piece
+    uint4 v[8];      // 8 keys x 8 head_dim columns per lane: lane%16 = column piece, lane/16 selects the keys
+};
+
+// Everything a wave needs to address its KV head's rows.
+struct Addr {
+    const char* kbase;          // pool base + kv head offset
+    const char* vbase;
+    const int32_t* table;       // block-table row of the sequence
+    int64_t page_bytes;
+    int64_t token_bytes;
+    int32_t log2_page;
+    int32_t pmask;
+    uint32_t koff;              // UNIFORM: lane-invariant byte offset of the lane's K piece inside a 16-key block
+    uint32_t voff[4];           // UNIFORM: same for the lane's 4 V rows of a 16-key block
+    int32_t r16, quad;
+};
+
+// Issue the 16 loads of the tile that starts at key `t0`.  Keys at or beyond `c1` are clamped to the last
+// valid key, so every address is a live slot; their scores are masked by the caller.
+template <bool UNIFORM>
+__device__ __forceinline__ void load_tile(Tile& t, const Addr& a, int32_t t0, int32_t c1)
+{
+    if constexpr (UNIFORM) {
+        if (t0 + kTileKeys <= c1) {   // full tile: two 16-key blocks, each inside one page
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const int32_t kb = t0 + 16 * mt;
+                const int64_t page = __builtin_amdgcn_readfirstlane(a.table[kb >> a.log2_page]);
+                const int64_t blk = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
+                const char* kp = a.kbase + blk;
+                const char* vp = a.vbase + blk;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) t.k[mt][ks] = load16(kp + a.koff + 64 * ks);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t.v[4 * mt + i] = load16(vp + a.voff[i]);
+            }
+            return;
+        }
+    }
+    // ragged tail (or page size below 16): per-lane translation of clamped keys
+    const int32_t last = c1 - 1;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int32_t key = min(t0 + 16 * mt + a.r16, last);
+        const int64_t page = a.table[key >> a.log2_page];
+        const char* kp = a.kbase + page * a.page_bytes + (int64_t)(key & a.pmask) * a.token_bytes + a.quad * 16;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) t.k[mt][ks] = load16(kp + 64 * ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int32_t vkey = min(t0 + 16 * mt + 4 * a.quad + i, last);
+            const int64_t vpage = a.table[vkey >> a.log2_page];
+            t.v[4 * mt + i] = load16(a.vbase + vpage * a.page_bytes + (int64_t)(vkey & a.pmask) * a.token_bytes +
+                                     a.r16 * 16);
+        }
+    }
+}
+
+struct State {
+    f32x4 o[8];    // O^T accumulator: o[j][r] = column 32*quad + 8*r + j of head lane%16
+    float m;       // running max of the log2-domain scores of head lane%16
+    float l;       // this lane's share of the running sum
+};
+
+__device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf16x8 (&qf)[4], float sc, int32_t t0,
+                                             int32_t c1, int32_t quad)
+{
+    f32x4 s[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        s[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            s[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[mt][ks]), qf[ks], s[mt], 0,
+                                                            0, 0);
+    }
+    // s[mt][i] is the score of key t0 + 16*mt + 4*quad + i for head lane%16
+    const bool partial = t0 + kTileKeys > c1;    // wave-uniform
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float x = s[mt][i] * sc;
+            if (partial && t0 + 16 * mt + 4 * quad + i >= c1) x = -INFINITY;   // mask by selection
+            s[mt][i] = x;
+            tmax = fmaxf(tmax, x);
+        }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(st.m, tmax);       // finite: every tile holds at least one valid key
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(s[mt][i] - m_new);
+            s[mt][i] = p;
+            psum += p;
+        }
+    st.m = m_new;
+    st.l = st.l * alpha + psum;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
+    }
+    // probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4)
+    uint4 pb;
+    pb.x = pack_bf16(s[0][0], s[0][1]);
+    pb.y = pack_bf16(s[0][2], s[0][3]);
+    pb.z = pack_bf16(s[1][0], s[1][1]);
+    pb.w = pack_bf16(s[1][2], s[1][3]);
+    const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
+    // in-register 8x8 transpose of V, one head_dim column (j) at a time, feeding the A operand
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        uint4 a;   // columns j of rows (0,1), (2,3), (4,5), (6,7): word j/2 of each row, low or high half
+        a.x = __builtin_amdgcn_perm(word(t.v[1], j / 2), word(t.v[0], j / 2), sel);
+        a.y = __builtin_amdgcn_perm(word(t.v[3], j / 2), word(t.v[2], j / 2), sel);
+        a.z = __builtin_amdgcn_perm(word(t.v[5], j / 2), word(t.v[4], j / 2), sel);
+        a.w = __builtin_amdgcn_perm(word(t.v[7], j / 2), word(t.v[6], j / 2), sel);
+        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pfrag, st.o[j], 0, 0, 0);
+    }
+}
+
+template <int NW, bool UNIFORM>
+__global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
+    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t num_q_heads,
+    int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk,
+    int32_t nsplit)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int32_t split = blockIdx.x;
+    const int32_t kvh = blockIdx.y * NW + wave;
+    const int32_t s = blockIdx.z;
+    const int32_t G = num_q_heads / cache.num_kv_heads;
+    const int32_t r16 = lane & 15, quad = lane >> 4;
+    const int32_t len = seq_lens[s];
+    const int32_t c0 = split * chunk;
+    const int32_t c1 = min(len, c0 + chunk);
+    const int32_t h = kvh * G + r16;                       // this lane's query head (valid if r16 < G)
+    const int64_t o_idx = (int64_t)s * num_q_heads + h;
+
+    if (c0 >= c1) {
+        if (nsplit == 1 && r16 < G) {                      // empty sequence: out = 0, lse = -inf
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = uint4{0, 0, 0, 0};
+            if (lse && quad == 0) lse[o_idx] = -INFINITY;
+        }
+        return;
+    }
+
+    // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
+    // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
+    bf16x8 qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        uint4 v = uint4{0, 0, 0, 0};
+        if (r16 < G) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
+        qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+
+    Addr a;
+    a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
+    a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
+    a.table = block_table + (int64_t)s * max_blocks;
+    a.page_bytes = cache.page_stride * 2;
+    a.token_bytes = cache.token_stride * 2;
+    a.log2_page = cache.log2_page;
+    a.pmask = cache.page_size - 1;
+    a.r16 = r16;
+    a.quad = quad;
+    a.koff = (uint32_t)(r16 * a.token_bytes + quad * 16);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + r16 * 16);
+
+    State st;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st.o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m = -INFINITY;
+    st.l = 0.f;
+    const float sc = scale * kLog2e;
+
+    // two tiles in registers: while one is computed the other's loads are in flight
+    Tile ta, tb;
+    load_tile<UNIFORM>(ta, a, c0, c1);
+    for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
+        const int32_t t1 = t0 + kTileKeys;
+        if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
+        compute_tile(st, ta, qf, sc, t0, c1, quad);
+        if (t1 >= c1) break;
+        if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
+        compute_tile(st, tb, qf, sc, t1, c1, quad);
+    }
+
+    float l = st.l;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (r16 >= G) return;
+    const float inv = 1.f / l;
+    const float lse_nat = (st.m + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
+    if (nsplit == 1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            uint4 w;
+            w.x = pack_bf16(st.o[0][r] * inv, st.o[1][r] * inv);
+            w.y = pack_bf16(st.o[2][r] * inv, st.o[3][r] * inv);
+            w.z = pack_bf16(st.o[4][r] * inv, st.o[5][r] * inv);
+            w.w = pack_bf16(st.o[6][r] * inv, st.o[7][r] * inv);
+            *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = w;
+        }
+        if (lse && quad == 0) lse[o_idx] = lse_nat;
+    } else {
+        float* po = part_o + (o_idx * nsplit + split) * kD + 32 * quad;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            *reinterpret_cast<float4*>(po + 8 * r) =
+                float4{st.o[0][r] * inv, st.o[1][r] * inv, st.o[2][r] * inv, st.o[3][r] * inv};
+            *reinterpret_cast<float4*>(po + 8 * r + 4) =
+                float4{st.o[4][r] * inv, st.o[5][r] * inv, st.o[6][r] * inv, st.o[7][r] * inv};
+        }
+        if (quad == 0) part_lse[o_idx * nsplit + split] = lse_nat;
+    }
+}
+
+template <int NW>
+void launch_nw(const AttnArgs& a, hipStream_t stream)
+{
+    const dim3 grid((uint32_t)a.plan.nsplit, (uint32_t)(a.cache.num_kv_heads / NW), (uint32_t)a.batch);
+    const bool uniform = a.cache.page_size >= 16;
+    auto kern = uniform ? paged_decode_mfma_kernel<NW, true> : paged_decode_mfma_kernel<NW, false>;
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                       a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.part_o, a.part_lse,
+                       a.plan.chunk, a.plan.nsplit);
+}
+
+}  // namespace
+
+bool decode_mfma_supported(const AttnArgs& a)
+{
+    if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
+    const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
+    if (G > 16) return false;
+    if (a.batch > 65535 || a.cache.num_kv_heads > 65535) return false;
+    // per-lane byte offsets inside a 16-key block are kept in 32 bits
+    if (a.cache.token_stride * 2 * 16 + a.cache.head_stride * 2 > 0x7fffffffLL) return false;
+    return true;
+}
+
+pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream)
+{
+    const int32_t hkv = a.cache.num_kv_heads;
+    ProfileScope prof("paged_decode_mfma_kernel", stream);
+    if (hkv % 8 == 0) launch_nw<8>(a, stream);
+    else if (hkv % 4 == 0) launch_nw<4>(a, stream);
+    else if (hkv % 2 == 0) launch_nw<2>(a, stream);
+    else launch_nw<1>(a, stream);
+    return launch_status();
+}
+
+}  // namespace pa
