@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV attention hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: paged_kv_append of the step's
+new tokens, then paged attention over the paged cache (split-KV kernel + LSE merge for decode).  The
+headline workload is the long-context decode (batch 16 x 131072 context, 64 query / 8 KV heads,
+head_dim 128, bf16, page size 16); --workload selects the others.  Inputs are resident in HBM before
+the timed region starts.  One JSON line is printed on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+WORKLOADS = {
+    # name: (config number, page size, context override)
+    "decode_b16_ctx131072_p16": (5, 16, None),
+    "decode_b16_ctx131072_p64": (5, 64, None),
+    "decode_mixed64_shared_prefix": (4, 16, None),
+    "decode_b8_ctx2048": (2, 16, 2048),
+    "decode_b8_ctx1024": (2, 16, 1024),
+    "decode_b8_ctx512": (2, 16, 512),
+    "decode_b8_ctx256": (2, 16, 256),
+    "decode_b8_ctx128": (2, 16, 128),
+    "decode_fp32_single": (1, 16, None),
+    "prefill_b4_s2048_causal": (3, 16, None),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="decode_b16_ctx131072_p16", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-oracle", action="store_true", help="skip the CPU-oracle baseline / parity leg")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the extra prefill measurement")
+    ap.add_argument("--oracle-seqs", type=int, default=4, help="sequences of the workload the oracle is timed on")
+    return ap.parse_args()
+
+
+def time_steps(torch, step, steps, warmup):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def run_oracle_sample(sub, out_gpu_rows):
+    """Time the CPU oracle (append + attention) on whole sequences of the workload (host copies taken
+    before the GPU path ran) and compare the GPU rows of those sequences with it."""
+    import oracle
+    from tests import parity
+    t0 = time.perf_counter()
+    _, _, ref, _ = parity.oracle_step(oracle, sub)
+    dt = time.perf_counter() - t0
+    max_abs, max_rel = parity.errors(parity.to_f64(out_gpu_rows), ref)
+    return dt, max_abs, max_rel, oracle.num_threads()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every box of this build has one, and the path has no multi-GPU part "
+              f"(--gpus {args.gpus} refused).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2506_07311_amd as pa
+    from paper_2506_07311_amd import binding, workloads as W
+
+    pa.load_library()
+    dev = "cuda:0"
+    cfg, P, ctx = WORKLOADS[args.workload]
+    w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
+    torch.cuda.synchronize()
+    is_prefill = cfg == 3
+    seqs = list(range(min(args.oracle_seqs, w.batch)))
+    sub = None if args.no_oracle else W.restrict(w, seqs, device="cpu")
+
+    ws = torch.empty(pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.total_q, w.max_seq_len),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty_like(w.q)
+
+    def step():
+        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+        if is_prefill:
+            pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table, w.seq_lens,
+                                       w.max_seq_len, w.scale, w.causal, out=out, workspace=ws)
+        else:
+            pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
+                                      out=out, workspace=ws)
+
+    # timed region: per-kernel HIP events (recorded by the library on the launch stream) stay on, so the
+    # dominant kernel's duration comes from the same K steps the step time does
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    sec = time_steps(torch, step, args.steps, 0)
+    binding.pa_profile_enable(False)
+    kernels = {}
+    for name in ("paged_kv_append_kernel", "paged_decode_mfma_kernel", "paged_attention_generic_kernel",
+                 "paged_attention_merge_kernel", "paged_prefill_mfma_kernel"):
+        n, ms = binding.pa_profile_read(name)
+        if n:
+            kernels[name] = {"launches": n, "avg_us": ms * 1e3 / n}
+    binding.pa_profile_reset()
+
+    us = sec * 1e6
+    kv_bytes = w.logical_kv_bytes()
+    tokens = w.total_q                      # tokens produced (decode) / processed (prefill) per step
+    result = {
+        "metric": "paged_prefill_us_per_step" if is_prefill else "paged_decode_us_per_step",
+        "value": round(us, 2), "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": w.batch, "context": w.max_seq_len,
+                   "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
+                   "page_size": w.page_size, "pool_pages": w.num_pages, "step": "append + attention (+ merge)"},
+        "tokens_per_s": round(tokens / sec, 1),
+        "kv_bytes_per_step": kv_bytes,
+        "step_hbm_gbps": round(kv_bytes / sec / 1e9, 1),
+        "step_hbm_frac": round(kv_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),
+        "kernels": kernels,
+    }
+    if is_prefill:
+        flops = sum(4 * w.num_q_heads * w.head_dim * (ql * (L - ql) + ql * (ql + 1) // 2 if w.causal else ql * L)
+                    for ql, L in zip(w.q_lens_host, w.seq_lens_host))
+        dom = kernels.get("paged_prefill_mfma_kernel") or kernels.get("paged_attention_generic_kernel")
+        ach = flops / (dom["avg_us"] * 1e-6) / 1e12
+        result["roofline"] = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                              "kernel": "paged_prefill_mfma_kernel" if "paged_prefill_mfma_kernel" in kernels
+                              else "paged_attention_generic_kernel", "useful_flops": flops}
+    else:
+        name = "paged_decode_mfma_kernel" if "paged_decode_mfma_kernel" in kernels else "paged_attention_generic_kernel"
+        ach = kv_bytes / (kernels[name]["avg_us"] * 1e-6) / 1e9
+        result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": name,
+                              "algorithmic_bytes": kv_bytes}
+
+    if not args.no_oracle:
+        cu = w.cu_q_lens.cpu().tolist()
+        rows = [r for s_ in seqs for r in range(cu[s_], cu[s_ + 1])]
+        dt, max_abs, max_rel, cores = run_oracle_sample(sub, out[rows])
+        scale_up = w.batch / len(seqs)
+        result["cpu_baseline"] = {"value": round(dt * scale_up * 1e6, 1), "unit": "us/step", "cores": cores,
+                                  "kind": "oracle",
+                                  "sample": f"{len(seqs)} of {w.batch} sequences (all heads, full context) in "
+                                            f"{dt:.2f} s, scaled x{scale_up:g}"}
+        result["parity_sample"] = {"max_abs": max_abs, "max_rel_rms_floored": max_rel, "sequences": seqs}
+
+    if not is_prefill and not args.no_prefill:
+        del w, ws, out
+        torch.cuda.empty_cache()
+        wp = W.config(3, device=dev, poison=False)
+        wsp = torch.empty(256, dtype=torch.uint8, device=dev)
+        outp = torch.empty_like(wp.q)
+
+        def pstep():
+            pa.paged_kv_append(wp.k_cache, wp.v_cache, wp.k_new, wp.v_new, wp.seq_ids, wp.positions, wp.block_table)
+            pa.paged_attention_prefill(wp.k_cache, wp.v_cache, wp.q, wp.cu_q_lens, wp.max_q_len, wp.block_table,
+                                       wp.seq_lens, wp.max_seq_len, wp.scale, wp.causal, out=outp, workspace=wsp)
+        for _ in range(2):
+            pstep()
+        torch.cuda.synchronize()
+        binding.pa_profile_reset()
+        binding.pa_profile_enable(True)
+        psec = time_steps(torch, pstep, max(3, args.steps // 2), 0)
+        binding.pa_profile_enable(False)
+        S = wp.max_seq_len
+        flops = 4 * wp.batch * wp.num_q_heads * wp.head_dim * S * (S + 1) // 2
+        pk = None
+        for name in ("paged_prefill_mfma_kernel", "paged_attention_generic_kernel"):
+            n, ms = binding.pa_profile_read(name)
+            if n:
+                pk = (name, ms * 1e3 / n)
+                break
+        binding.pa_profile_reset()
+        result["prefill"] = {"workload": "prefill_b4_s2048_causal", "us_per_step": round(psec * 1e6, 1),
+                             "tokens_per_s": round(wp.total_q / psec, 1), "kernel": pk[0],
+                             "kernel_avg_us": round(pk[1], 1), "useful_flops": flops,
+                             "mfma_tflops": round(flops / (pk[1] * 1e-6) / 1e12, 1),
+                             "mfma_frac": round(flops / (pk[1] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -156,13 +156,21 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
 #pragma unroll
         for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
     }
-    // probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4)
-    uint4 pb;
+    // Probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4).
+    // They are carried as TWO bf16 terms (p = hi + lo, lo = bf16(p - hi)): the matrix cores idle most of the
+    // time in this HBM-bound kernel, so the second product is free and removes the 2^-9 weight rounding that
+    // would otherwise dominate the error of short contexts.
+    uint4 pb, pl;
     pb.x = pack_bf16(s[0][0], s[0][1]);
     pb.y = pack_bf16(s[0][2], s[0][3]);
     pb.z = pack_bf16(s[1][0], s[1][1]);
     pb.w = pack_bf16(s[1][2], s[1][3]);
+    pl.x = pack_bf16(s[0][0] - __uint_as_float(pb.x << 16), s[0][1] - __uint_as_float(pb.x & 0xffff0000u));
+    pl.y = pack_bf16(s[0][2] - __uint_as_float(pb.y << 16), s[0][3] - __uint_as_float(pb.y & 0xffff0000u));
+    pl.z = pack_bf16(s[1][0] - __uint_as_float(pb.z << 16), s[1][1] - __uint_as_float(pb.z & 0xffff0000u));
+    pl.w = pack_bf16(s[1][2] - __uint_as_float(pb.w << 16), s[1][3] - __uint_as_float(pb.w & 0xffff0000u));
     const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
+    const bf16x8 pfrag_lo = __builtin_bit_cast(bf16x8, pl);
     // in-register 8x8 transpose of V, one head_dim column (j) at a time, feeding the A operand
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -173,6 +181,7 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
         a.z = __builtin_amdgcn_perm(word(t.v[5], j / 2), word(t.v[4], j / 2), sel);
         a.w = __builtin_amdgcn_perm(word(t.v[7], j / 2), word(t.v[6], j / 2), sel);
         st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pfrag, st.o[j], 0, 0, 0);
+        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pfrag_lo, st.o[j], 0, 0, 0);
     }
 }
 

@@ -198,6 +198,42 @@ def make_workload(name: str, *, seq_lens: List[int], q_lens: Optional[List[int]]
         seq_lens_host=list(map(int, seq_lens)), q_lens_host=list(map(int, q_lens)))
 
 
+def restrict(w: PagedWorkload, seqs: List[int], device: Optional[str] = None) -> PagedWorkload:
+    """The same workload cut down to the sequences ``seqs``: only the physical pages they map to are kept
+    (copied, re-numbered 0..n-1 in ascending page order, aliases preserved) together with their block-table
+    rows, lengths, queries and appended tokens.  Plain tensor indexing; used to hand the CPU oracle whole
+    sequences of a workload whose pool is too large to copy to the host."""
+    seqs = list(seqs)
+    idx = torch.tensor(seqs, dtype=torch.long, device=w.block_table.device)
+    bt = w.block_table[idx]
+    live = bt >= 0
+    pages = torch.unique(bt[live]).long()
+    remap = torch.full((w.num_pages,), -1, dtype=torch.int32, device=bt.device)
+    remap[pages] = torch.arange(pages.numel(), dtype=torch.int32, device=bt.device)
+    bt2 = torch.where(live, remap[bt.clamp(min=0).long()], bt)
+    cu = w.cu_q_lens.cpu().numpy()
+    rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in seqs] + [np.zeros(0, dtype=np.int64)]).astype(np.int64)
+    q_lens = [w.q_lens_host[s] for s in seqs]
+    cu2 = np.zeros(len(seqs) + 1, dtype=np.int32)
+    np.cumsum(np.asarray(q_lens, dtype=np.int64), out=cu2[1:])
+    ids = w.seq_ids.cpu().numpy()
+    sel = np.nonzero(np.isin(ids, seqs))[0]
+    order = {s: i for i, s in enumerate(seqs)}
+    new_ids = np.asarray([order[int(x)] for x in ids[sel]], dtype=np.int32)
+    dev = device or str(w.q.device)
+
+    def pick(t, index):
+        return t[torch.as_tensor(index, dtype=torch.long, device=t.device)].to(dev)
+
+    return PagedWorkload(
+        name=w.name + "_sub", dtype=w.dtype, page_size=w.page_size, num_pages=int(pages.numel()),
+        num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim, scale=w.scale, causal=w.causal,
+        k_cache=w.k_cache[pages].to(dev), v_cache=w.v_cache[pages].to(dev), block_table=bt2.to(dev),
+        seq_lens=w.seq_lens[idx].to(dev), q=pick(w.q, rows), cu_q_lens=torch.from_numpy(cu2).to(dev),
+        k_new=pick(w.k_new, sel), v_new=pick(w.v_new, sel), seq_ids=torch.from_numpy(new_ids).to(dev),
+        positions=pick(w.positions, sel), seq_lens_host=[w.seq_lens_host[s] for s in seqs], q_lens_host=q_lens)
+
+
 def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> List[int]:
     """n lengths with ln(len) uniform on [ln lo, ln hi], rounded to integers."""
     rng = np.random.default_rng(3000 + seed)

@@ -35,25 +35,15 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().double().cpu().numpy()
 
 
-def oracle_step(oracle, w: W.PagedWorkload, append=True, seqs=None):
-    """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse).
-    ``seqs`` restricts attention to a subset of sequences (rows of out follow that subset's queries)."""
+def oracle_step(oracle, w: W.PagedWorkload, append=True):
+    """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse)."""
     k, v = W.to_numpy(w.k_cache).copy(), W.to_numpy(w.v_cache).copy()
     bt = W.to_numpy(w.block_table)
     if append and w.seq_ids.numel():
         oracle.kv_append(k, v, W.to_numpy(w.k_new), W.to_numpy(w.v_new), W.to_numpy(w.seq_ids),
                          W.to_numpy(w.positions), bt)
-    lens = W.to_numpy(w.seq_lens)
-    cu = W.to_numpy(w.cu_q_lens)
-    q = W.to_numpy(w.q)
-    if seqs is not None:
-        seqs = list(seqs)
-        rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in seqs])
-        q = q[rows]
-        ql = [int(cu[s + 1] - cu[s]) for s in seqs]
-        cu = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
-        bt, lens = bt[seqs], lens[seqs]
-    out, lse = oracle.attention(k, v, q, bt, lens, w.scale, causal=w.causal, cu_q_lens=cu)
+    out, lse = oracle.attention(k, v, W.to_numpy(w.q), bt, W.to_numpy(w.seq_lens), w.scale, causal=w.causal,
+                                cu_q_lens=W.to_numpy(w.cu_q_lens))
     return k, v, out, lse
 
 
@@ -75,16 +65,21 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True):
     return out, lse
 
 
+def _bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a      # NaN-poisoned slots compare by bit pattern
+
+
 def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None):
-    """Full parity of one step: pools bit-exact after the append, attention within tolerance."""
+    """Full parity of one step: pools bit-exact after the append, attention within tolerance.
+    With ``seqs`` the oracle sees only those sequences (their pages copied out BEFORE the GPU path runs);
+    the GPU path always runs the whole workload."""
     # the oracle runs first, on host copies taken before the GPU path touches the pools
-    k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, w, seqs=seqs)
+    ref_w = w if seqs is None else W.restrict(w, seqs, device="cpu")
+    k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, ref_w)
     out, lse = gpu_step(pa, w, prefill=prefill)
-    # NaN-poisoned slots compare by bit pattern
-    def bits(a):
-        return a.view(np.uint32) if a.dtype == np.float32 else a
-    assert np.array_equal(bits(W.to_numpy(w.k_cache)), bits(k_ref)), f"{what}: K pool differs after append"
-    assert np.array_equal(bits(W.to_numpy(w.v_cache)), bits(v_ref)), f"{what}: V pool differs after append"
+    after = w if seqs is None else W.restrict(w, seqs, device="cpu")
+    assert np.array_equal(_bits(W.to_numpy(after.k_cache)), _bits(k_ref)), f"{what}: K pool differs after append"
+    assert np.array_equal(_bits(W.to_numpy(after.v_cache)), _bits(v_ref)), f"{what}: V pool differs after append"
     got, got_lse = to_f64(out), to_f64(lse)
     if seqs is not None:
         cu = W.to_numpy(w.cu_q_lens)

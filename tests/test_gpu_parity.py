@@ -214,3 +214,24 @@ def test_aliased_prefix_pages_equal_copied_pages_bitwise(pa):
                                          w.max_seq_len, w.scale)
     torch.cuda.synchronize()
     assert torch.equal(out_alias, out_copy)
+
+
+# ----------------------------------------------------------------------------- full benchmark sizes
+def test_config3_full_size_causal_prefill(pa, oracle):
+    """All 4 x 2048 queries of the benchmark prefill, every row against the oracle."""
+    parity.check_step(pa, oracle, W.config(3, device=DEV), "config 3 full")
+
+
+def test_config4_full_size_mixed_decode(pa, oracle):
+    """All 64 ragged sequences (lengths 64..32768, shared 1024-token prefixes), the launch bench.py times."""
+    parity.check_step(pa, oracle, W.config(4, device=DEV), "config 4 full", seqs=list(range(64)))
+
+
+@pytest.mark.parametrize("P", [16, 64])
+def test_config5_full_size_sampled_sequences(pa, oracle, P):
+    """Batch 16 x 131072 context in the launch configuration bench.py times; three whole sequences
+    (all 64 heads) are recomputed by the oracle, and every output of the batch must be finite."""
+    w = W.config(5, device=DEV, page_size=P)
+    parity.check_step(pa, oracle, w, f"config 5 full P={P}", seqs=[0, 7, 15])
+    del w
+    torch.cuda.empty_cache()
