@@ -34,6 +34,8 @@ WORKLOADS = {
     "decode_b8_ctx128": (2, 16, 128),
     "decode_fp32_single": (1, 16, None),
     "prefill_b4_s2048_causal": (3, 16, None),
+    # plain paged copy of known size (Algorithm 1 Gather over 16 x 65536 tokens): calibrates HBM byte counters
+    "gather_copy_calibration": (5, 16, 65536),
 }
 
 
@@ -72,6 +74,34 @@ def run_oracle_sample(sub, out_gpu_rows):
     return dt, max_abs, max_rel, oracle.num_threads()
 
 
+def run_gather_calibration(torch, pa, binding, w, args):
+    """Time paged_kv_gather, a pure copy: it reads and writes exactly sum(len) * 2*Hkv*d*E bytes."""
+    import numpy as np
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(w.seq_lens_host)]), dtype=torch.int32, device=w.q.device)
+    total = int(sum(w.seq_lens_host))
+
+    def step():
+        pa.paged_kv_gather(w.k_cache, w.v_cache, w.block_table, w.seq_lens, cu, total, w.max_seq_len)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    sec = time_steps(torch, step, args.steps, 0)
+    binding.pa_profile_enable(False)
+    n, ms = binding.pa_profile_read("paged_kv_gather_kernel")
+    nbytes = w.logical_kv_bytes()
+    ach = nbytes / (ms / n * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "paged_gather_us_per_step", "value": round(sec * 1e6, 2), "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": args.workload, "tokens": total, "bytes_read": nbytes, "bytes_written": nbytes},
+        "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "paged_kv_gather_kernel",
+                     "algorithmic_bytes": nbytes, "note": "achieved counts bytes read; as many are written"}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -88,6 +118,8 @@ def main():
     w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
     torch.cuda.synchronize()
     is_prefill = cfg == 3
+    if args.workload == "gather_copy_calibration":
+        return run_gather_calibration(torch, pa, binding, w, args)
     seqs = list(range(min(args.oracle_seqs, w.batch)))
     sub = None if args.no_oracle else W.restrict(w, seqs, device="cpu")
 
