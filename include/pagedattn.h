@@ -141,7 +141,9 @@ const char* pa_status_string(pa_status status);
 /*
  * Tuning knobs (host state, process-wide, not thread-safe against concurrent
  * launches).  name is one of
- *   "decode_chunk_tokens"  context tokens per split-KV workgroup (0 = heuristic)
+ *   "decode_chunk_tokens"  context tokens per split-KV workgroup of the portable kernel (0 = heuristic)
+ *   "decode_workgroups"    workgroups the MFMA decode kernel spreads the batch's key tiles over
+ *                          (0 = one per compute unit)
  *   "force_generic"        1 = always take the portable VALU kernels
  * Returns PA_ERR_INVALID_ARG for an unknown name or a value out of range.
  */

@@ -14,8 +14,23 @@ namespace {
 
 struct Options {
     int64_t decode_chunk_tokens = 0;
+    int64_t decode_workgroups = 0;
     int64_t force_generic = 0;
 } g_opt;
+
+// Compute units of the current device (the tile-stream decode launches one workgroup per CU by default).
+int32_t device_cus()
+{
+    static int32_t cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
 struct ProfileRecord {
     std::string kernel;
@@ -77,6 +92,27 @@ SplitPlan plan_decode(int32_t batch, int32_t max_seq_len, int32_t page_size)
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Workgroups along the tile stream for the MFMA decode kernel: one per compute unit (per KV-head group), but
+// never so many that a workgroup gets fewer than two 32-key tiles of the longest possible stream.
+int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups)
+{
+    int64_t target = g_opt.decode_workgroups > 0 ? g_opt.decode_workgroups : device_cus() / head_groups;
+    if (target < 1) target = 1;
+    const int64_t tiles = (int64_t)batch * ((max_seq_len + 31) / 32);
+    int64_t n = tiles / 2;
+    if (n > target) n = target;
+    if (n > kMaxDecodeWGs) n = kMaxDecodeWGs;
+    if (n < 1) n = 1;
+    return (int32_t)n;
+}
+
+size_t stream_workspace_bytes(int32_t batch, int32_t hq, int32_t d, int32_t wgs)
+{
+    const size_t parts = (size_t)wgs + batch;
+    return align256(parts * hq * d * sizeof(float)) + align256(parts * hq * sizeof(float)) +
+           2 * align256((size_t)batch * sizeof(int32_t));
+}
+
 size_t part_o_bytes(int64_t rows, int32_t hq, int32_t d, int32_t nsplit)
 {
     return align256((size_t)rows * hq * nsplit * d * sizeof(float));
@@ -129,13 +165,30 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.part_o = reinterpret_cast<float*>(workspace);
     a.part_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) +
                                           part_o_bytes(total_q, num_q_heads, cache->head_dim, a.plan.nsplit));
+    a.stream_split = 0;
+    a.num_wgs = 0;
+    a.seg_first = a.seg_last = nullptr;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     if (decode) {
-        if (!g_opt.force_generic && decode_mfma_supported(a))
+        if (!g_opt.force_generic && decode_mfma_supported(a)) {
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads);
+            a.stream_split = 1;
+            a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
+            const size_t parts = (size_t)a.num_wgs + batch;
+            char* p = reinterpret_cast<char*>(workspace);
+            a.part_o = reinterpret_cast<float*>(p);
+            p += align256(parts * num_q_heads * cache->head_dim * sizeof(float));
+            a.part_lse = reinterpret_cast<float*>(p);
+            p += align256(parts * num_q_heads * sizeof(float));
+            a.seg_first = reinterpret_cast<int32_t*>(p);
+            p += align256((size_t)batch * sizeof(int32_t));
+            a.seg_last = reinterpret_cast<int32_t*>(p);
             st = launch_decode_mfma(a, s);
-        else
-            st = launch_attention_generic(a, s);
+            if (st != PA_OK) return st;
+            return launch_merge(a, s);
+        }
+        st = launch_attention_generic(a, s);
         if (st != PA_OK) return st;
         if (a.plan.nsplit > 1) st = launch_merge(a, s);
         return st;
@@ -146,8 +199,6 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
 
 }  // namespace
 
-int64_t option_decode_chunk_tokens() { return g_opt.decode_chunk_tokens; }
-int64_t option_force_generic() { return g_opt.force_generic; }
 
 void profile_begin(const char* kernel, hipStream_t stream)
 {
@@ -210,7 +261,9 @@ size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32
     // Only the decode entry point splits the context; the prefill kernels write their outputs directly.
     if (total_q > batch) return 256;
     const int32_t ns = nsplit_bound(max_seq_len);
-    return part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
+    const size_t chunked = part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
+    const size_t stream = stream_workspace_bytes(batch, num_q_heads, head_dim, kMaxDecodeWGs);
+    return chunked > stream ? chunked : stream;
 }
 
 pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -250,6 +303,11 @@ pa_status pa_set_option(const char* name, int64_t value)
     if (!strcmp(name, "decode_chunk_tokens")) {
         if (value < 0 || value > (1 << 24)) return PA_ERR_INVALID_ARG;
         g_opt.decode_chunk_tokens = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "decode_workgroups")) {
+        if (value < 0 || value > kMaxDecodeWGs) return PA_ERR_INVALID_ARG;
+        g_opt.decode_workgroups = value;
         return PA_OK;
     }
     if (!strcmp(name, "force_generic")) {

@@ -50,7 +50,8 @@ struct SplitPlan {
 };
 
 constexpr int32_t kMinChunk = 256;     // smallest chunk the planner will pick
-constexpr int32_t kMaxSplits = 512;    // bound of nsplit used to size the workspace
+constexpr int32_t kMaxSplits = 64;     // bound of nsplit used to size the workspace
+constexpr int32_t kMaxDecodeWGs = 2048;  // bound of the tile-stream decode grid used to size the workspace
 
 // ---------------------------------------------------------------------------------------------
 // Launch bookkeeping: error capture and optional per-kernel event timing.
@@ -69,8 +70,6 @@ inline pa_status launch_status()
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;
 }
 
-int64_t option_decode_chunk_tokens();
-int64_t option_force_generic();
 
 // ---------------------------------------------------------------------------------------------
 // Kernel launchers (each defined in its own .hip file).  All take validated arguments.
@@ -101,13 +100,20 @@ struct AttnArgs {
     int32_t causal;
     float* part_o;           // workspace: partial outputs
     float* part_lse;         // workspace: partial LSEs
-    SplitPlan plan;
+    SplitPlan plan;          // chunked split (portable kernel)
+    // tile-stream split (MFMA decode kernel): partial (w + s) of workgroup w and sequence s; the workgroups
+    // holding a sequence's first / last tile are recorded in seg_first / seg_last (first = -1: no merge needed)
+    int32_t stream_split;    // 1 when the tile-stream layout is in use
+    int32_t num_wgs;
+    int32_t* seg_first;
+    int32_t* seg_last;
 };
 
 // Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.
 pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream);
 // MFMA decode kernel: bf16, head_dim 128, group size <= 16.
 bool decode_mfma_supported(const AttnArgs& a);
+int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads);
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
 // MFMA prefill kernel: bf16, head_dim 128.
 bool prefill_mfma_supported(const AttnArgs& a);

@@ -185,50 +185,85 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Work distribution.  The context of the whole batch is one stream of 32-key tiles (sequence after sequence,
+// ceil(len/32) tiles each); workgroup w of the nwg launched owns the contiguous tile range
+// [w*T/nwg, (w+1)*T/nwg).  Every workgroup therefore streams the same number of bytes whatever the length
+// mix is, and a sequence is cut only where a workgroup boundary falls inside it.  Each (workgroup, sequence)
+// intersection is one softmax partial; partial id = w + s is unique because w and s only grow along the
+// stream.  The workgroup that holds a sequence's first / last tile records itself in seg_first / seg_last for
+// the merge kernel; a sequence that lies inside one workgroup is written to `out` directly (seg_first = -1).
+// ---------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int32_t tiles_of(int32_t len) { return (len + kTileKeys - 1) / kTileKeys; }
+
+// Sum of tiles over the batch; every lane returns the same value.
+__device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_lens, int32_t batch, int lane)
+{
+    int32_t n = 0;
+    for (int32_t i = lane; i < batch; i += 64) n += tiles_of(seq_lens[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+    return n;
+}
+
+// Sequence that holds global tile g (0 <= g < total) and the number of tiles before that sequence.
+__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens, int32_t batch, int32_t g, int lane,
+                                            int32_t& seq, int32_t& tiles_before)
+{
+    int32_t base = 0;
+    seq = batch;
+    tiles_before = 0;
+    for (int32_t blk = 0; blk < batch; blk += 64) {
+        const int32_t idx = blk + lane;
+        const int32_t n = idx < batch ? tiles_of(seq_lens[idx]) : 0;
+        int32_t inc = n;                                   // inclusive scan over the 64 lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += t;
+        }
+        const int32_t blk_total = __shfl(inc, 63, 64);
+        if (g < base + blk_total) {
+            const uint64_t hit = __ballot(base + inc > g);
+            const int first = __ffsll((unsigned long long)hit) - 1;
+            seq = blk + first;
+            tiles_before = base + __shfl(inc, first, 64) - __shfl(n, first, 64);
+            return;
+        }
+        base += blk_total;
+    }
+}
+
 template <int NW, bool UNIFORM>
 __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
-    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t num_q_heads,
-    int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk,
-    int32_t nsplit)
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch,
+    int32_t num_q_heads, int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse,
+    int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int32_t split = blockIdx.x;
+    const int32_t w = blockIdx.x;
     const int32_t kvh = blockIdx.y * NW + wave;
-    const int32_t s = blockIdx.z;
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t r16 = lane & 15, quad = lane >> 4;
-    const int32_t len = seq_lens[s];
-    const int32_t c0 = split * chunk;
-    const int32_t c1 = min(len, c0 + chunk);
-    const int32_t h = kvh * G + r16;                       // this lane's query head (valid if r16 < G)
-    const int64_t o_idx = (int64_t)s * num_q_heads + h;
+    const float sc = scale * kLog2e;
 
-    if (c0 >= c1) {
-        if (nsplit == 1 && r16 < G) {                      // empty sequence: out = 0, lse = -inf
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = uint4{0, 0, 0, 0};
-            if (lse && quad == 0) lse[o_idx] = -INFINITY;
-        }
-        return;
-    }
-
-    // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
-    // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
-    bf16x8 qf[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        uint4 v = uint4{0, 0, 0, 0};
-        if (r16 < G) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
-        qf[ks] = __builtin_bit_cast(bf16x8, v);
-    }
+    // Only min(nwg, total) workgroups take part, so that every participating one holds at least one tile
+    // and the partials of a sequence belong to consecutive workgroups with none missing.
+    const int32_t total = total_tiles(seq_lens, batch, lane);
+    const int32_t nwg = min((int32_t)gridDim.x, total);
+    if (w >= nwg) return;
+    int32_t g = (int32_t)(((int64_t)w * total) / nwg);
+    const int32_t g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
+    int32_t s, before;
+    locate_tile(seq_lens, batch, g, lane, s, before);
+    s = __builtin_amdgcn_readfirstlane(s);
+    before = __builtin_amdgcn_readfirstlane(before);
 
     Addr a;
     a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
     a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
-    a.table = block_table + (int64_t)s * max_blocks;
     a.page_bytes = cache.page_stride * 2;
     a.token_bytes = cache.token_stride * 2;
     a.log2_page = cache.log2_page;
@@ -239,87 +274,127 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + r16 * 16);
 
-    State st;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) st.o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    st.m = -INFINITY;
-    st.l = 0.f;
-    const float sc = scale * kLog2e;
+    while (g < g_end) {
+        // segment: tiles [t_begin, t_end) of sequence s
+        const int32_t len = seq_lens[s];
+        const int32_t nt = tiles_of(len);
+        if (nt == 0) { ++s; continue; }                    // empty sequences hold no tiles
+        const int32_t t_begin = g - before;
+        const int32_t t_end = min(nt, g_end - before);
+        const int32_t c0 = t_begin * kTileKeys;
+        const int32_t c1 = min(len, t_end * kTileKeys);
+        const int32_t h = kvh * G + r16;                   // this lane's query head (valid if r16 < G)
+        const int64_t o_idx = (int64_t)s * num_q_heads + h;
+        a.table = block_table + (int64_t)s * max_blocks;
 
-    // two tiles in registers: while one is computed the other's loads are in flight
-    Tile ta, tb;
-    load_tile<UNIFORM>(ta, a, c0, c1);
-    for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
-        const int32_t t1 = t0 + kTileKeys;
-        if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
-        compute_tile(st, ta, qf, sc, t0, c1, quad);
-        if (t1 >= c1) break;
-        if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
-        compute_tile(st, tb, qf, sc, t1, c1, quad);
-    }
+        // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
+        // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
+        bf16x8 qf[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 v = uint4{0, 0, 0, 0};
+            if (r16 < G) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
+            qf[ks] = __builtin_bit_cast(bf16x8, v);
+        }
+        State st;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.m = -INFINITY;
+        st.l = 0.f;
 
-    float l = st.l;
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    if (r16 >= G) return;
-    const float inv = 1.f / l;
-    const float lse_nat = (st.m + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
-    if (nsplit == 1) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            uint4 w;
-            w.x = pack_bf16(st.o[0][r] * inv, st.o[1][r] * inv);
-            w.y = pack_bf16(st.o[2][r] * inv, st.o[3][r] * inv);
-            w.z = pack_bf16(st.o[4][r] * inv, st.o[5][r] * inv);
-            w.w = pack_bf16(st.o[6][r] * inv, st.o[7][r] * inv);
-            *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = w;
+        // two tiles in registers: while one is computed the other's loads are in flight
+        Tile ta, tb;
+        load_tile<UNIFORM>(ta, a, c0, c1);
+        for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
+            const int32_t t1 = t0 + kTileKeys;
+            if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
+            compute_tile(st, ta, qf, sc, t0, c1, quad);
+            if (t1 >= c1) break;
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
+            compute_tile(st, tb, qf, sc, t1, c1, quad);
         }
-        if (lse && quad == 0) lse[o_idx] = lse_nat;
-    } else {
-        float* po = part_o + (o_idx * nsplit + split) * kD + 32 * quad;
+
+        float l = st.l;
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const bool whole = t_begin == 0 && t_end == nt;    // the sequence lies inside this workgroup
+        if (r16 < G) {
+            const float inv = 1.f / l;
+            const float lse_nat = (st.m + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
+            if (whole) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            *reinterpret_cast<float4*>(po + 8 * r) =
-                float4{st.o[0][r] * inv, st.o[1][r] * inv, st.o[2][r] * inv, st.o[3][r] * inv};
-            *reinterpret_cast<float4*>(po + 8 * r + 4) =
-                float4{st.o[4][r] * inv, st.o[5][r] * inv, st.o[6][r] * inv, st.o[7][r] * inv};
+                for (int r = 0; r < 4; ++r) {
+                    uint4 wv;
+                    wv.x = pack_bf16(st.o[0][r] * inv, st.o[1][r] * inv);
+                    wv.y = pack_bf16(st.o[2][r] * inv, st.o[3][r] * inv);
+                    wv.z = pack_bf16(st.o[4][r] * inv, st.o[5][r] * inv);
+                    wv.w = pack_bf16(st.o[6][r] * inv, st.o[7][r] * inv);
+                    *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = wv;
+                }
+                if (lse && quad == 0) lse[o_idx] = lse_nat;
+            } else {
+                const int64_t p_idx = (int64_t)(w + s) * num_q_heads + h;
+                float* po = part_o + p_idx * kD + 32 * quad;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    *reinterpret_cast<float4*>(po + 8 * r) =
+                        float4{st.o[0][r] * inv, st.o[1][r] * inv, st.o[2][r] * inv, st.o[3][r] * inv};
+                    *reinterpret_cast<float4*>(po + 8 * r + 4) =
+                        float4{st.o[4][r] * inv, st.o[5][r] * inv, st.o[6][r] * inv, st.o[7][r] * inv};
+                }
+                if (quad == 0) part_lse[p_idx] = lse_nat;
+            }
         }
-        if (quad == 0) part_lse[o_idx * nsplit + split] = lse_nat;
+        if (wave == 0 && lane == 0 && blockIdx.y == 0) {
+            if (t_begin == 0) seg_first[s] = whole ? -1 : w;
+            if (t_end == nt) seg_last[s] = w;
+        }
+        g = before + t_end;
+        before += nt;
+        ++s;
     }
 }
 
 template <int NW>
 void launch_nw(const AttnArgs& a, hipStream_t stream)
 {
-    const dim3 grid((uint32_t)a.plan.nsplit, (uint32_t)(a.cache.num_kv_heads / NW), (uint32_t)a.batch);
+    const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), 1);
     const bool uniform = a.cache.page_size >= 16;
     auto kern = uniform ? paged_decode_mfma_kernel<NW, true> : paged_decode_mfma_kernel<NW, false>;
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
-                       a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.part_o, a.part_lse,
-                       a.plan.chunk, a.plan.nsplit);
+                       a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.part_o,
+                       a.part_lse, a.seg_first, a.seg_last);
 }
 
 }  // namespace
+
+int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads)
+{
+    return num_kv_heads % 8 == 0 ? 8 : num_kv_heads % 4 == 0 ? 4 : num_kv_heads % 2 == 0 ? 2 : 1;
+}
 
 bool decode_mfma_supported(const AttnArgs& a)
 {
     if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
     if (G > 16) return false;
-    if (a.batch > 65535 || a.cache.num_kv_heads > 65535) return false;
+    if (a.cache.num_kv_heads > 65535 * 8) return false;
     // per-lane byte offsets inside a 16-key block are kept in 32 bits
     if (a.cache.token_stride * 2 * 16 + a.cache.head_stride * 2 > 0x7fffffffLL) return false;
+    // tile counts are kept in 32 bits
+    if ((int64_t)a.batch * ((a.max_seq_len + kTileKeys - 1) / kTileKeys) > 0x7fffffffLL) return false;
     return true;
 }
 
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream)
 {
-    const int32_t hkv = a.cache.num_kv_heads;
     ProfileScope prof("paged_decode_mfma_kernel", stream);
-    if (hkv % 8 == 0) launch_nw<8>(a, stream);
-    else if (hkv % 4 == 0) launch_nw<4>(a, stream);
-    else if (hkv % 2 == 0) launch_nw<2>(a, stream);
-    else launch_nw<1>(a, stream);
+    switch (decode_mfma_heads_per_wg(a.cache.num_kv_heads)) {
+        case 8: launch_nw<8>(a, stream); break;
+        case 4: launch_nw<4>(a, stream); break;
+        case 2: launch_nw<2>(a, stream); break;
+        default: launch_nw<1>(a, stream); break;
+    }
     return launch_status();
 }
 

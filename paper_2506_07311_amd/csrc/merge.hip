@@ -40,6 +40,44 @@ __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
     if (lse && e == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
 }
 
+// Tile-stream layout: sequence s was cut by the workgroups seg_first[s] .. seg_last[s]; workgroup w left its
+// partial at index (w + s).  seg_first[s] < 0 means one workgroup held the whole sequence and wrote the final
+// result itself.
+template <bool BF16>
+__global__ __launch_bounds__(256) void paged_attention_merge_stream_kernel(
+    const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
+    float* __restrict__ lse, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ seg_first,
+    const int32_t* __restrict__ seg_last, int32_t num_q_heads, int32_t d)
+{
+    const int32_t s = blockIdx.x / num_q_heads;
+    const int32_t h = blockIdx.x % num_q_heads;
+    const int64_t o_idx = blockIdx.x;
+    const int e = threadIdx.x;
+    int32_t n = 0, first = 0;
+    if (seq_lens[s] > 0) {
+        first = seg_first[s];
+        if (first < 0) return;                      // already final
+        n = seg_last[s] - first + 1;
+    }
+    const int64_t p0 = (int64_t)(first + s) * num_q_heads + h;     // partial c sits num_q_heads rows further each
+    float M = -INFINITY;
+    for (int32_t c = 0; c < n; ++c) M = fmaxf(M, part_lse[p0 + (int64_t)c * num_q_heads]);
+    float wsum = 0.f, acc = 0.f;
+    for (int32_t c = 0; c < n; ++c) {
+        const float w = expf(part_lse[p0 + (int64_t)c * num_q_heads] - M);
+        wsum += w;
+        if (e < d) acc = fmaf(w, part_o[(p0 + (int64_t)c * num_q_heads) * d + e], acc);
+    }
+    const float r = n > 0 ? acc / wsum : 0.f;
+    if (e < d) {
+        if (BF16)
+            reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
+        else
+            reinterpret_cast<float*>(out)[o_idx * d + e] = r;
+    }
+    if (lse && e == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
+}
+
 }  // namespace
 
 pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
@@ -48,6 +86,17 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     const int threads = ((a.cache.head_dim + 63) / 64) * 64;
     ProfileScope prof("paged_attention_merge_kernel", stream);
+    if (a.stream_split) {
+        if (a.dtype == PA_DTYPE_BF16)
+            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<true>, dim3((uint32_t)blocks), dim3(threads), 0,
+                               stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
+                               a.num_q_heads, a.cache.head_dim);
+        else
+            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<false>, dim3((uint32_t)blocks), dim3(threads), 0,
+                               stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
+                               a.num_q_heads, a.cache.head_dim);
+        return launch_status();
+    }
     if (a.dtype == PA_DTYPE_BF16)
         hipLaunchKernelGGL(paged_attention_merge_kernel<true>, dim3((uint32_t)blocks), dim3(threads), 0, stream,
                            a.part_o, a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads,

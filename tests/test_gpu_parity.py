@@ -120,17 +120,42 @@ def test_decode_group_sizes(pa, oracle, Hq, Hkv):
     parity.check_step(pa, oracle, w, f"decode Hq={Hq} Hkv={Hkv}")
 
 
-@pytest.mark.parametrize("chunk", [32, 64, 256, 4096])
-def test_decode_split_schedules(pa, oracle, chunk):
-    """Every split schedule merges to the same answer (the LSE merge is exact)."""
+@pytest.mark.parametrize("wgs", [1, 3, 7, 64, 256, 1000])
+def test_decode_split_schedules(pa, oracle, wgs):
+    """Every cut of the batch's key-tile stream merges to the same answer (the LSE merge is exact): one
+    workgroup takes everything, boundaries inside and between sequences, more workgroups than tiles."""
     from paper_2506_07311_amd import binding
-    w = W.make_workload("t", seq_lens=[2049, 64, 31, 1000, 4096], num_q_heads=32, num_kv_heads=8, head_dim=128,
-                        page_size=16, dtype=torch.bfloat16, seed=32, device=DEV)
-    binding.pa_set_option("decode_chunk_tokens", chunk)
+    w = W.make_workload("t", seq_lens=[2049, 64, 0, 31, 1000, 4096, 1], num_q_heads=32, num_kv_heads=8,
+                        head_dim=128, page_size=16, dtype=torch.bfloat16, seed=32, device=DEV)
+    binding.pa_set_option("decode_workgroups", wgs)
     try:
-        parity.check_step(pa, oracle, w, f"decode chunk={chunk}")
+        parity.check_step(pa, oracle, w, f"decode workgroups={wgs}")
+    finally:
+        binding.pa_set_option("decode_workgroups", 0)
+
+
+@pytest.mark.parametrize("chunk", [32, 256, 4096])
+def test_portable_decode_chunk_schedules(pa, oracle, chunk):
+    """The portable kernel's fixed-size chunk split, forced on a shape the MFMA kernel would take."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[2049, 64, 0, 31, 1000], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, seed=33, device=DEV)
+    binding.pa_set_option("decode_chunk_tokens", chunk)
+    binding.pa_set_option("force_generic", 1)
+    try:
+        parity.check_step(pa, oracle, w, f"portable decode chunk={chunk}")
     finally:
         binding.pa_set_option("decode_chunk_tokens", 0)
+        binding.pa_set_option("force_generic", 0)
+
+
+def test_many_sequences_decode(pa, oracle):
+    """More sequences than lanes in a wave: the tile-stream schedule scans the lengths in blocks of 64."""
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(0, 200, size=300)]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=8, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=34, device=DEV)
+    parity.check_step(pa, oracle, w, "300 sequences")
 
 
 @pytest.mark.parametrize("dtype,d,P", [(torch.bfloat16, 128, 16), (torch.float32, 64, 16), (torch.bfloat16, 128, 64),
