@@ -5,16 +5,21 @@
 // consecutive queries of one (sequence, query head); wave w owns 32 of them.  The context is walked in
 // tiles of 64 keys.  A tile's K and V rows are fetched page by page through the block table (Algorithm 1:
 // page = block_table[s][j >> log2 P], slot = j & (P-1)) with coalesced 16-byte loads into registers one
-// tile ahead, then staged in LDS:
-//   K   row-major [64 keys][128] (+16 B row padding: conflict-free 16-byte MFMA operand reads)
-//   V^T [128 columns][64 keys]   (in-lane 4x8 transpose with byte permutes before the LDS write, keys stored
-//                                 in the order the P operand needs them so that one 16-byte read is an operand)
+// tile ahead (their page ids two tiles ahead), then stored row-major in LDS:
+//   K [64 keys][128] rows padded to 272 B: the 16-byte operand reads of 8 consecutive lanes hit 32 banks
+//   V [64 keys][128] rows padded to 288 B: read back TRANSPOSED with ds_read_b64_tr_b16, the LDS transpose
+//     load of gfx950 -- the contraction index of P.V is the key while memory is contiguous along head_dim
 // Both products are computed transposed so that every per-query quantity is lane-local (lane%32 = query):
 //   S^T[key, q]  = K[key, :] . Q[q, :]^T        A = K from LDS, B = Q held in registers for the whole kernel
 //   O^T[col, q] += V^T[col, key] . P^T[key, q]  A = V^T from LDS, B = P straight from the S^T accumulators
 // The accumulator layout of S^T (lane holds keys 8a + 4h + b of its query) is, after packing to bf16, already
-// the B-operand layout of the second product for a permuted key order; V^T is stored in that same order.
-// Online softmax runs in the log2 domain; masking (length, causal, ragged rows) is by selection.
+// the B-operand layout of the second product for a permuted key order, and the transpose loads fetch V in that
+// same order.  Online softmax runs in the log2 domain; masking (length, causal, ragged rows) is by selection.
+//
+// Softmax weights enter the matrix cores as bf16.  With few keys the individual weights are large and their
+// 2^-9 rounding shows in the output, so query tiles whose context is at most kPreciseKeys keys carry the weights
+// as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.  The two cases are two
+// instantiations launched back to back; each workgroup exits at once if its tile belongs to the other one.
 #include "common.h"
 
 namespace pa {
@@ -23,6 +28,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
@@ -30,9 +36,9 @@ constexpr int kD = 128;
 constexpr int kBM = 128;              // queries per workgroup
 constexpr int kBN = 64;               // keys per tile
 constexpr int kThreads = 256;
-constexpr int kPreciseKeys = 512;      // contexts up to this length use two-term bf16 weights
+constexpr int kPreciseKeys = 512;     // contexts up to this length use two-term bf16 weights
 constexpr int kKRow = 256 + 16;       // bytes per K row in LDS
-constexpr int kVRow = 128 + 16;       // bytes per V^T row in LDS
+constexpr int kVRow = 256 + 32;       // bytes per V row in LDS
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -42,71 +48,193 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-__device__ __forceinline__ uint32_t word(const uint4 v, int w)
-{
-    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
-}
-
-struct Stage {
-    uint4 k0, k1, k2, k3;   // K rows (tid/16) + 16*i, 16-byte piece tid%16
-    uint4 v0, v1, v2, v3;   // V rows 4*(tid/16) + i, 16-byte piece tid%16
+// ---------------------------------------------------------------------------------------------------
+// Staging: thread (c = tid%16, g = tid/16) moves the 16-byte piece c of K rows and V rows g + 16*i, i < 4.
+// ---------------------------------------------------------------------------------------------------
+struct PageIds {   // page of key g + 16*i (K and V rows of a thread share their keys)
+    int32_t p0, p1, p2, p3;
 };
 
-// One 16-byte piece of the row of `key` (clamped to a live slot) of a pool: Algorithm 1's translation.
-__device__ __forceinline__ uint4 load_row_piece(const char* base, const CacheView& cache, const int32_t* table,
-                                                int32_t key, int32_t last_key)
+__device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, const int32_t* table, int32_t key,
+                                         int32_t last_key)
 {
-    key = min(key, last_key);
-    const int64_t page = table[key >> cache.log2_page];
-    const int32_t slot = key & (cache.page_size - 1);
-    return *reinterpret_cast<const uint4*>(base + (page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2);
+    p.p0 = table[min(key, last_key) >> cache.log2_page];
+    p.p1 = table[min(key + 16, last_key) >> cache.log2_page];
+    p.p2 = table[min(key + 32, last_key) >> cache.log2_page];
+    p.p3 = table[min(key + 48, last_key) >> cache.log2_page];
 }
 
-__device__ __forceinline__ void load_stage(Stage& st, const CacheView& cache, const int32_t* table, int32_t kvh,
-                                           int32_t t0, int32_t last_key, int tid)
+// Byte offset of the row of `key` (clamped to a live slot) in page `page`.
+__device__ __forceinline__ int64_t row_offset(const CacheView& cache, int32_t page, int32_t key, int32_t last_key)
 {
-    const int c = tid & 15, g = tid >> 4;
-    const int64_t head_off = (int64_t)kvh * cache.head_stride * 2 + c * 16;
-    const char* kb = reinterpret_cast<const char*>(cache.k) + head_off;
-    const char* vb = reinterpret_cast<const char*>(cache.v) + head_off;
-    st.k0 = load_row_piece(kb, cache, table, t0 + g, last_key);
-    st.k1 = load_row_piece(kb, cache, table, t0 + g + 16, last_key);
-    st.k2 = load_row_piece(kb, cache, table, t0 + g + 32, last_key);
-    st.k3 = load_row_piece(kb, cache, table, t0 + g + 48, last_key);
-    st.v0 = load_row_piece(vb, cache, table, t0 + 4 * g + 0, last_key);
-    st.v1 = load_row_piece(vb, cache, table, t0 + 4 * g + 1, last_key);
-    st.v2 = load_row_piece(vb, cache, table, t0 + 4 * g + 2, last_key);
-    st.v3 = load_row_piece(vb, cache, table, t0 + 4 * g + 3, last_key);
+    const int32_t slot = min(key, last_key) & (cache.page_size - 1);
+    return ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2;
 }
 
-__device__ __forceinline__ void store_stage(const Stage& st, char* k_s, char* v_s, int tid)
+__device__ __forceinline__ void load_stage(uint4& k0, uint4& k1, uint4& k2, uint4& k3, uint4& v0, uint4& v1, uint4& v2,
+                                           uint4& v3, const PageIds& p, const CacheView& cache, const char* kb,
+                                           const char* vb, int32_t key, int32_t last_key)
 {
-    const int c = tid & 15, g = tid >> 4;
-    *reinterpret_cast<uint4*>(k_s + (g + 0) * kKRow + c * 16) = st.k0;
-    *reinterpret_cast<uint4*>(k_s + (g + 16) * kKRow + c * 16) = st.k1;
-    *reinterpret_cast<uint4*>(k_s + (g + 32) * kKRow + c * 16) = st.k2;
-    *reinterpret_cast<uint4*>(k_s + (g + 48) * kKRow + c * 16) = st.k3;
-    // keys 4g .. 4g+3 of the tile: 16-key group ks = g/4, u = g%4; the second product reads, per 16-key group,
-    // lane half h, element e <-> key 8*(e/4) + 4*h + e%4, so key 4u + b sits at slot 8*(u%2) + 4*(u/2) + b
-    const int ks = g >> 2, u = g & 3;
-    const int col_byte = (16 * ks + 8 * (u & 1) + 4 * (u >> 1)) * 2;
+    const int64_t o0 = row_offset(cache, p.p0, key, last_key);
+    const int64_t o1 = row_offset(cache, p.p1, key + 16, last_key);
+    const int64_t o2 = row_offset(cache, p.p2, key + 32, last_key);
+    const int64_t o3 = row_offset(cache, p.p3, key + 48, last_key);
+    k0 = *reinterpret_cast<const uint4*>(kb + o0);
+    k1 = *reinterpret_cast<const uint4*>(kb + o1);
+    k2 = *reinterpret_cast<const uint4*>(kb + o2);
+    k3 = *reinterpret_cast<const uint4*>(kb + o3);
+    v0 = *reinterpret_cast<const uint4*>(vb + o0);
+    v1 = *reinterpret_cast<const uint4*>(vb + o1);
+    v2 = *reinterpret_cast<const uint4*>(vb + o2);
+    v3 = *reinterpret_cast<const uint4*>(vb + o3);
+}
+
+__device__ __forceinline__ void store_stage(const uint4 k0, const uint4 k1, const uint4 k2, const uint4 k3, const uint4 v0,
+                                            const uint4 v1, const uint4 v2, const uint4 v3, char* kw, char* vw)
+{
+    *reinterpret_cast<uint4*>(kw) = k0;
+    *reinterpret_cast<uint4*>(kw + 16 * kKRow) = k1;
+    *reinterpret_cast<uint4*>(kw + 32 * kKRow) = k2;
+    *reinterpret_cast<uint4*>(kw + 48 * kKRow) = k3;
+    *reinterpret_cast<uint4*>(vw) = v0;
+    *reinterpret_cast<uint4*>(vw + 16 * kVRow) = v1;
+    *reinterpret_cast<uint4*>(vw + 32 * kVRow) = v2;
+    *reinterpret_cast<uint4*>(vw + 48 * kVRow) = v3;
+}
+
+__device__ __forceinline__ bf16x8 lds_frag(const char* p)
+{
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+}
+
+// V^T operand of the second product for 32 head_dim columns and one 16-key step, from row-major V.
+// ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block receives element i%4 of the 8 bytes
+// addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.  Lane x = q + 4*j of a block therefore points at
+// key j of the step, columns 4q..4q+3 of the block's 16 columns, and lane i ends up with column i of 4 keys.
+// `vp` already holds this lane's part of the address; two loads fetch the keys of contraction slots 0-3 and 4-7.
+struct tr_pair {
+    s16x4 lo, hi;
+};
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* vp)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    tr_pair r;
+    r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
+    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kVRow));
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// One 64-key tile for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
+//   kp = k_s + (lane%32) * kKRow + 16 * (lane/32)         this lane's K operand row / 8-element piece
+//   vp = v_s + (4*(lane/32) + (lane%16)/4) * kVRow + 2 * (16*((lane/16)%2) + 4*(lane%4))   transpose-load address
+//   key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's query may see (MASK only)
+// sc = scale * log2(e) > 0.  LDS operand reads are issued a few matrix instructions ahead of their use.
+template <bool PRECISE, bool MASK>
+__device__ __forceinline__ void attend_tile(const char* kp, const char* vp, const bf16x8 (&qf)[8], f32x16 (&o)[4],
+                                            float& m, float& l, float sc, int32_t key0, int32_t nk)
+{
+    f32x16 s0, s1;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-        uint2 w;
-        w.x = __builtin_amdgcn_perm(word(st.v1, j / 2), word(st.v0, j / 2), sel);
-        w.y = __builtin_amdgcn_perm(word(st.v3, j / 2), word(st.v2, j / 2), sel);
-        *reinterpret_cast<uint2*>(v_s + (8 * c + j) * kVRow + col_byte) = w;
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    bf16x8 ka[4], kb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ka[i] = lds_frag(kp + 32 * i);
+        kb[i] = lds_frag(kp + 32 * kKRow + 32 * i);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[i], qf[i], s1, 0, 0, 0);
+        ka[i] = lds_frag(kp + 32 * (i + 4));
+        kb[i] = lds_frag(kp + 32 * kKRow + 32 * (i + 4));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i + 4], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[i], qf[i + 4], s1, 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // 8 LDS reads
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);    // 2 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // 2 LDS reads
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    // the first V^T operands land while the softmax runs
+    bf16x8 va[4], vb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vp + 64 * t);
+
+    // s0[r] / s1[r]: key (tile) + 32*mt + 8*(r/4) + 4*(lane/32) + r%4, query lane%32
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (MASK) {
+            if (key0 + 8 * (r / 4) + (r % 4) >= nk) s0[r] = -INFINITY;
+            if (key0 + 32 + 8 * (r / 4) + (r % 4) >= nk) s1[r] = -INFINITY;
+        }
+        tmax = fmaxf(tmax, fmaxf(s0[r], s1[r]));
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m, tmax * sc);                  // sc > 0: scaling commutes with the max
+    const float m_use = (MASK && m_new == -INFINITY) ? 0.f : m_new;   // a query with no allowed key so far
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        s0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], sc, -m_use));
+        s1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], sc, -m_use));
+        psum += s0[r] + s1[r];
+    }
+    m = m_new;
+    l = l * alpha + psum;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] *= alpha;
+    }
+    // P^T as B operand of step ks (16 keys): elements e = 0..7 <-> accumulator registers 8*(ks%2) + e of tile ks/2
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const f32x16& sx = (ks < 2) ? s0 : s1;
+        const int r0 = 8 * (ks & 1);
+        uint4 w, wl;
+        w.x = pack_bf16(sx[r0 + 0], sx[r0 + 1]);
+        w.y = pack_bf16(sx[r0 + 2], sx[r0 + 3]);
+        w.z = pack_bf16(sx[r0 + 4], sx[r0 + 5]);
+        w.w = pack_bf16(sx[r0 + 6], sx[r0 + 7]);
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, w);
+        if (PRECISE) {   // second bf16 term of the weights: p = hi + lo, lo = bf16(p - hi)
+            wl.x = pack_bf16(sx[r0 + 0] - __uint_as_float(w.x << 16), sx[r0 + 1] - __uint_as_float(w.x & 0xffff0000u));
+            wl.y = pack_bf16(sx[r0 + 2] - __uint_as_float(w.y << 16), sx[r0 + 3] - __uint_as_float(w.y & 0xffff0000u));
+            wl.z = pack_bf16(sx[r0 + 4] - __uint_as_float(w.z << 16), sx[r0 + 5] - __uint_as_float(w.z & 0xffff0000u));
+            wl.w = pack_bf16(sx[r0 + 6] - __uint_as_float(w.w << 16), sx[r0 + 7] - __uint_as_float(w.w & 0xffff0000u));
+        } else {
+            wl = w;
+        }
+        const bf16x8 pl = __builtin_bit_cast(bf16x8, wl);
+        bf16x8 (&cur)[4] = (ks & 1) ? vb : va;
+        bf16x8 (&nxt)[4] = (ks & 1) ? va : vb;
+        if (ks + 1 < 4) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) nxt[t] = lds_frag_tr(vp + 64 * t + 16 * (ks + 1) * kVRow);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pf, o[t], 0, 0, 0);
+            if (PRECISE) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pl, o[t], 0, 0, 0);
+        }
     }
 }
 
+template <bool PRECISE>
 __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
 {
     __shared__ __attribute__((aligned(16))) char k_s[kBN * kKRow];
-    __shared__ __attribute__((aligned(16))) char v_s[kD * kVRow];
+    __shared__ __attribute__((aligned(16))) char v_s[kBN * kVRow];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -119,6 +247,13 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     const int32_t m0 = tile * kBM;
     if (m0 >= q_len) return;
     const int32_t len = seq_lens[s];
+    // workgroup-wide key range; it also selects which instantiation handles this query tile
+    const int32_t q_last = min(m0 + kBM, q_len) - 1;
+    int32_t nk_wg = len;
+    if (causal) nk_wg = min(len, len - q_len + q_last + 1);
+    nk_wg = max(nk_wg, 0);
+    if ((nk_wg <= kPreciseKeys) != PRECISE) return;
+
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t kvh = h / G;
     const int32_t* table = block_table + (int64_t)s * max_blocks;
@@ -130,17 +265,15 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     int32_t nk = len;                                        // keys 0 .. nk-1 are allowed
     if (causal) nk = min(len, len - q_len + qi_c + 1);
     nk = max(nk, 0);
-    // workgroup-wide key range
-    const int32_t q_last = min(m0 + kBM, q_len) - 1;
-    int32_t nk_wg = len;
-    if (causal) nk_wg = min(len, len - q_len + q_last + 1);
-    nk_wg = max(nk_wg, 0);
-    // per wave: the largest bound of its 32 queries decides which tiles it can skip
-    int32_t nk_wave = len;
-    if (causal) nk_wave = min(len, len - q_len + min(m0 + 32 * wave + 31, q_len - 1) + 1);
+    // per wave: the largest bound of its 32 queries decides which tiles it can skip, the smallest which
+    // tiles need no mask
+    int32_t nk_wave = len, nk_wave_min = len;
+    if (causal) {
+        nk_wave = min(len, len - q_len + min(m0 + 32 * wave + 31, q_len - 1) + 1);
+        nk_wave_min = min(len, len - q_len + min(m0 + 32 * wave, q_len - 1) + 1);
+    }
     nk_wave = max(nk_wave, 0);
-    int32_t nk_wave_min = len;                               // smallest bound: tiles below it need no mask
-    if (causal) nk_wave_min = max(0, min(len, len - q_len + min(m0 + 32 * wave, q_len - 1) + 1));
+    nk_wave_min = max(nk_wave_min, 0);
 
     const int64_t row = (int64_t)(q_begin + qi_c) * num_q_heads + h;
     // Q as B operand: lane%32 = query, step ks covers head_dim elements 16*ks + 8*hh .. +7
@@ -156,92 +289,38 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
         for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
     float m = -INFINITY, l = 0.f;
     const float sc = scale * kLog2e;
-    // Short contexts carry the softmax weights as two bf16 terms: with few keys the individual weights are
-    // large and their 2^-9 rounding would show in the output; over long contexts it averages out.
-    const bool precise = nk_wg <= kPreciseKeys;              // workgroup-uniform
 
-    Stage st;
-    if (nk_wg > 0) load_stage(st, cache, table, kvh, 0, len - 1, tid);
+    const char* kp = k_s + ql * kKRow + 16 * hh;
+    const char* vp = v_s + (4 * hh + ((lane & 15) >> 2)) * kVRow + 2 * (16 * ((lane >> 4) & 1) + 4 * (lane & 3));
+    // staging role of this thread: 16-byte piece sc16 of rows sg + 16*i
+    const int sc16 = tid & 15, sg = tid >> 4;
+    const int64_t head_off = (int64_t)kvh * cache.head_stride * 2 + sc16 * 16;
+    const char* kb = reinterpret_cast<const char*>(cache.k) + head_off;
+    const char* vb = reinterpret_cast<const char*>(cache.v) + head_off;
+    char* kw = k_s + sg * kKRow + sc16 * 16;
+    char* vw = v_s + sg * kVRow + sc16 * 16;
+    const int32_t last_key = len - 1;
+
+    uint4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
+    PageIds ids;
+    if (nk_wg > 0) {
+        load_ids(ids, cache, table, sg, last_key);
+        load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, sg, last_key);
+        if (kBN < nk_wg) load_ids(ids, cache, table, kBN + sg, last_key);
+    }
     for (int32_t t0 = 0; t0 < nk_wg; t0 += kBN) {
         __syncthreads();                                     // previous tile's LDS reads are done
-        store_stage(st, k_s, v_s, tid);
+        store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw, vw);
         __syncthreads();
-        if (t0 + kBN < nk_wg) load_stage(st, cache, table, kvh, t0 + kBN, len - 1, tid);
+        if (t0 + kBN < nk_wg) {                              // rows of the next tile, page ids of the one after
+            load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, t0 + kBN + sg, last_key);
+            if (t0 + 2 * kBN < nk_wg) load_ids(ids, cache, table, t0 + 2 * kBN + sg, last_key);
+        }
         if (t0 >= nk_wave) continue;                         // wave-uniform: nothing for this wave here
-
-        // S^T tiles: keys 32*mt .. +31 of the tile against this wave's 32 queries
-        f32x16 sacc[2];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4*>(k_s + (32 * mt + ql) * kKRow + 32 * ks + 16 * hh));
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[mt], 0, 0, 0);
-            }
-        }
-        // sacc[mt][r]: key t0 + 32*mt + 8*(r/4) + 4*hh + r%4, query lane%32
-        const bool need_mask = t0 + kBN > nk_wave_min;       // wave-uniform
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float x = sacc[mt][r] * sc;
-                if (need_mask && t0 + 32 * mt + 8 * (r / 4) + 4 * hh + (r % 4) >= nk) x = -INFINITY;
-                sacc[mt][r] = x;
-                tmax = fmaxf(tmax, x);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(m, tmax);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a query with no allowed key so far
-        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-        float psum = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(sacc[mt][r] - m_use);
-                sacc[mt][r] = p;
-                psum += p;
-            }
-        m = m_new;
-        l = l * alpha + psum;
-        if (__any(alpha != 1.f)) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) o[t] *= alpha;
-        }
-        // P^T as B operand of step ks (16 keys): elements e = 0..7 <-> accumulator registers 8*(ks%2) + e of tile ks/2
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int mt = ks >> 1, r0 = 8 * (ks & 1);
-            uint4 w, wl;
-            w.x = pack_bf16(sacc[mt][r0 + 0], sacc[mt][r0 + 1]);
-            w.y = pack_bf16(sacc[mt][r0 + 2], sacc[mt][r0 + 3]);
-            w.z = pack_bf16(sacc[mt][r0 + 4], sacc[mt][r0 + 5]);
-            w.w = pack_bf16(sacc[mt][r0 + 6], sacc[mt][r0 + 7]);
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, w);
-            if (precise) {   // second bf16 term of the weights: p = hi + lo, lo = bf16(p - hi)
-                wl.x = pack_bf16(sacc[mt][r0 + 0] - __uint_as_float(w.x << 16),
-                                 sacc[mt][r0 + 1] - __uint_as_float(w.x & 0xffff0000u));
-                wl.y = pack_bf16(sacc[mt][r0 + 2] - __uint_as_float(w.y << 16),
-                                 sacc[mt][r0 + 3] - __uint_as_float(w.y & 0xffff0000u));
-                wl.z = pack_bf16(sacc[mt][r0 + 4] - __uint_as_float(w.z << 16),
-                                 sacc[mt][r0 + 5] - __uint_as_float(w.z & 0xffff0000u));
-                wl.w = pack_bf16(sacc[mt][r0 + 6] - __uint_as_float(w.w << 16),
-                                 sacc[mt][r0 + 7] - __uint_as_float(w.w & 0xffff0000u));
-            }
-            const bf16x8 pl = __builtin_bit_cast(bf16x8, wl);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4*>(v_s + (32 * t + ql) * kVRow + 32 * ks + 16 * hh));
-                o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[t], 0, 0, 0);
-                if (precise) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, o[t], 0, 0, 0);
-            }
-        }
+        if (t0 + kBN > nk_wave_min)                          // wave-uniform: some score of this tile is masked
+            attend_tile<PRECISE, true>(kp, vp, qf, o, m, l, sc, t0 + 4 * hh, nk);
+        else
+            attend_tile<PRECISE, false>(kp, vp, qf, o, m, l, sc, t0 + 4 * hh, nk);
     }
 
     l += __shfl_xor(l, 32, 64);
@@ -267,6 +346,7 @@ bool prefill_mfma_supported(const AttnArgs& a)
 {
     if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
     if (a.batch > 65535 || a.num_q_heads > 65535) return false;
+    if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
     return true;
 }
 
@@ -276,9 +356,12 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     if (tiles <= 0) return PA_OK;
     const dim3 grid((uint32_t)tiles, (uint32_t)a.num_q_heads, (uint32_t)a.batch);
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q,
-                       (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks,
-                       a.scale, a.causal);
+    hipLaunchKernelGGL(paged_prefill_mfma_kernel<false>, grid, dim3(kThreads), 0, stream, a.cache,
+                       (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
+                       a.num_q_heads, a.max_blocks, a.scale, a.causal);
+    hipLaunchKernelGGL(paged_prefill_mfma_kernel<true>, grid, dim3(kThreads), 0, stream, a.cache,
+                       (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
+                       a.num_q_heads, a.max_blocks, a.scale, a.causal);
     return launch_status();
 }
 
