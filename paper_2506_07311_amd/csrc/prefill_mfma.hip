@@ -36,9 +36,10 @@ constexpr int kD = 128;
 constexpr int kBM = 128;              // queries per workgroup
 constexpr int kBN = 64;               // keys per tile
 constexpr int kThreads = 256;
-constexpr int kPreciseKeys = 512;     // contexts up to this length use two-term bf16 weights
+constexpr int kPreciseKeys = 256;     // contexts up to this length use two-term bf16 weights
 constexpr int kKRow = 256 + 16;       // bytes per K row in LDS
 constexpr int kVRow = 256 + 32;       // bytes per V row in LDS
+constexpr int kBufBytes = kBN * (kKRow + kVRow);   // one tile buffer: K rows, then V rows
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -233,8 +234,11 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
 {
-    __shared__ __attribute__((aligned(16))) char k_s[kBN * kKRow];
-    __shared__ __attribute__((aligned(16))) char v_s[kBN * kVRow];
+    // two tile buffers (K rows then V rows each): while one is read by the matrix cores the next tile is
+    // written into the other, so one barrier per tile suffices
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const k_s = smem;
+    char* const v_s = smem + kBN * kKRow;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -303,24 +307,37 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
 
     uint4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
     PageIds ids;
-    if (nk_wg > 0) {
+    const int32_t n_tiles = (nk_wg + kBN - 1) / kBN;
+    if (n_tiles > 0) {
         load_ids(ids, cache, table, sg, last_key);
         load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, sg, last_key);
-        if (kBN < nk_wg) load_ids(ids, cache, table, kBN + sg, last_key);
-    }
-    for (int32_t t0 = 0; t0 < nk_wg; t0 += kBN) {
-        __syncthreads();                                     // previous tile's LDS reads are done
+        if (n_tiles > 1) load_ids(ids, cache, table, kBN + sg, last_key);
         store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw, vw);
-        __syncthreads();
-        if (t0 + kBN < nk_wg) {                              // rows of the next tile, page ids of the one after
-            load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, t0 + kBN + sg, last_key);
-            if (t0 + 2 * kBN < nk_wg) load_ids(ids, cache, table, t0 + 2 * kBN + sg, last_key);
+        if (n_tiles > 1) {
+            load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, kBN + sg, last_key);
+            if (n_tiles > 2) load_ids(ids, cache, table, 2 * kBN + sg, last_key);
         }
-        if (t0 >= nk_wave) continue;                         // wave-uniform: nothing for this wave here
-        if (t0 + kBN > nk_wave_min)                          // wave-uniform: some score of this tile is masked
-            attend_tile<PRECISE, true>(kp, vp, qf, o, m, l, sc, t0 + 4 * hh, nk);
-        else
-            attend_tile<PRECISE, false>(kp, vp, qf, o, m, l, sc, t0 + 4 * hh, nk);
+        __syncthreads();
+    }
+    for (int32_t t = 0; t < n_tiles; ++t) {
+        const int32_t t0 = t * kBN;
+        const int32_t cur = (t & 1) * kBufBytes, nxt = kBufBytes - cur;
+        if (t0 < nk_wave) {                                  // wave-uniform: else nothing for this wave here
+            if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
+                attend_tile<PRECISE, true>(kp + cur, vp + cur, qf, o, m, l, sc, t0 + 4 * hh, nk);
+            else
+                attend_tile<PRECISE, false>(kp + cur, vp + cur, qf, o, m, l, sc, t0 + 4 * hh, nk);
+        }
+        if (t + 1 < n_tiles) {
+            // tile t+1 (in registers since the previous iteration) goes into the buffer every wave finished
+            // reading before the last barrier; then the rows of tile t+2 and the page ids of tile t+3 are requested
+            store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw + nxt, vw + nxt);
+            if (t + 2 < n_tiles) {
+                load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, t0 + 2 * kBN + sg, last_key);
+                if (t + 3 < n_tiles) load_ids(ids, cache, table, t0 + 3 * kBN + sg, last_key);
+            }
+        }
+        __syncthreads();
     }
 
     l += __shfl_xor(l, 32, 64);
@@ -355,11 +372,19 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     const int32_t tiles = (a.max_q_len + kBM - 1) / kBM;
     if (tiles <= 0) return PA_OK;
     const dim3 grid((uint32_t)tiles, (uint32_t)a.num_q_heads, (uint32_t)a.batch);
+    constexpr int kSmem = 2 * kBufBytes;   // above the 64 KiB default: raised once per process
+    static const bool raised = [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess;
+    }();
+    if (!raised) return PA_ERR_HIP;
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel<false>, grid, dim3(kThreads), 0, stream, a.cache,
+    hipLaunchKernelGGL(paged_prefill_mfma_kernel<false>, grid, dim3(kThreads), kSmem, stream, a.cache,
                        (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
                        a.num_q_heads, a.max_blocks, a.scale, a.causal);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel<true>, grid, dim3(kThreads), 0, stream, a.cache,
+    hipLaunchKernelGGL(paged_prefill_mfma_kernel<true>, grid, dim3(kThreads), kSmem, stream, a.cache,
                        (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
                        a.num_q_heads, a.max_blocks, a.scale, a.causal);
     return launch_status();
