@@ -18,8 +18,7 @@
 //
 // Softmax weights enter the matrix cores as bf16.  With few keys the individual weights are large and their
 // 2^-9 rounding shows in the output, so query tiles whose context is at most kPreciseKeys keys carry the weights
-// as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.  The two cases are two
-// instantiations launched back to back; each workgroup exits at once if its tile belongs to the other one.
+// as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
 #include "common.h"
 
 namespace pa {
@@ -229,8 +228,8 @@ __device__ __forceinline__ void attend_tile(const char* kp, const char* vp, cons
 }
 
 template <bool PRECISE>
-__global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
-    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+__device__ __forceinline__ void prefill_body(
+    const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
 {
@@ -256,7 +255,7 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     int32_t nk_wg = len;
     if (causal) nk_wg = min(len, len - q_len + q_last + 1);
     nk_wg = max(nk_wg, 0);
-    if ((nk_wg <= kPreciseKeys) != PRECISE) return;
+    if ((nk_wg <= kPreciseKeys) != PRECISE) return;         // the other instantiation handles this tile
 
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t kvh = h / G;
@@ -357,6 +356,17 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     if (lse && hh == 0) lse[row] = l > 0.f ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
 }
 
+// Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
+// workgroup runs exactly one of them, decided by its context length.
+__global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
+    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
+{
+    prefill_body<false>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, num_q_heads, max_blocks, scale, causal);
+    prefill_body<true>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, num_q_heads, max_blocks, scale, causal);
+}
+
 }  // namespace
 
 bool prefill_mfma_supported(const AttnArgs& a)
@@ -374,19 +384,14 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     const dim3 grid((uint32_t)tiles, (uint32_t)a.num_q_heads, (uint32_t)a.batch);
     constexpr int kSmem = 2 * kBufBytes;   // above the 64 KiB default: raised once per process
     static const bool raised = [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess &&
-               hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<true>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess;
     }();
     if (!raised) return PA_ERR_HIP;
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel<false>, grid, dim3(kThreads), kSmem, stream, a.cache,
-                       (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
-                       a.num_q_heads, a.max_blocks, a.scale, a.causal);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel<true>, grid, dim3(kThreads), kSmem, stream, a.cache,
-                       (const uint16_t*)a.q, (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens,
-                       a.num_q_heads, a.max_blocks, a.scale, a.causal);
+    hipLaunchKernelGGL(paged_prefill_mfma_kernel, grid, dim3(kThreads), kSmem, stream, a.cache, (const uint16_t*)a.q,
+                       (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks,
+                       a.scale, a.causal);
     return launch_status();
 }
 
