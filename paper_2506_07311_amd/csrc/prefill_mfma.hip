@@ -231,7 +231,8 @@ template <bool PRECISE>
 __device__ __forceinline__ void prefill_body(
     const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
+    float scale, int32_t causal)
 {
     // two tile buffers (K rows then V rows each): while one is read by the matrix cores the next tile is
     // written into the other, so one barrier per tile suffices
@@ -242,11 +243,15 @@ __device__ __forceinline__ void prefill_body(
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int ql = lane & 31, hh = lane >> 5;
-    const int32_t s = blockIdx.z;
-    const int32_t h = blockIdx.y;
+    // Workgroups are dispatched in blockIdx.x order: the query-tile index is the slowest-varying part and runs
+    // backwards, so the whole grid is handed out heaviest (latest causal tiles) first.
+    const int32_t hb = num_q_heads * batch;
+    const int32_t tile = num_tiles - 1 - (int32_t)(blockIdx.x / hb);
+    const int32_t rest = blockIdx.x % hb;
+    const int32_t s = rest / num_q_heads;
+    const int32_t h = rest % num_q_heads;
     const int32_t q_begin = cu_q_lens[s];
     const int32_t q_len = cu_q_lens[s + 1] - q_begin;
-    const int32_t tile = gridDim.x - 1 - blockIdx.x;        // heaviest (latest) query tiles are dispatched first
     const int32_t m0 = tile * kBM;
     if (m0 >= q_len) return;
     const int32_t len = seq_lens[s];
@@ -361,10 +366,13 @@ __device__ __forceinline__ void prefill_body(
 __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, int32_t num_q_heads, int32_t max_blocks, float scale, int32_t causal)
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
+    float scale, int32_t causal)
 {
-    prefill_body<false>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, num_q_heads, max_blocks, scale, causal);
-    prefill_body<true>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, num_q_heads, max_blocks, scale, causal);
+    prefill_body<false>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+                        scale, causal);
+    prefill_body<true>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+                       scale, causal);
 }
 
 }  // namespace
@@ -372,7 +380,6 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
 bool prefill_mfma_supported(const AttnArgs& a)
 {
     if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
-    if (a.batch > 65535 || a.num_q_heads > 65535) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
     return true;
 }
@@ -381,7 +388,9 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
 {
     const int32_t tiles = (a.max_q_len + kBM - 1) / kBM;
     if (tiles <= 0) return PA_OK;
-    const dim3 grid((uint32_t)tiles, (uint32_t)a.num_q_heads, (uint32_t)a.batch);
+    const int64_t blocks = (int64_t)tiles * a.num_q_heads * a.batch;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    const dim3 grid((uint32_t)blocks, 1, 1);
     constexpr int kSmem = 2 * kBufBytes;   // above the 64 KiB default: raised once per process
     static const bool raised = [] {
         return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel),
@@ -390,8 +399,8 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     if (!raised) return PA_ERR_HIP;
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
     hipLaunchKernelGGL(paged_prefill_mfma_kernel, grid, dim3(kThreads), kSmem, stream, a.cache, (const uint16_t*)a.q,
-                       (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks,
-                       a.scale, a.causal);
+                       (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch, tiles, a.num_q_heads,
+                       a.max_blocks, a.scale, a.causal);
     return launch_status();
 }
 
