@@ -124,107 +124,153 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* vp)
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// One 64-key tile for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
-//   kp = k_s + (lane%32) * kKRow + 16 * (lane/32)         this lane's K operand row / 8-element piece
-//   vp = v_s + (4*(lane/32) + (lane%16)/4) * kVRow + 2 * (16*((lane/16)%2) + 4*(lane%4))   transpose-load address
-//   key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's query may see (MASK only)
-// sc = scale * log2(e) > 0.  LDS operand reads are issued a few matrix instructions ahead of their use.
-template <bool PRECISE, bool MASK>
-__device__ __forceinline__ void attend_tile(const char* kp, const char* vp, const bf16x8 (&qf)[8], f32x16 (&o)[4],
-                                            float& m, float& l, float sc, int32_t key0, int32_t nk)
+// max over the two lanes that share a query (lane and lane ^ 32) without an LDS round trip
+__device__ __forceinline__ float pair_max(float x)
 {
-    f32x16 s0, s1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-    bf16x8 ka[4], kb[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        ka[i] = lds_frag(kp + 32 * i);
-        kb[i] = lds_frag(kp + 32 * kKRow + 32 * i);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[i], qf[i], s1, 0, 0, 0);
-        ka[i] = lds_frag(kp + 32 * (i + 4));
-        kb[i] = lds_frag(kp + 32 * kKRow + 32 * (i + 4));
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i + 4], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[i], qf[i + 4], s1, 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // 8 LDS reads
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);    // 2 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);    // 2 LDS reads
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-    // the first V^T operands land while the softmax runs
-    bf16x8 va[4], vb[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vp + 64 * t);
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
-    // s0[r] / s1[r]: key (tile) + 32*mt + 8*(r/4) + 4*(lane/32) + r%4, query lane%32
+// Online-softmax update with the 32 keys of one half tile.  s holds raw scores on entry; the weights are
+// returned in p.  The running statistic is a REFERENCE exponent m_ref (log2 domain) that may trail the true
+// running max by up to kJump: weights are exp2(score - m_ref) <= 2^kJump, which fp32 sums and bf16 operands
+// carry without loss, and out = O / l does not depend on the reference.  The weights therefore do not wait for
+// the max of the half: they are computed speculatively with the reference as it stands, and only when some
+// query's max jumps more than kJump above its reference (always on its first keys, rarely later) is the
+// reference raised, O and l rescaled and the half's weights recomputed -- a wave-uniform slow path that keeps
+// the common path free of branches between the score and the value products.
+constexpr float kJump = 8.f;
+
+template <bool MASK, bool FIRST>
+__device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4], float& m_ref, float& l, float sc,
+                                             int32_t key0, int32_t nk)
+{
     float tmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        if (MASK) {
-            if (key0 + 8 * (r / 4) + (r % 4) >= nk) s0[r] = -INFINITY;
-            if (key0 + 32 + 8 * (r / 4) + (r % 4) >= nk) s1[r] = -INFINITY;
-        }
-        tmax = fmaxf(tmax, fmaxf(s0[r], s1[r]));
+        if (MASK && key0 + 8 * (r / 4) + (r % 4) >= nk) s[r] = -INFINITY;   // mask by selection
+        tmax = fmaxf(tmax, s[r]);
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m, tmax * sc);                  // sc > 0: scaling commutes with the max
-    const float m_use = (MASK && m_new == -INFINITY) ? 0.f : m_new;   // a query with no allowed key so far
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
     float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        s0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], sc, -m_use));
-        s1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], sc, -m_use));
-        psum += s0[r] + s1[r];
+        p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, -m_ref));
+        psum += p[r];
     }
-    m = m_new;
-    l = l * alpha + psum;
-    if (__any(alpha != 1.f)) {
+    // keep the speculative weights ahead of the branch below (they are dead on its slow path, and the
+    // optimiser would otherwise sink them behind the test, back onto the critical path)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(p[r]));
+    if (FIRST) {
+        // instruction order for the region that holds both score products and this half's softmax: the second
+        // half's 8 matrix instructions are issued with the vector work of the first half's softmax in between
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
+        }
+    }
+    const float top = pair_max(tmax) * sc;                    // sc > 0: scaling commutes with the max
+    const bool jump = !(top - m_ref <= kJump);                // also true for the NaN / inf of a fresh reference
+    if (__any(jump)) {
+        const float m_new = fmaxf(m_ref, top);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new; // a query with no allowed key so far
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);
 #pragma unroll
         for (int t = 0; t < 4; ++t) o[t] *= alpha;
-    }
-    // P^T as B operand of step ks (16 keys): elements e = 0..7 <-> accumulator registers 8*(ks%2) + e of tile ks/2
+        l *= alpha;
+        m_ref = m_new;
+        psum = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const f32x16& sx = (ks < 2) ? s0 : s1;
-        const int r0 = 8 * (ks & 1);
+        for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, -m_use));
+            psum += p[r];
+        }
+    }
+    l += psum;
+}
+
+// O^T += V^T P^T for the 32 keys of one half tile (two 16-key steps).  vh = this lane's transpose-load address
+// for the first step of the half.  P^T as B operand of a step: elements e = 0..7 <-> weights 8*step + e.
+template <bool PRECISE>
+__device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const char* vh)
+{
+    bf16x8 va[4], vb[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vh + 64 * t);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) vb[t] = lds_frag_tr(vh + 64 * t + 16 * kVRow);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        const int r0 = 8 * st;
         uint4 w, wl;
-        w.x = pack_bf16(sx[r0 + 0], sx[r0 + 1]);
-        w.y = pack_bf16(sx[r0 + 2], sx[r0 + 3]);
-        w.z = pack_bf16(sx[r0 + 4], sx[r0 + 5]);
-        w.w = pack_bf16(sx[r0 + 6], sx[r0 + 7]);
+        w.x = pack_bf16(s[r0 + 0], s[r0 + 1]);
+        w.y = pack_bf16(s[r0 + 2], s[r0 + 3]);
+        w.z = pack_bf16(s[r0 + 4], s[r0 + 5]);
+        w.w = pack_bf16(s[r0 + 6], s[r0 + 7]);
         const bf16x8 pf = __builtin_bit_cast(bf16x8, w);
         if (PRECISE) {   // second bf16 term of the weights: p = hi + lo, lo = bf16(p - hi)
-            wl.x = pack_bf16(sx[r0 + 0] - __uint_as_float(w.x << 16), sx[r0 + 1] - __uint_as_float(w.x & 0xffff0000u));
-            wl.y = pack_bf16(sx[r0 + 2] - __uint_as_float(w.y << 16), sx[r0 + 3] - __uint_as_float(w.y & 0xffff0000u));
-            wl.z = pack_bf16(sx[r0 + 4] - __uint_as_float(w.z << 16), sx[r0 + 5] - __uint_as_float(w.z & 0xffff0000u));
-            wl.w = pack_bf16(sx[r0 + 6] - __uint_as_float(w.w << 16), sx[r0 + 7] - __uint_as_float(w.w & 0xffff0000u));
+            wl.x = pack_bf16(s[r0 + 0] - __uint_as_float(w.x << 16), s[r0 + 1] - __uint_as_float(w.x & 0xffff0000u));
+            wl.y = pack_bf16(s[r0 + 2] - __uint_as_float(w.y << 16), s[r0 + 3] - __uint_as_float(w.y & 0xffff0000u));
+            wl.z = pack_bf16(s[r0 + 4] - __uint_as_float(w.z << 16), s[r0 + 5] - __uint_as_float(w.z & 0xffff0000u));
+            wl.w = pack_bf16(s[r0 + 6] - __uint_as_float(w.w << 16), s[r0 + 7] - __uint_as_float(w.w & 0xffff0000u));
         } else {
             wl = w;
         }
         const bf16x8 pl = __builtin_bit_cast(bf16x8, wl);
-        bf16x8 (&cur)[4] = (ks & 1) ? vb : va;
-        bf16x8 (&nxt)[4] = (ks & 1) ? va : vb;
-        if (ks + 1 < 4) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) nxt[t] = lds_frag_tr(vp + 64 * t + 16 * (ks + 1) * kVRow);
-        }
+        const bf16x8 (&cur)[4] = st ? vb : va;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pf, o[t], 0, 0, 0);
             if (PRECISE) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pl, o[t], 0, 0, 0);
         }
     }
+}
+
+// S^T of one half tile (32 keys) against the wave's 32 queries: 8 chained matrix instructions, the K operand
+// reads kept four ahead.  kh = this lane's K operand address for the half.
+__device__ __forceinline__ void half_scores(f32x16& s, const char* kh, const bf16x8 (&qf)[8])
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    bf16x8 ka[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ka[i] = lds_frag(kh + 32 * i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s, 0, 0, 0);
+        ka[i] = lds_frag(kh + 32 * (i + 4));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i + 4], s, 0, 0, 0);
+}
+
+// One 64-key tile for one wave, processed as two half tiles of 32 keys so that, within the wave, the softmax of
+// one half (vector ALU) runs under the matrix instructions of the other half:
+//     matrix cores:  S(h0)   S(h1)          PV(h0)          PV(h1)
+//     vector ALU:            softmax(h0)    softmax(h1)
+//   kp = k_s + (lane%32) * kKRow + 16 * (lane/32)         this lane's K operand row / 8-element piece
+//   vp = v_s + (4*(lane/32) + (lane%16)/4) * kVRow + 2 * (16*((lane/16)%2) + 4*(lane%4))   transpose-load address
+//   key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's query may see (MASK only)
+// sc = scale * log2(e) > 0.
+template <bool PRECISE, bool MASK>
+__device__ __forceinline__ void attend_tile(const char* kp, const char* vp, const bf16x8 (&qf)[8], f32x16 (&o)[4],
+                                            float& m, float& l, float sc, int32_t key0, int32_t nk)
+{
+    f32x16 s0, s1, p;
+    half_scores(s0, kp, qf);
+    half_scores(s1, kp + 32 * kKRow, qf);
+    half_softmax<MASK, true>(p, s0, o, m, l, sc, key0, nk);
+    half_pv<PRECISE>(o, p, vp);
+    half_softmax<MASK, false>(p, s1, o, m, l, sc, key0 + 32, nk);
+    half_pv<PRECISE>(o, p, vp + 32 * kVRow);
 }
 
 template <bool PRECISE>
