@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU-oracle baseline / parity leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the extra prefill measurement")
     ap.add_argument("--oracle-seqs", type=int, default=4, help="sequences of the workload the oracle is timed on")
+    ap.add_argument("--launch", choices=["direct", "graph"], default="direct",
+                    help="graph: capture one step (append + attention + merge) in a HIP graph and replay it; for the "
+                         "small workloads, whose step is shorter than the host's launch overhead")
     return ap.parse_args()
 
 
@@ -142,10 +145,26 @@ def main():
         step()
     torch.cuda.synchronize()
     binding.pa_profile_reset()
-    binding.pa_profile_enable(True)
-    sec = time_steps(torch, step, args.steps, 0)
-    binding.pa_profile_enable(False)
     kernels = {}
+    if args.launch == "graph":
+        # per-kernel events cannot be recorded inside a captured graph: time them in K direct steps first,
+        # then time the step itself as K replays of the captured graph
+        binding.pa_profile_enable(True)
+        time_steps(torch, step, args.steps, 0)
+        binding.pa_profile_enable(False)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        sec = time_steps(torch, graph.replay, args.steps, 2)
+    else:
+        binding.pa_profile_enable(True)
+        sec = time_steps(torch, step, args.steps, 0)
+        binding.pa_profile_enable(False)
     for name in ("paged_kv_append_kernel", "paged_decode_mfma_kernel", "paged_attention_generic_kernel",
                  "paged_attention_merge_kernel", "paged_prefill_mfma_kernel"):
         n, ms = binding.pa_profile_read(name)
@@ -163,7 +182,8 @@ def main():
         "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": w.batch, "context": w.max_seq_len,
                    "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
-                   "page_size": w.page_size, "pool_pages": w.num_pages, "step": "append + attention (+ merge)"},
+                   "page_size": w.page_size, "pool_pages": w.num_pages, "step": "append + attention (+ merge)",
+                   "launch": args.launch},
         "tokens_per_s": round(tokens / sec, 1),
         "kv_bytes_per_step": kv_bytes,
         "step_hbm_gbps": round(kv_bytes / sec / 1e9, 1),

@@ -251,13 +251,32 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 
     // Only min(nwg, total) workgroups take part, so that every participating one holds at least one tile
     // and the partials of a sequence belong to consecutive workgroups with none missing.
-    const int32_t total = total_tiles(seq_lens, batch, lane);
-    const int32_t nwg = min((int32_t)gridDim.x, total);
-    if (w >= nwg) return;
-    int32_t g = (int32_t)(((int64_t)w * total) / nwg);
-    const int32_t g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
-    int32_t s, before;
-    locate_tile(seq_lens, batch, g, lane, s, before);
+    int32_t total, g, g_end, s, before;
+    if (batch <= 64) {
+        // one read of the lengths serves both the total and the search for this workgroup's first sequence
+        const int32_t n = lane < batch ? tiles_of(seq_lens[lane]) : 0;
+        int32_t inc = n;                                   // inclusive scan over the 64 lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += t;
+        }
+        total = __shfl(inc, 63, 64);
+        const int32_t nwg = min((int32_t)gridDim.x, total);
+        if (w >= nwg) return;
+        g = (int32_t)(((int64_t)w * total) / nwg);
+        g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
+        const uint64_t hit = __ballot(inc > g);
+        s = __ffsll((unsigned long long)hit) - 1;
+        before = __shfl(inc, s, 64) - __shfl(n, s, 64);
+    } else {
+        total = total_tiles(seq_lens, batch, lane);
+        const int32_t nwg = min((int32_t)gridDim.x, total);
+        if (w >= nwg) return;
+        g = (int32_t)(((int64_t)w * total) / nwg);
+        g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
+        locate_tile(seq_lens, batch, g, lane, s, before);
+    }
     s = __builtin_amdgcn_readfirstlane(s);
     before = __builtin_amdgcn_readfirstlane(before);
 

@@ -42,40 +42,72 @@ __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
 
 // Tile-stream layout: sequence s was cut by the workgroups seg_first[s] .. seg_last[s]; workgroup w left its
 // partial at index (w + s).  seg_first[s] < 0 means one workgroup held the whole sequence and wrote the final
-// result itself.
+// result itself.  One workgroup merges one (sequence, head): the partial LSEs are fetched by as many threads at
+// once and reduced through LDS, then every thread owns one output column and sums the weighted partial rows
+// with independent loads (eight in flight), so the kernel costs a few memory latencies, not one per partial.
+constexpr int kMergeThreads = 128;
+
 template <bool BF16>
-__global__ __launch_bounds__(256) void paged_attention_merge_stream_kernel(
+__global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
     float* __restrict__ lse, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ seg_first,
     const int32_t* __restrict__ seg_last, int32_t num_q_heads, int32_t d)
 {
+    __shared__ float w_s[kMaxDecodeWGs + 1];
+    __shared__ float red[4];
     const int32_t s = blockIdx.x / num_q_heads;
     const int32_t h = blockIdx.x % num_q_heads;
     const int64_t o_idx = blockIdx.x;
-    const int e = threadIdx.x;
-    int32_t n = 0, first = 0;
-    if (seq_lens[s] > 0) {
-        first = seg_first[s];
-        if (first < 0) return;                      // already final
-        n = seg_last[s] - first + 1;
-    }
+    const int tid = threadIdx.x;
+    const int32_t len = seq_lens[s];
+    const int32_t first = seg_first[s];
+    const int32_t last = seg_last[s];
+    if (len > 0 && first < 0) return;                  // already final
+    const int32_t n = len > 0 ? last - first + 1 : 0;
     const int64_t p0 = (int64_t)(first + s) * num_q_heads + h;     // partial c sits num_q_heads rows further each
-    float M = -INFINITY;
-    for (int32_t c = 0; c < n; ++c) M = fmaxf(M, part_lse[p0 + (int64_t)c * num_q_heads]);
-    float wsum = 0.f, acc = 0.f;
-    for (int32_t c = 0; c < n; ++c) {
-        const float w = expf(part_lse[p0 + (int64_t)c * num_q_heads] - M);
-        wsum += w;
-        if (e < d) acc = fmaf(w, part_o[(p0 + (int64_t)c * num_q_heads) * d + e], acc);
+
+    // weights exp(lse_c - M) into LDS
+    float mx = -INFINITY;
+    for (int32_t c = tid; c < n; c += kMergeThreads) {
+        const float v = part_lse[p0 + (int64_t)c * num_q_heads];
+        w_s[c] = v;
+        mx = fmaxf(mx, v);
     }
-    const float r = n > 0 ? acc / wsum : 0.f;
-    if (e < d) {
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    const float M = fmaxf(red[0], red[1]);
+    float ws = 0.f;
+    for (int32_t c = tid; c < n; c += kMergeThreads) {
+        const float wgt = expf(w_s[c] - M);
+        w_s[c] = wgt;
+        ws += wgt;
+    }
+    ws = wave_sum(ws);
+    if ((tid & 63) == 0) red[2 + (tid >> 6)] = ws;
+    __syncthreads();
+    const float wsum = red[2] + red[3];
+
+    for (int e = tid; e < d; e += kMergeThreads) {
+        const float* po = part_o + p0 * d + e;
+        const int64_t step = (int64_t)num_q_heads * d;
+        float acc = 0.f;
+        int32_t c = 0;
+        for (; c + 8 <= n; c += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = po[(int64_t)(c + u) * step];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = fmaf(w_s[c + u], v[u], acc);
+        }
+        for (; c < n; ++c) acc = fmaf(w_s[c], po[(int64_t)c * step], acc);
+        const float r = n > 0 ? acc / wsum : 0.f;
         if (BF16)
             reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
         else
             reinterpret_cast<float*>(out)[o_idx * d + e] = r;
     }
-    if (lse && e == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
+    if (lse && tid == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
 }
 
 }  // namespace
@@ -88,11 +120,11 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
     ProfileScope prof("paged_attention_merge_kernel", stream);
     if (a.stream_split) {
         if (a.dtype == PA_DTYPE_BF16)
-            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<true>, dim3((uint32_t)blocks), dim3(threads), 0,
+            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<true>, dim3((uint32_t)blocks), dim3(kMergeThreads), 0,
                                stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
                                a.num_q_heads, a.cache.head_dim);
         else
-            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<false>, dim3((uint32_t)blocks), dim3(threads), 0,
+            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<false>, dim3((uint32_t)blocks), dim3(kMergeThreads), 0,
                                stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
                                a.num_q_heads, a.cache.head_dim);
         return launch_status();

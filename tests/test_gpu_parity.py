@@ -260,3 +260,51 @@ def test_config5_full_size_sampled_sequences(pa, oracle, P):
     parity.check_step(pa, oracle, w, f"config 5 full P={P}", seqs=[0, 7, 15])
     del w
     torch.cuda.empty_cache()
+
+
+# ----------------------------------------------------------------------------- HIP graph replay
+def test_decode_step_replays_in_a_hip_graph(pa, oracle):
+    """One step (append + decode + merge) captured in a HIP graph: every replay, with eager work and
+    synchronisations in between and fresh inputs written in place, must reproduce the eager result bitwise
+    (the library records no memset node and allocates nothing, so the capture holds only its kernels)."""
+    w = W.make_workload("t", seq_lens=[700, 64, 2048, 33], num_q_heads=32, num_kv_heads=8, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, seed=61, device=DEV)
+    ws = torch.empty(pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.batch, w.max_seq_len),
+                     dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(w.q)
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device=DEV)
+
+    def step():
+        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+        pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
+                                  out=out, lse=lse, workspace=ws)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    for it in range(4):
+        # fresh inputs, written in place so the captured pointers stay valid
+        w.q.copy_(torch.randn(w.q.shape, generator=gen, device=DEV).to(w.q.dtype))
+        w.k_new.copy_(torch.randn(w.k_new.shape, generator=gen, device=DEV).to(w.q.dtype))
+        w.v_new.copy_(torch.randn(w.v_new.shape, generator=gen, device=DEV).to(w.q.dtype))
+        torch.cuda.synchronize()
+        step()                                   # eager
+        torch.cuda.synchronize()
+        eager_out, eager_lse = out.clone(), lse.clone()
+        out.zero_()
+        lse.zero_()
+        ws.fill_(0xFF)                           # the workspace need not survive between steps
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out), f"replay {it}: out differs from eager"
+        assert torch.equal(lse, eager_lse), f"replay {it}: lse differs from eager"
+    k_ref, v_ref, o_ref, _ = parity.oracle_step(oracle, w, append=False)   # pools already hold the last append
+    parity.assert_close(parity.to_f64(out), o_ref, w.dtype, "graph replay vs oracle")
