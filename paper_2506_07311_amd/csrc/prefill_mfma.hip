@@ -55,38 +55,53 @@ struct PageIds {   // page of key g + 16*i (K and V rows of a thread share their
     int32_t p0, p1, p2, p3;
 };
 
-__device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, const int32_t* table, int32_t key,
+// UNIFORM (page size >= 16): the 16 keys g + 16*i, g = 0..15, of all threads lie in one page, so the page id is
+// wave-uniform -- a scalar load, and the page base address is scalar arithmetic.
+template <bool UNIFORM>
+__device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, const int32_t* table, int32_t t0, int32_t g,
                                          int32_t last_key)
 {
+    const int32_t key = UNIFORM ? t0 : t0 + g;
     p.p0 = table[min(key, last_key) >> cache.log2_page];
     p.p1 = table[min(key + 16, last_key) >> cache.log2_page];
     p.p2 = table[min(key + 32, last_key) >> cache.log2_page];
     p.p3 = table[min(key + 48, last_key) >> cache.log2_page];
+    if (UNIFORM) {
+        p.p0 = __builtin_amdgcn_readfirstlane(p.p0);
+        p.p1 = __builtin_amdgcn_readfirstlane(p.p1);
+        p.p2 = __builtin_amdgcn_readfirstlane(p.p2);
+        p.p3 = __builtin_amdgcn_readfirstlane(p.p3);
+    }
 }
 
-// Byte offset of the row of `key` (clamped to a live slot) in page `page`.
-__device__ __forceinline__ int64_t row_offset(const CacheView& cache, int32_t page, int32_t key, int32_t last_key)
+// One 16-byte piece of the K row and of the V row of `key` (clamped to a live slot) in page `page`.
+// lane_off = byte offset of this thread's head and piece inside a token row.
+template <bool UNIFORM>
+__device__ __forceinline__ void load_rows(uint4& k, uint4& v, const CacheView& cache, int32_t page, int32_t key,
+                                          int32_t last_key, uint32_t lane_off)
 {
     const int32_t slot = min(key, last_key) & (cache.page_size - 1);
-    return ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2;
+    if (UNIFORM) {
+        const int64_t base = (int64_t)page * cache.page_stride * 2;                            // scalar
+        const uint32_t off = (uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off;   // 32-bit multiply-add
+        k = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.k) + base + off);
+        v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.v) + base + off);
+    } else {
+        const int64_t off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
+        k = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.k) + off);
+        v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.v) + off);
+    }
 }
 
+template <bool UNIFORM>
 __device__ __forceinline__ void load_stage(uint4& k0, uint4& k1, uint4& k2, uint4& k3, uint4& v0, uint4& v1, uint4& v2,
-                                           uint4& v3, const PageIds& p, const CacheView& cache, const char* kb,
-                                           const char* vb, int32_t key, int32_t last_key)
+                                           uint4& v3, const PageIds& p, const CacheView& cache, int32_t key,
+                                           int32_t last_key, uint32_t lane_off)
 {
-    const int64_t o0 = row_offset(cache, p.p0, key, last_key);
-    const int64_t o1 = row_offset(cache, p.p1, key + 16, last_key);
-    const int64_t o2 = row_offset(cache, p.p2, key + 32, last_key);
-    const int64_t o3 = row_offset(cache, p.p3, key + 48, last_key);
-    k0 = *reinterpret_cast<const uint4*>(kb + o0);
-    k1 = *reinterpret_cast<const uint4*>(kb + o1);
-    k2 = *reinterpret_cast<const uint4*>(kb + o2);
-    k3 = *reinterpret_cast<const uint4*>(kb + o3);
-    v0 = *reinterpret_cast<const uint4*>(vb + o0);
-    v1 = *reinterpret_cast<const uint4*>(vb + o1);
-    v2 = *reinterpret_cast<const uint4*>(vb + o2);
-    v3 = *reinterpret_cast<const uint4*>(vb + o3);
+    load_rows<UNIFORM>(k0, v0, cache, p.p0, key, last_key, lane_off);
+    load_rows<UNIFORM>(k1, v1, cache, p.p1, key + 16, last_key, lane_off);
+    load_rows<UNIFORM>(k2, v2, cache, p.p2, key + 32, last_key, lane_off);
+    load_rows<UNIFORM>(k3, v3, cache, p.p3, key + 48, last_key, lane_off);
 }
 
 __device__ __forceinline__ void store_stage(const uint4 k0, const uint4 k1, const uint4 k2, const uint4 k3, const uint4 v0,
@@ -273,7 +288,7 @@ __device__ __forceinline__ void attend_tile(const char* kp, const char* vp, cons
     half_pv<PRECISE>(o, p, vp + 32 * kVRow);
 }
 
-template <bool PRECISE>
+template <bool PRECISE, bool UNIFORM>
 __device__ __forceinline__ void prefill_body(
     const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
@@ -348,9 +363,7 @@ __device__ __forceinline__ void prefill_body(
     const char* vp = v_s + (4 * hh + ((lane & 15) >> 2)) * kVRow + 2 * (16 * ((lane >> 4) & 1) + 4 * (lane & 3));
     // staging role of this thread: 16-byte piece sc16 of rows sg + 16*i
     const int sc16 = tid & 15, sg = tid >> 4;
-    const int64_t head_off = (int64_t)kvh * cache.head_stride * 2 + sc16 * 16;
-    const char* kb = reinterpret_cast<const char*>(cache.k) + head_off;
-    const char* vb = reinterpret_cast<const char*>(cache.v) + head_off;
+    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + sc16 * 16);
     char* kw = k_s + sg * kKRow + sc16 * 16;
     char* vw = v_s + sg * kVRow + sc16 * 16;
     const int32_t last_key = len - 1;
@@ -359,13 +372,13 @@ __device__ __forceinline__ void prefill_body(
     PageIds ids;
     const int32_t n_tiles = (nk_wg + kBN - 1) / kBN;
     if (n_tiles > 0) {
-        load_ids(ids, cache, table, sg, last_key);
-        load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, sg, last_key);
-        if (n_tiles > 1) load_ids(ids, cache, table, kBN + sg, last_key);
+        load_ids<UNIFORM>(ids, cache, table, 0, sg, last_key);
+        load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, sg, last_key, lane_off);
+        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, kBN, sg, last_key);
         store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw, vw);
         if (n_tiles > 1) {
-            load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, kBN + sg, last_key);
-            if (n_tiles > 2) load_ids(ids, cache, table, 2 * kBN + sg, last_key);
+            load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kBN + sg, last_key, lane_off);
+            if (n_tiles > 2) load_ids<UNIFORM>(ids, cache, table, 2 * kBN, sg, last_key);
         }
         __syncthreads();
     }
@@ -383,8 +396,9 @@ __device__ __forceinline__ void prefill_body(
             // reading before the last barrier; then the rows of tile t+2 and the page ids of tile t+3 are requested
             store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw + nxt, vw + nxt);
             if (t + 2 < n_tiles) {
-                load_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kb, vb, t0 + 2 * kBN + sg, last_key);
-                if (t + 3 < n_tiles) load_ids(ids, cache, table, t0 + 3 * kBN + sg, last_key);
+                load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, t0 + 2 * kBN + sg, last_key,
+                                    lane_off);
+                if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 3 * kBN, sg, last_key);
             }
         }
         __syncthreads();
@@ -409,15 +423,16 @@ __device__ __forceinline__ void prefill_body(
 
 // Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
 // workgroup runs exactly one of them, decided by its context length.
+template <bool UNIFORM>
 __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
     float scale, int32_t causal)
 {
-    prefill_body<false>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+    prefill_body<false, UNIFORM>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
                         scale, causal);
-    prefill_body<true>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+    prefill_body<true, UNIFORM>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
                        scale, causal);
 }
 
@@ -439,14 +454,18 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     const dim3 grid((uint32_t)blocks, 1, 1);
     constexpr int kSmem = 2 * kBufBytes;   // above the 64 KiB default: raised once per process
     static const bool raised = [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess;
     }();
     if (!raised) return PA_ERR_HIP;
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
-    hipLaunchKernelGGL(paged_prefill_mfma_kernel, grid, dim3(kThreads), kSmem, stream, a.cache, (const uint16_t*)a.q,
-                       (uint16_t*)a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch, tiles, a.num_q_heads,
-                       a.max_blocks, a.scale, a.causal);
+    // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
+    auto kern = a.cache.page_size >= 16 ? paged_prefill_mfma_kernel<true> : paged_prefill_mfma_kernel<false>;
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), kSmem, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                       a.cu_q_lens, a.block_table, a.seq_lens, a.batch, tiles, a.num_q_heads, a.max_blocks, a.scale,
+                       a.causal);
     return launch_status();
 }
 
