@@ -22,6 +22,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
+# HBM bytes per launch of the dominant kernel, measured once per workload with two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE) and scaled by what the same counters read for the plain gather copy of known size
+# (FETCH_SIZE x1.998, WRITE_SIZE x1.000); the summaries are under profiles/.
+MEASURED_TRAFFIC = {
+    "decode_b16_ctx131072_p16": {"read_bytes": 8589673000, "write_bytes": 8474500,
+                                 "source": "profiles/decode_b16_ctx131072_p16.md"},
+    "prefill_b4_s2048_causal": {"read_bytes": 670838000, "write_bytes": 81740000,
+                                "source": "profiles/prefill_b4_s2048_causal.md"},
+}
+
 WORKLOADS = {
     # name: (config number, page size, context override)
     "decode_b16_ctx131072_p16": (5, 16, None),
@@ -196,14 +206,16 @@ def main():
         dom = kernels.get("paged_prefill_mfma_kernel") or kernels.get("paged_attention_generic_kernel")
         ach = flops / (dom["avg_us"] * 1e-6) / 1e12
         result["roofline"] = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                              "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                              "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "traffic": MEASURED_TRAFFIC.get(args.workload),
                               "kernel": "paged_prefill_mfma_kernel" if "paged_prefill_mfma_kernel" in kernels
                               else "paged_attention_generic_kernel", "useful_flops": flops}
     else:
         name = "paged_decode_mfma_kernel" if "paged_decode_mfma_kernel" in kernels else "paged_attention_generic_kernel"
         ach = kv_bytes / (kernels[name]["avg_us"] * 1e-6) / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": name,
+                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                              "kernel": name,
                               "algorithmic_bytes": kv_bytes}
 
     if not args.no_oracle:
