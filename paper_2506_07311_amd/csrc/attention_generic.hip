@@ -19,6 +19,7 @@ constexpr int kMaxD = 256;
 template <typename T> struct Vec;
 template <> struct Vec<float> {
     static constexpr int N = 4;
+    typedef double dot_t;   // fp32 I/O is held to 1e-5: 128-term fp32 dot products alone would use most of that
     __device__ static void load(const void* p, float* f)
     {
         const float4 v = *reinterpret_cast<const float4*>(p);
@@ -30,6 +31,7 @@ template <> struct Vec<float> {
 struct bf16_tag {};
 template <> struct Vec<bf16_tag> {
     static constexpr int N = 8;
+    typedef float dot_t;
     __device__ static void load(const void* p, float* f)
     {
         const uint4 v = *reinterpret_cast<const uint4*>(p);
@@ -135,14 +137,14 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
             const int32_t j = t0 + jj;
             const int64_t page = table[j >> cache.log2_page];
             const char* kr = kbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
-            float dot = 0.f;
+            typename V::dot_t dot = 0;
             for (int32_t c = 0; c < vpr; ++c) {
                 float kv[N];
                 V::load(kr + c * 16, kv);
 #pragma unroll
-                for (int e = 0; e < N; ++e) dot = fmaf(q_s[c * N + e], kv[e], dot);
+                for (int e = 0; e < N; ++e) dot += (typename V::dot_t)q_s[c * N + e] * (typename V::dot_t)kv[e];
             }
-            const float sj = dot * scale;
+            const float sj = (float)(dot * scale);
             sc[jj] = sj;
             lmax = fmaxf(lmax, sj);
         }
