@@ -4,11 +4,15 @@
 // with v_mfma_f32_32x32x16_bf16 in the flash-attention arrangement: one workgroup of 4 waves owns 128
 // consecutive queries of one (sequence, query head); wave w owns 32 of them.  The context is walked in
 // tiles of 64 keys.  A tile's K and V rows are fetched page by page through the block table (Algorithm 1:
-// page = block_table[s][j >> log2 P], slot = j & (P-1)) with coalesced 16-byte loads into registers one
-// tile ahead (their page ids two tiles ahead), then stored row-major in LDS:
-//   K [64 keys][128] rows padded to 272 B: the 16-byte operand reads of 8 consecutive lanes hit 32 banks
-//   V [64 keys][128] rows padded to 288 B: read back TRANSPOSED with ds_read_b64_tr_b16, the LDS transpose
-//     load of gfx950 -- the contraction index of P.V is the key while memory is contiguous along head_dim
+// page = block_table[s][j >> log2 P], slot = j & (P-1)) and written STRAIGHT INTO LDS by the load unit
+// (global_load_lds_dwordx4: 16 bytes per lane, a wave fills 4 consecutive 256-byte rows per instruction), one
+// tile ahead of the one being computed, into the other of two 32 KiB buffers -- no staging registers, no LDS
+// store instructions, one barrier per tile.  Rows are unpadded; the 16-byte piece L of row r sits at piece
+// L ^ 2*(r%8) (each lane simply fetches the piece that belongs at its LDS position), which makes both kinds
+// of operand read conflict-free:
+//   K rows are read as 16-byte MFMA operands (8 consecutive lanes = 8 consecutive rows, same logical piece),
+//   V rows are read TRANSPOSED with ds_read_b64_tr_b16, the LDS transpose load of gfx950 -- the contraction
+//     index of P.V is the key while memory is contiguous along head_dim.
 // Both products are computed transposed so that every per-query quantity is lane-local (lane%32 = query):
 //   S^T[key, q]  = K[key, :] . Q[q, :]^T        A = K from LDS, B = Q held in registers for the whole kernel
 //   O^T[col, q] += V^T[col, key] . P^T[key, q]  A = V^T from LDS, B = P straight from the S^T accumulators
@@ -36,9 +40,9 @@ constexpr int kBM = 128;              // queries per workgroup
 constexpr int kBN = 64;               // keys per tile
 constexpr int kThreads = 256;
 constexpr int kPreciseKeys = 256;     // contexts up to this length use two-term bf16 weights
-constexpr int kKRow = 256 + 16;       // bytes per K row in LDS
-constexpr int kVRow = 256 + 32;       // bytes per V row in LDS
-constexpr int kBufBytes = kBN * (kKRow + kVRow);   // one tile buffer: K rows, then V rows
+constexpr int kRow = 256;             // bytes per K or V row in LDS (unpadded, pieces swizzled)
+constexpr int kTileBytes = kBN * kRow;   // K part of a tile buffer; the V part follows
+constexpr int kBufBytes = 2 * kTileBytes;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -49,19 +53,23 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Staging: thread (c = tid%16, g = tid/16) moves the 16-byte piece c of K rows and V rows g + 16*i, i < 4.
+// Tile fetch.  Wave w issues, for i < 4, one load-to-LDS instruction for K and one for V that fill rows
+// 16*i + 4*w .. +3 of the tile: lane l brings the 16-byte piece that belongs at position l%16 of row
+// 16*i + 4*w + l/16.  UNIFORM (page size >= 16): the four rows of an instruction lie in one page, so the page
+// id is a scalar load and the page base scalar arithmetic; page ids are fetched one tile earlier than the rows.
 // ---------------------------------------------------------------------------------------------------
-struct PageIds {   // page of key g + 16*i (K and V rows of a thread share their keys)
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_void;
+
+struct PageIds {
     int32_t p0, p1, p2, p3;
 };
 
-// UNIFORM (page size >= 16): the 16 keys g + 16*i, g = 0..15, of all threads lie in one page, so the page id is
-// wave-uniform -- a scalar load, and the page base address is scalar arithmetic.
 template <bool UNIFORM>
-__device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, const int32_t* table, int32_t t0, int32_t g,
-                                         int32_t last_key)
+__device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, const int32_t* table, int32_t t0,
+                                         int32_t row, int32_t last_key)
 {
-    const int32_t key = UNIFORM ? t0 : t0 + g;
+    const int32_t key = UNIFORM ? t0 : t0 + row;
     p.p0 = table[min(key, last_key) >> cache.log2_page];
     p.p1 = table[min(key + 16, last_key) >> cache.log2_page];
     p.p2 = table[min(key + 32, last_key) >> cache.log2_page];
@@ -74,47 +82,31 @@ __device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, con
     }
 }
 
-// One 16-byte piece of the K row and of the V row of `key` (clamped to a live slot) in page `page`.
-// lane_off = byte offset of this thread's head and piece inside a token row.
+// K row and V row of `key` (clamped to a live slot) in page `page` -> LDS rows at `dst` (K) and dst + kTileBytes (V).
 template <bool UNIFORM>
-__device__ __forceinline__ void load_rows(uint4& k, uint4& v, const CacheView& cache, int32_t page, int32_t key,
-                                          int32_t last_key, uint32_t lane_off)
-{
-    const int32_t slot = min(key, last_key) & (cache.page_size - 1);
-    if (UNIFORM) {
-        const int64_t base = (int64_t)page * cache.page_stride * 2;                            // scalar
-        const uint32_t off = (uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off;   // 32-bit multiply-add
-        k = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.k) + base + off);
-        v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.v) + base + off);
-    } else {
-        const int64_t off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
-        k = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.k) + off);
-        v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(cache.v) + off);
-    }
-}
-
-template <bool UNIFORM>
-__device__ __forceinline__ void load_stage(uint4& k0, uint4& k1, uint4& k2, uint4& k3, uint4& v0, uint4& v1, uint4& v2,
-                                           uint4& v3, const PageIds& p, const CacheView& cache, int32_t key,
+__device__ __forceinline__ void fetch_rows(char* dst, const CacheView& cache, int32_t page, int32_t key,
                                            int32_t last_key, uint32_t lane_off)
 {
-    load_rows<UNIFORM>(k0, v0, cache, p.p0, key, last_key, lane_off);
-    load_rows<UNIFORM>(k1, v1, cache, p.p1, key + 16, last_key, lane_off);
-    load_rows<UNIFORM>(k2, v2, cache, p.p2, key + 32, last_key, lane_off);
-    load_rows<UNIFORM>(k3, v3, cache, p.p3, key + 48, last_key, lane_off);
+    const int32_t slot = min(key, last_key) & (cache.page_size - 1);
+    int64_t off;
+    if (UNIFORM)
+        off = (int64_t)page * cache.page_stride * 2 + ((uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off);
+    else
+        off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
+    __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.k) + off), (lds_void*)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.v) + off),
+                                     (lds_void*)(dst + kTileBytes), 16, 0, 0);
 }
 
-__device__ __forceinline__ void store_stage(const uint4 k0, const uint4 k1, const uint4 k2, const uint4 k3, const uint4 v0,
-                                            const uint4 v1, const uint4 v2, const uint4 v3, char* kw, char* vw)
+// dst = buffer + 4*w*kRow (this wave's first row); row = 4*w + lane/16 (this lane's row within a 16-row group).
+template <bool UNIFORM>
+__device__ __forceinline__ void fetch_tile(char* dst, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
+                                           int32_t last_key, uint32_t lane_off)
 {
-    *reinterpret_cast<uint4*>(kw) = k0;
-    *reinterpret_cast<uint4*>(kw + 16 * kKRow) = k1;
-    *reinterpret_cast<uint4*>(kw + 32 * kKRow) = k2;
-    *reinterpret_cast<uint4*>(kw + 48 * kKRow) = k3;
-    *reinterpret_cast<uint4*>(vw) = v0;
-    *reinterpret_cast<uint4*>(vw + 16 * kVRow) = v1;
-    *reinterpret_cast<uint4*>(vw + 32 * kVRow) = v2;
-    *reinterpret_cast<uint4*>(vw + 48 * kVRow) = v3;
+    fetch_rows<UNIFORM>(dst, cache, p.p0, t0 + row, last_key, lane_off);
+    fetch_rows<UNIFORM>(dst + 16 * kRow, cache, p.p1, t0 + row + 16, last_key, lane_off);
+    fetch_rows<UNIFORM>(dst + 32 * kRow, cache, p.p2, t0 + row + 32, last_key, lane_off);
+    fetch_rows<UNIFORM>(dst + 48 * kRow, cache, p.p3, t0 + row + 48, last_key, lane_off);
 }
 
 __device__ __forceinline__ bf16x8 lds_frag(const char* p)
@@ -126,7 +118,7 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p)
 // ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block receives element i%4 of the 8 bytes
 // addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.  Lane x = q + 4*j of a block therefore points at
 // key j of the step, columns 4q..4q+3 of the block's 16 columns, and lane i ends up with column i of 4 keys.
-// `vp` already holds this lane's part of the address; two loads fetch the keys of contraction slots 0-3 and 4-7.
+// `vp` already holds this lane's (swizzled) address; two loads fetch the keys of contraction slots 0-3 and 4-7.
 struct tr_pair {
     s16x4 lo, hi;
 };
@@ -135,7 +127,7 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* vp)
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     tr_pair r;
     r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
-    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kVRow));
+    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kRow));
     return __builtin_bit_cast(bf16x8, r);
 }
 
@@ -212,16 +204,18 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4
     l += psum;
 }
 
-// O^T += V^T P^T for the 32 keys of one half tile (two 16-key steps).  vh = this lane's transpose-load address
-// for the first step of the half.  P^T as B operand of a step: elements e = 0..7 <-> weights 8*step + e.
+// O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps).  vbuf = V part of the tile buffer,
+// vx[t] = this lane's swizzled transpose-load offset for the 32 columns t.  P^T as B operand of a step:
+// elements e = 0..7 <-> weights 8*step + e.
 template <bool PRECISE>
-__device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const char* vh)
+__device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const char* vbuf, int half,
+                                        const uint32_t (&vx)[4])
 {
     bf16x8 va[4], vb[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vh + 64 * t);
+    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vbuf + vx[t] + (32 * half) * kRow);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) vb[t] = lds_frag_tr(vh + 64 * t + 16 * kVRow);
+    for (int t = 0; t < 4; ++t) vb[t] = lds_frag_tr(vbuf + vx[t] + (32 * half + 16) * kRow);
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
         const int r0 = 8 * st;
@@ -249,19 +243,21 @@ __device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const c
     }
 }
 
-// S^T of one half tile (32 keys) against the wave's 32 queries: 8 chained matrix instructions, the K operand
-// reads kept four ahead.  kh = this lane's K operand address for the half.
-__device__ __forceinline__ void half_scores(f32x16& s, const char* kh, const bf16x8 (&qf)[8])
+// S^T of half tile `half` (32 keys) against the wave's 32 queries: 8 chained matrix instructions, the K operand
+// reads kept four ahead.  kx[ks] = this lane's swizzled operand offset for head_dim step ks.
+__device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int half, const uint32_t (&kx)[8],
+                                            const bf16x8 (&qf)[8])
 {
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    const char* kh = kbuf + (32 * half) * kRow;
     bf16x8 ka[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ka[i] = lds_frag(kh + 32 * i);
+    for (int i = 0; i < 4; ++i) ka[i] = lds_frag(kh + kx[i]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s, 0, 0, 0);
-        ka[i] = lds_frag(kh + 32 * (i + 4));
+        ka[i] = lds_frag(kh + kx[i + 4]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i + 4], s, 0, 0, 0);
@@ -271,36 +267,29 @@ __device__ __forceinline__ void half_scores(f32x16& s, const char* kh, const bf1
 // one half (vector ALU) runs under the matrix instructions of the other half:
 //     matrix cores:  S(h0)   S(h1)          PV(h0)          PV(h1)
 //     vector ALU:            softmax(h0)    softmax(h1)
-//   kp = k_s + (lane%32) * kKRow + 16 * (lane/32)         this lane's K operand row / 8-element piece
-//   vp = v_s + (4*(lane/32) + (lane%16)/4) * kVRow + 2 * (16*((lane/16)%2) + 4*(lane%4))   transpose-load address
-//   key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's query may see (MASK only)
-// sc = scale * log2(e) > 0.
+// buf = tile buffer (K rows, then V rows); key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's
+// query may see (MASK only); sc = scale * log2(e) > 0.
 template <bool PRECISE, bool MASK>
-__device__ __forceinline__ void attend_tile(const char* kp, const char* vp, const bf16x8 (&qf)[8], f32x16 (&o)[4],
-                                            float& m, float& l, float sc, int32_t key0, int32_t nk)
+__device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[8], const uint32_t (&vx)[4],
+                                            const bf16x8 (&qf)[8], f32x16 (&o)[4], float& m, float& l, float sc,
+                                            int32_t key0, int32_t nk)
 {
     f32x16 s0, s1, p;
-    half_scores(s0, kp, qf);
-    half_scores(s1, kp + 32 * kKRow, qf);
+    half_scores(s0, buf, 0, kx, qf);
+    half_scores(s1, buf, 1, kx, qf);
     half_softmax<MASK, true>(p, s0, o, m, l, sc, key0, nk);
-    half_pv<PRECISE>(o, p, vp);
+    half_pv<PRECISE>(o, p, buf + kTileBytes, 0, vx);
     half_softmax<MASK, false>(p, s1, o, m, l, sc, key0 + 32, nk);
-    half_pv<PRECISE>(o, p, vp + 32 * kVRow);
+    half_pv<PRECISE>(o, p, buf + kTileBytes, 1, vx);
 }
 
 template <bool PRECISE, bool UNIFORM>
 __device__ __forceinline__ void prefill_body(
-    const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
     float scale, int32_t causal)
 {
-    // two tile buffers (K rows then V rows each): while one is read by the matrix cores the next tile is
-    // written into the other, so one barrier per tile suffices
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* const k_s = smem;
-    char* const v_s = smem + kBN * kKRow;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int ql = lane & 31, hh = lane >> 5;
@@ -359,47 +348,58 @@ __device__ __forceinline__ void prefill_body(
     float m = -INFINITY, l = 0.f;
     const float sc = scale * kLog2e;
 
-    const char* kp = k_s + ql * kKRow + 16 * hh;
-    const char* vp = v_s + (4 * hh + ((lane & 15) >> 2)) * kVRow + 2 * (16 * ((lane >> 4) & 1) + 4 * (lane & 3));
-    // staging role of this thread: 16-byte piece sc16 of rows sg + 16*i
-    const int sc16 = tid & 15, sg = tid >> 4;
-    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + sc16 * 16);
-    char* kw = k_s + sg * kKRow + sc16 * 16;
-    char* vw = v_s + sg * kVRow + sc16 * 16;
+    // swizzled LDS offsets of this lane's operands (see the header): K piece (2*ks + hh) of row ql,
+    // V pieces of the 32 columns t for the lane's transpose-load row
+    uint32_t kx[8], vx[4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kx[ks] = ql * kRow + 16 * hh + 32 * (ks ^ (ql & 7));
+    {
+        const int j = (lane & 15) >> 2, qq = lane & 3, dblk = (lane >> 4) & 1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            vx[t] = (4 * hh + j) * kRow + 16 * ((4 * t + 2 * dblk + (qq >> 1)) ^ (2 * (4 * hh + j))) + 8 * (qq & 1);
+    }
+    // fetch role of this lane: position lane%16 of rows 16*i + frow holds logical piece (lane%16) ^ 2*(frow%8)
+    const int frow = 4 * wave + (lane >> 4);
+    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + 16 * ((lane & 15) ^ (2 * (frow & 7))));
+    const int32_t wrow = __builtin_amdgcn_readfirstlane(4 * wave * kRow);
     const int32_t last_key = len - 1;
 
-    uint4 sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3;
     PageIds ids;
     const int32_t n_tiles = (nk_wg + kBN - 1) / kBN;
     if (n_tiles > 0) {
-        load_ids<UNIFORM>(ids, cache, table, 0, sg, last_key);
-        load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, sg, last_key, lane_off);
-        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, kBN, sg, last_key);
-        store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw, vw);
-        if (n_tiles > 1) {
-            load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, kBN + sg, last_key, lane_off);
-            if (n_tiles > 2) load_ids<UNIFORM>(ids, cache, table, 2 * kBN, sg, last_key);
-        }
-        __syncthreads();
+        load_ids<UNIFORM>(ids, cache, table, 0, frow, last_key);
+        fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, 0, frow, last_key, lane_off);
+        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, kBN, frow, last_key);
+        __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
     }
-    for (int32_t t = 0; t < n_tiles; ++t) {
+    // Two tiles per trip so that each buffer is a distinct LDS object for the compiler: while the matrix cores
+    // read one, the load unit fills the other with the next tile; the page ids of the tile after that are requested
+    // at the same time.  The barrier at the end of a tile waits for this wave's loads first.
+    for (int32_t t = 0; t < n_tiles; t += 2) {
         const int32_t t0 = t * kBN;
-        const int32_t cur = (t & 1) * kBufBytes, nxt = kBufBytes - cur;
+        if (t + 1 < n_tiles) {
+            fetch_tile<UNIFORM>(buf1 + wrow, ids, cache, t0 + kBN, frow, last_key, lane_off);
+            if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
+        }
         if (t0 < nk_wave) {                                  // wave-uniform: else nothing for this wave here
             if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
-                attend_tile<PRECISE, true>(kp + cur, vp + cur, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, true>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
             else
-                attend_tile<PRECISE, false>(kp + cur, vp + cur, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, false>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
         }
-        if (t + 1 < n_tiles) {
-            // tile t+1 (in registers since the previous iteration) goes into the buffer every wave finished
-            // reading before the last barrier; then the rows of tile t+2 and the page ids of tile t+3 are requested
-            store_stage(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, kw + nxt, vw + nxt);
-            if (t + 2 < n_tiles) {
-                load_stage<UNIFORM>(sk0, sk1, sk2, sk3, sv0, sv1, sv2, sv3, ids, cache, t0 + 2 * kBN + sg, last_key,
-                                    lane_off);
-                if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 3 * kBN, sg, last_key);
-            }
+        __syncthreads();
+        if (t + 1 >= n_tiles) break;
+        const int32_t t1 = t0 + kBN;
+        if (t + 2 < n_tiles) {
+            fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, t1 + kBN, frow, last_key, lane_off);
+            if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
+        }
+        if (t1 < nk_wave) {
+            if (t1 + kBN > nk_wave_min)
+                attend_tile<PRECISE, true>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
+            else
+                attend_tile<PRECISE, false>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
         }
         __syncthreads();
     }
@@ -430,9 +430,11 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
     float scale, int32_t causal)
 {
-    prefill_body<false, UNIFORM>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+    __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
+    prefill_body<false, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
                         scale, causal);
-    prefill_body<true, UNIFORM>(cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
+    prefill_body<true, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
                        scale, causal);
 }
 
@@ -452,18 +454,10 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     const int64_t blocks = (int64_t)tiles * a.num_q_heads * a.batch;
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     const dim3 grid((uint32_t)blocks, 1, 1);
-    constexpr int kSmem = 2 * kBufBytes;   // above the 64 KiB default: raised once per process
-    static const bool raised = [] {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess &&
-               hipFuncSetAttribute(reinterpret_cast<const void*>(paged_prefill_mfma_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) == hipSuccess;
-    }();
-    if (!raised) return PA_ERR_HIP;
     ProfileScope prof("paged_prefill_mfma_kernel", stream);
     // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
     auto kern = a.cache.page_size >= 16 ? paged_prefill_mfma_kernel<true> : paged_prefill_mfma_kernel<false>;
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), kSmem, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                        a.cu_q_lens, a.block_table, a.seq_lens, a.batch, tiles, a.num_q_heads, a.max_blocks, a.scale,
                        a.causal);
     return launch_status();
