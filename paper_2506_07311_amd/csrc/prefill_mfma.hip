@@ -7,12 +7,14 @@
 // page = block_table[s][j >> log2 P], slot = j & (P-1)) and written STRAIGHT INTO LDS by the load unit
 // (global_load_lds_dwordx4: 16 bytes per lane, a wave fills 4 consecutive 256-byte rows per instruction), one
 // tile ahead of the one being computed, into the other of two 32 KiB buffers -- no staging registers, no LDS
-// store instructions, one barrier per tile.  Rows are unpadded; the 16-byte piece L of row r sits at piece
-// L ^ 2*(r%8) (each lane simply fetches the piece that belongs at its LDS position), which makes both kinds
-// of operand read conflict-free:
-//   K rows are read as 16-byte MFMA operands (8 consecutive lanes = 8 consecutive rows, same logical piece),
+// store instructions, one barrier per tile.  Rows are unpadded (256 B = all 64 LDS banks); the 16-byte piece L
+// of row r sits at piece L ^ swz(r), swz(r) = 4*(r%4) + (r/4)%4 (each lane simply fetches the piece that belongs
+// at its LDS position), which makes both kinds of operand read conflict-free:
+//   K rows are read as 16-byte MFMA operands (16 consecutive lanes = 16 consecutive rows, same logical piece:
+//     swz takes 16 distinct values),
 //   V rows are read TRANSPOSED with ds_read_b64_tr_b16, the LDS transpose load of gfx950 -- the contraction
-//     index of P.V is the key while memory is contiguous along head_dim.
+//     index of P.V is the key while memory is contiguous along head_dim (32 lanes read 64 bytes of each of 4
+//     consecutive rows: swz moves them to 4 different quarters of the banks).
 // Both products are computed transposed so that every per-query quantity is lane-local (lane%32 = query):
 //   S^T[key, q]  = K[key, :] . Q[q, :]^T        A = K from LDS, B = Q held in registers for the whole kernel
 //   O^T[col, q] += V^T[col, key] . P^T[key, q]  A = V^T from LDS, B = P straight from the S^T accumulators
@@ -43,6 +45,9 @@ constexpr int kPreciseKeys = 256;     // contexts up to this length use two-term
 constexpr int kRow = 256;             // bytes per K or V row in LDS (unpadded, pieces swizzled)
 constexpr int kTileBytes = kBN * kRow;   // K part of a tile buffer; the V part follows
 constexpr int kBufBytes = 2 * kTileBytes;
+
+// 16-byte piece L of LDS row r is stored at piece L ^ swz(r).
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -118,16 +123,16 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p)
 // ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block receives element i%4 of the 8 bytes
 // addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.  Lane x = q + 4*j of a block therefore points at
 // key j of the step, columns 4q..4q+3 of the block's 16 columns, and lane i ends up with column i of 4 keys.
-// `vp` already holds this lane's (swizzled) address; two loads fetch the keys of contraction slots 0-3 and 4-7.
+// The two loads fetch the keys of contraction slots 0-3 and 4-7 (8 rows apart; their swizzles differ).
 struct tr_pair {
     s16x4 lo, hi;
 };
-__device__ __forceinline__ bf16x8 lds_frag_tr(const char* vp)
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* lo, const char* hi)
 {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     tr_pair r;
-    r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
-    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * kRow));
+    r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lo));
+    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(hi));
     return __builtin_bit_cast(bf16x8, r);
 }
 
@@ -166,8 +171,8 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4
     }
     // keep the speculative weights ahead of the branch below (they are dead on its slow path, and the
     // optimiser would otherwise sink them behind the test, back onto the critical path)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(p[r]));
+    asm volatile("" ::"v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7]), "v"(p[8]),
+                 "v"(p[9]), "v"(p[10]), "v"(p[11]), "v"(p[12]), "v"(p[13]), "v"(p[14]), "v"(p[15]));
     if (FIRST) {
         // instruction order for the region that holds both score products and this half's softmax: the second
         // half's 8 matrix instructions are issued with the vector work of the first half's softmax in between
@@ -205,17 +210,18 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4
 }
 
 // O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps).  vbuf = V part of the tile buffer,
-// vx[t] = this lane's swizzled transpose-load offset for the 32 columns t.  P^T as B operand of a step:
+// vx[2t], vx[2t+1] = this lane's swizzled transpose-load offsets (slots 0-3 / 4-7) for the 32 columns t.  P^T as B operand of a step:
 // elements e = 0..7 <-> weights 8*step + e.
 template <bool PRECISE>
 __device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const char* vbuf, int half,
-                                        const uint32_t (&vx)[4])
+                                        const uint32_t (&vx)[8])
 {
     bf16x8 va[4], vb[4];
+    const char* v0 = vbuf + (32 * half) * kRow;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(vbuf + vx[t] + (32 * half) * kRow);
+    for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) vb[t] = lds_frag_tr(vbuf + vx[t] + (32 * half + 16) * kRow);
+    for (int t = 0; t < 4; ++t) vb[t] = lds_frag_tr(v0 + 16 * kRow + vx[2 * t], v0 + 16 * kRow + vx[2 * t + 1]);
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
         const int r0 = 8 * st;
@@ -248,8 +254,7 @@ __device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const c
 __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int half, const uint32_t (&kx)[8],
                                             const bf16x8 (&qf)[8])
 {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    s = (f32x16)(0.f);   // folded into the first matrix instruction's accumulator operand
     const char* kh = kbuf + (32 * half) * kRow;
     bf16x8 ka[4];
 #pragma unroll
@@ -270,7 +275,7 @@ __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int hal
 // buf = tile buffer (K rows, then V rows); key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's
 // query may see (MASK only); sc = scale * log2(e) > 0.
 template <bool PRECISE, bool MASK>
-__device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[8], const uint32_t (&vx)[4],
+__device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[8], const uint32_t (&vx)[8],
                                             const bf16x8 (&qf)[8], f32x16 (&o)[4], float& m, float& l, float sc,
                                             int32_t key0, int32_t nk)
 {
@@ -350,18 +355,23 @@ __device__ __forceinline__ void prefill_body(
 
     // swizzled LDS offsets of this lane's operands (see the header): K piece (2*ks + hh) of row ql,
     // V pieces of the 32 columns t for the lane's transpose-load row
-    uint32_t kx[8], vx[4];
+    uint32_t kx[8], vx[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kx[ks] = ql * kRow + 16 * hh + 32 * (ks ^ (ql & 7));
+    for (int ks = 0; ks < 8; ++ks) kx[ks] = ql * kRow + 16 * ((2 * ks + hh) ^ swz(ql));
     {
+        // transpose-load rows of this lane: key 4*hh + j (+8 for slots 4-7) of a 16-key step, columns 4*qq..+3 of
+        // the 16-column block dblk of the 32 columns t
         const int j = (lane & 15) >> 2, qq = lane & 3, dblk = (lane >> 4) & 1;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            vx[t] = (4 * hh + j) * kRow + 16 * ((4 * t + 2 * dblk + (qq >> 1)) ^ (2 * (4 * hh + j))) + 8 * (qq & 1);
+        for (int t = 0; t < 4; ++t) {
+            const int piece = 4 * t + 2 * dblk + (qq >> 1);
+            vx[2 * t] = (4 * hh + j) * kRow + 16 * (piece ^ swz(4 * hh + j)) + 8 * (qq & 1);
+            vx[2 * t + 1] = (4 * hh + j + 8) * kRow + 16 * (piece ^ swz(4 * hh + j + 8)) + 8 * (qq & 1);
+        }
     }
-    // fetch role of this lane: position lane%16 of rows 16*i + frow holds logical piece (lane%16) ^ 2*(frow%8)
+    // fetch role of this lane: position lane%16 of rows 16*i + frow holds logical piece (lane%16) ^ swz(frow)
     const int frow = 4 * wave + (lane >> 4);
-    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + 16 * ((lane & 15) ^ (2 * (frow & 7))));
+    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + 16 * ((lane & 15) ^ swz(frow)));
     const int32_t wrow = __builtin_amdgcn_readfirstlane(4 * wave * kRow);
     const int32_t last_key = len - 1;
 
