@@ -46,6 +46,8 @@ WORKLOADS = {
     "prefill_b4_s2048_causal": (3, 16, None),
     # plain paged copy of known size (Algorithm 1 Gather over 16 x 65536 tokens): calibrates HBM byte counters
     "gather_copy_calibration": (5, 16, 65536),
+    # host-side KV page manager under serving churn (Algorithm 1 Reserve; Sec. III-B): not an attention workload
+    "page_manager_serving": (None, 16, None),
 }
 
 
@@ -115,6 +117,66 @@ def run_gather_calibration(torch, pa, binding, w, args):
                      "algorithmic_bytes": nbytes, "note": "achieved counts bytes read; as many are written"}}))
 
 
+def run_page_manager(torch, binding, args, P):
+    """Serving churn through pa_pool_*: 256 live sequences grow by one token per step (one page pop every P
+    steps per sequence, its row entry copied to the device table on the stream); every step four sequences end
+    (release) and four prompts of 64..2048 tokens are admitted (reserve).  Times host calls only: they are what
+    the manager costs per step; a step is args.steps iterations of the whole batch."""
+    import random
+    B, max_blocks, pages = 256, 512, 256 * 160
+    table = torch.zeros((B, max_blocks), dtype=torch.int32, device="cuda:0")
+    pool = binding.pa_pool_create(pages, P, B, max_blocks, table)
+    rng = random.Random(7)
+    lens = [rng.randrange(64, 2048) for _ in range(B)]
+    for s in range(B):
+        binding.pa_pool_reserve(pool, s, lens[s])
+    lib = binding.load_library()
+    import ctypes
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    i32 = ctypes.c_int32
+    n_calls = pops = 0
+
+    def step():
+        nonlocal n_calls, pops
+        for s in range(B):
+            lens[s] = min(lens[s] + 1, max_blocks * P)
+            pops += lens[s] % P == 1
+            assert lib.pa_pool_reserve(pool, i32(s), i32(lens[s]), stream) == 0
+        for _ in range(4):
+            s = rng.randrange(B)
+            assert lib.pa_pool_release(pool, i32(s), stream) == 0
+            lens[s] = rng.randrange(64, 2048)
+            assert lib.pa_pool_reserve(pool, i32(s), i32(lens[s]), stream) == 0
+        n_calls += B + 8
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    n_calls = pops = 0
+    sec = time_steps(torch, step, args.steps, 0)
+    # the same calls on a pool without a device table: the bookkeeping alone
+    host = binding.pa_pool_create(pages, P, B, max_blocks)
+    null = ctypes.c_void_p(0)
+    t0 = time.perf_counter()
+    reps = 200000
+    for i in range(reps):
+        lib.pa_pool_reserve(host, i32(0), i32((i % 4096) + 1), null)
+        if i % 4096 == 4095:
+            lib.pa_pool_release(host, i32(0), null)
+    per_call_host = (time.perf_counter() - t0) / reps
+    binding.pa_pool_destroy(host)
+    binding.pa_pool_destroy(pool)
+    print(json.dumps({
+        "metric": "page_manager_us_per_serving_step", "value": round(sec * 1e6, 2), "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": args.workload, "live_sequences": B, "page_size": P, "pages": pages,
+                   "calls_per_step": n_calls // args.steps, "page_pops_per_step": round(pops / args.steps, 1)},
+        "host_us_per_call_with_device_table": round(sec * 1e6 / (n_calls / args.steps), 3),
+        "host_us_per_call_bookkeeping_only": round(per_call_host * 1e6, 3),
+        "note": "both per-call figures include the Python ctypes call (about 0.3-0.5 us)"}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -128,6 +190,8 @@ def main():
     pa.load_library()
     dev = "cuda:0"
     cfg, P, ctx = WORKLOADS[args.workload]
+    if args.workload == "page_manager_serving":
+        return run_page_manager(torch, binding, args, P)
     w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
     torch.cuda.synchronize()
     is_prefill = cfg == 3

@@ -39,7 +39,8 @@ typedef enum {
     PA_ERR_INVALID_ARG = 1,          /* NULL pointer, negative size, Hq % Hkv != 0, page size not a power of two */
     PA_ERR_UNSUPPORTED = 2,          /* dtype / head_dim / stride combination no kernel is written for            */
     PA_ERR_WORKSPACE_TOO_SMALL = 3,  /* workspace_bytes < paged_attention_workspace_bytes(...)                    */
-    PA_ERR_HIP = 4                   /* a HIP launch reported an error                                            */
+    PA_ERR_HIP = 4,                  /* a HIP call reported an error                                              */
+    PA_ERR_OUT_OF_PAGES = 5          /* the page pool cannot satisfy a reservation (nothing was changed)          */
 } pa_status;
 
 typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
@@ -160,6 +161,75 @@ pa_status pa_set_option(const char* name, int64_t value);
 pa_status pa_profile_enable(int32_t on);
 pa_status pa_profile_reset(void);
 pa_status pa_profile_read(const char* kernel_prefix, int32_t* launches, double* total_ms);
+
+/*
+ * ---------------------------------------------------------------------------
+ * KV page manager (Algorithm 1 Reserve; Sec. III-B "Paged KV-Manager"; Sec. I-A
+ * challenge 1: grow on demand, reclaim at once, share identical prefixes, all
+ * in constant time per page).
+ *
+ * A pa_pool is a HOST object that owns the bookkeeping of num_pages physical
+ * pages of page_size tokens: which pages are free, which sequence maps which
+ * logical block to which page, and how many sequences reference each page.  It
+ * never touches K/V data except in pa_pool_make_writable.  The free list is
+ * lock-free: never-used pages come from an atomic bump pointer, recycled pages
+ * from a tagged (ABA-safe) atomic stack, so reserving or releasing one page is
+ * O(1) and calls for DIFFERENT sequences may run concurrently from several host
+ * threads; calls for the SAME sequence must be serialised by the caller
+ * (pa_pool_share_prefix counts as a call for both of its sequences).
+ *
+ * device_table (optional, may be NULL): the int32 [max_seqs, max_blocks] block
+ * table in device memory that the attention entry points read.  Every call
+ * that changes a sequence's row enqueues a copy of the changed entries on
+ * `stream`, from a pinned staging ring that holds their values as of the call,
+ * so the table is current for work enqueued later on the same stream and work
+ * enqueued earlier still sees the earlier row.  Use ONE stream for all calls on
+ * a pool (the ring's reuse is ordered by events on that stream); a page that
+ * was released may be handed out again at once, which is safe for the same
+ * reason.  Entries of unmapped blocks are -1.  pa_pool_destroy waits for the
+ * device to go idle when a device table is attached.
+ * ---------------------------------------------------------------------------
+ */
+typedef struct pa_pool pa_pool;
+
+/* Creates a pool.  num_pages, max_seqs, max_blocks > 0; page_size a power of two.
+ * When device_table is given, all of its max_seqs * max_blocks entries are set to -1 (synchronously). */
+pa_status pa_pool_create(pa_pool** pool, int32_t num_pages, int32_t page_size, int32_t max_seqs,
+                         int32_t max_blocks, int32_t* device_table);
+pa_status pa_pool_destroy(pa_pool* pool);
+
+/* Growth policy of pa_pool_reserve.  PA_GROW_EXACT (default) is Algorithm 1 as printed: n = ceil(len / P).
+ * PA_GROW_POW2 is the power-of-two cache allocation the paper's memory measurements mention (Sec. IV,
+ * "Memory Utilization"): when a sequence must grow, its block count goes to the next power of two >= n
+ * (capped at max_blocks), so a sequence growing token by token touches the free list O(log n) times; if the pool
+ * runs short the call keeps what it could get as long as that is >= n. */
+enum { PA_GROW_EXACT = 0, PA_GROW_POW2 = 1 };
+pa_status pa_pool_set_growth(pa_pool* pool, int32_t policy);
+
+/* Algorithm 1, Reserve, incremental: makes sure sequence seq owns n = ceil(len / page_size) blocks, popping
+ * the missing ones from the free list (a sequence never shrinks here).  PA_ERR_OUT_OF_PAGES leaves the
+ * sequence as it was; PA_ERR_INVALID_ARG if n > max_blocks or seq is out of range. */
+pa_status pa_pool_reserve(pa_pool* pool, int32_t seq, int32_t len, void* stream);
+
+/* Drops every block of the sequence; pages whose reference count reaches zero return to the free list. */
+pa_status pa_pool_release(pa_pool* pool, int32_t seq, void* stream);
+
+/* Prefix sharing: dst (which must hold no blocks) maps the first floor(prefix_tokens / page_size) blocks of src,
+ * whole pages only, and their reference counts grow by one.  No data is copied. */
+pa_status pa_pool_share_prefix(pa_pool* pool, int32_t dst_seq, int32_t src_seq, int32_t prefix_tokens, void* stream);
+
+/* Copy-on-write: if the page holding `position` of seq is referenced by more than one sequence, seq gets a
+ * private copy (one page of K and of V is copied on `stream` inside the pools `cache` describes) and the shared
+ * page loses one reference.  A no-op for a private page.  Call before appending into a page that may be shared. */
+pa_status pa_pool_make_writable(pa_pool* pool, const pa_kv_cache_desc* cache, int32_t seq, int32_t position,
+                                void* stream);
+
+/* Introspection (host, no synchronisation): free pages; blocks of a sequence; copy of a sequence's row into
+ * host_row[0 .. capacity) (returns PA_ERR_INVALID_ARG if capacity is too small); references of a page. */
+int32_t   pa_pool_num_free(const pa_pool* pool);
+int32_t   pa_pool_num_blocks(const pa_pool* pool, int32_t seq);
+pa_status pa_pool_get_row(const pa_pool* pool, int32_t seq, int32_t* host_row, int32_t capacity);
+int32_t   pa_pool_refcount(const pa_pool* pool, int32_t page);
 
 #ifdef __cplusplus
 }

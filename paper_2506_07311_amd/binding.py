@@ -23,6 +23,8 @@ EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
     "paged_attention_prefill", "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
+    "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
+    "pa_pool_make_writable", "pa_pool_num_free", "pa_pool_num_blocks", "pa_pool_get_row", "pa_pool_refcount",
 )
 
 
@@ -219,3 +221,85 @@ def pa_profile_read(kernel_prefix: str) -> Tuple[int, float]:
     _check(load_library().pa_profile_read(kernel_prefix.encode(), ctypes.byref(n), ctypes.byref(ms)),
            "pa_profile_read")
     return n.value, ms.value
+
+
+# ---- KV page manager (host object; see the pa_pool_* block of include/pagedattn.h) ----------------------------
+
+class PoolHandle(ctypes.c_void_p):
+    """Opaque pa_pool*; remembers whether a device table is attached (then calls take the current stream)."""
+    on_device = False
+
+
+def pa_pool_create(num_pages: int, page_size: int, max_seqs: int, max_blocks: int,
+                   device_table: Optional[torch.Tensor] = None) -> PoolHandle:
+    """Returns the pool handle.  device_table: int32 [max_seqs, max_blocks] device tensor kept current by the pool,
+    or None for a host-only pool (no GPU needed)."""
+    if device_table is not None:
+        _i32(device_table, "device_table")
+        if tuple(device_table.shape) != (max_seqs, max_blocks):
+            raise PagedAttnError("device_table must have shape [max_seqs, max_blocks]")
+    handle = PoolHandle(0)
+    handle.on_device = device_table is not None
+    _check(load_library().pa_pool_create(ctypes.byref(handle), ctypes.c_int32(num_pages), ctypes.c_int32(page_size),
+                                         ctypes.c_int32(max_seqs), ctypes.c_int32(max_blocks), _p(device_table)),
+           "pa_pool_create")
+    return handle
+
+
+def pa_pool_destroy(pool) -> None:
+    _check(load_library().pa_pool_destroy(pool), "pa_pool_destroy")
+
+
+PA_GROW_EXACT, PA_GROW_POW2 = 0, 1
+
+
+def pa_pool_set_growth(pool, policy: int) -> None:
+    _check(load_library().pa_pool_set_growth(pool, ctypes.c_int32(policy)), "pa_pool_set_growth")
+
+
+def _pool_stream(pool, stream) -> ctypes.c_void_p:
+    return _stream(stream) if pool.on_device else ctypes.c_void_p(0)
+
+
+def pa_pool_reserve(pool, seq: int, length: int, *, stream=None) -> None:
+    _check(load_library().pa_pool_reserve(pool, ctypes.c_int32(seq), ctypes.c_int32(length),
+                                          _pool_stream(pool, stream)), "pa_pool_reserve")
+
+
+def pa_pool_release(pool, seq: int, *, stream=None) -> None:
+    _check(load_library().pa_pool_release(pool, ctypes.c_int32(seq), _pool_stream(pool, stream)),
+           "pa_pool_release")
+
+
+def pa_pool_share_prefix(pool, dst_seq: int, src_seq: int, prefix_tokens: int, *, stream=None) -> None:
+    _check(load_library().pa_pool_share_prefix(pool, ctypes.c_int32(dst_seq), ctypes.c_int32(src_seq),
+                                               ctypes.c_int32(prefix_tokens), _pool_stream(pool, stream)),
+           "pa_pool_share_prefix")
+
+
+def pa_pool_make_writable(pool, k_cache, v_cache, seq: int, position: int, *, head_major=False, stream=None) -> None:
+    desc = cache_desc(k_cache, v_cache, head_major)
+    _check(load_library().pa_pool_make_writable(pool, ctypes.byref(desc), ctypes.c_int32(seq),
+                                                ctypes.c_int32(position), _stream(stream)), "pa_pool_make_writable")
+
+
+def pa_pool_num_free(pool) -> int:
+    return load_library().pa_pool_num_free(pool)
+
+
+def pa_pool_num_blocks(pool, seq: int) -> int:
+    return load_library().pa_pool_num_blocks(pool, ctypes.c_int32(seq))
+
+
+def pa_pool_get_row(pool, seq: int):
+    """The sequence's mapped pages, in block order, as a list of ints."""
+    n = pa_pool_num_blocks(pool, seq)
+    if n < 0:
+        raise PagedAttnError("pa_pool_get_row: invalid sequence")
+    row = (ctypes.c_int32 * max(n, 1))()
+    _check(load_library().pa_pool_get_row(pool, ctypes.c_int32(seq), row, ctypes.c_int32(n)), "pa_pool_get_row")
+    return list(row[:n])
+
+
+def pa_pool_refcount(pool, page: int) -> int:
+    return load_library().pa_pool_refcount(pool, ctypes.c_int32(page))

@@ -292,7 +292,8 @@ const char* pa_status_string(pa_status status)
         case PA_ERR_INVALID_ARG: return "invalid argument";
         case PA_ERR_UNSUPPORTED: return "unsupported dtype, shape or alignment";
         case PA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
-        case PA_ERR_HIP: return "HIP launch failed";
+        case PA_ERR_HIP: return "HIP call failed";
+        case PA_ERR_OUT_OF_PAGES: return "page pool exhausted";
     }
     return "unknown status";
 }

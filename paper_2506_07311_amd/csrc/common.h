@@ -81,6 +81,8 @@ pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, 
                            const int32_t* seq_lens, const int32_t* cu_seq_lens, int32_t batch, int32_t max_blocks,
                            int32_t max_seq_len, hipStream_t stream);
 
+pa_status launch_kv_copy_page(const pa_kv_cache_desc* c, int32_t src_page, int32_t dst_page, hipStream_t stream);
+
 struct AttnArgs {
     CacheView cache;
     pa_dtype dtype;

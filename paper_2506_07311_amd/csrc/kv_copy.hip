@@ -63,6 +63,22 @@ __global__ __launch_bounds__(kThreads) void paged_kv_gather_kernel(
         out_v[dst] = v_cache[src];
 }
 
+// Copy of one physical page (K and V) onto another, for copy-on-write of a shared page.
+__global__ __launch_bounds__(kThreads) void paged_kv_copy_page_kernel(
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int64_t src_page, int64_t dst_page, int32_t page_size,
+    int32_t vec_per_head, int32_t num_kv_heads, int64_t page_stride_v, int64_t token_stride_v, int64_t head_stride_v)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // over (slot, head, vec)
+    if (idx >= (int64_t)page_size * num_kv_heads * vec_per_head) return;
+    const int32_t vec = (int32_t)(idx % vec_per_head);
+    const int64_t th = idx / vec_per_head;
+    const int32_t h = (int32_t)(th % num_kv_heads);
+    const int32_t o = (int32_t)(th / num_kv_heads);
+    const int64_t in_page = (int64_t)o * token_stride_v + (int64_t)h * head_stride_v + vec;
+    uint4* pool = blockIdx.y == 0 ? k_cache : v_cache;
+    pool[dst_page * page_stride_v + in_page] = pool[src_page * page_stride_v + in_page];
+}
+
 inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
 
 }  // namespace
@@ -103,6 +119,24 @@ pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, 
                        (const uint4*)c->k_cache, (const uint4*)c->v_cache, (uint4*)out_k, (uint4*)out_v, block_table,
                        seq_lens, cu_seq_lens, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
                        c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
+    return launch_status();
+}
+
+pa_status launch_kv_copy_page(const pa_kv_cache_desc* c, int32_t src_page, int32_t dst_page, hipStream_t stream)
+{
+    const int eb = elem_bytes(c->dtype);
+    const int32_t epv = 16 / eb;
+    if (c->head_dim % epv || c->page_stride % epv || c->token_stride % epv || c->head_stride % epv)
+        return PA_ERR_UNSUPPORTED;
+    const int32_t vec_per_head = c->head_dim / epv;
+    const int64_t total = (int64_t)c->page_size * c->num_kv_heads * vec_per_head;
+    const int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (src_page < 0 || dst_page < 0 || src_page >= c->num_pages || dst_page >= c->num_pages) return PA_ERR_INVALID_ARG;
+    ProfileScope prof("paged_kv_copy_page_kernel", stream);
+    hipLaunchKernelGGL(paged_kv_copy_page_kernel, dim3((uint32_t)blocks, 2, 1), dim3(kThreads), 0, stream,
+                       (uint4*)c->k_cache, (uint4*)c->v_cache, (int64_t)src_page, (int64_t)dst_page, c->page_size,
+                       vec_per_head, c->num_kv_heads, c->page_stride / epv, c->token_stride / epv,
+                       c->head_stride / epv);
     return launch_status();
 }
 
