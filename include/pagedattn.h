@@ -130,6 +130,11 @@ pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, v
  * q, out : [total_q, Hq, d]; lse : NULL or float[total_q, Hq].  max_q_len :
  * host upper bound of q_len_s.  Other arguments as for decode (workspace sized
  * with this call's total_q).
+ * q_len_s may be anything from 0 to seq_lens[s] and differ per sequence: a
+ * chunk of a long prompt on top of cached context, decode rows (q_len 1) and
+ * whole prompts can share one call (the jagged batch of Sec. III-B: sequence
+ * ids are implied by the prefix sums).  A call with few query rows over a long
+ * context is cut along the context and merged through the workspace.
  */
 pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
                                   const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len,
@@ -145,6 +150,11 @@ const char* pa_status_string(pa_status status);
  *   "decode_chunk_tokens"  context tokens per split-KV workgroup of the portable kernel (0 = heuristic)
  *   "decode_workgroups"    workgroups the MFMA decode kernel spreads the batch's key tiles over
  *                          (0 = one per compute unit)
+ *   "prefill_chunk_tokens" context tokens per workgroup of the MFMA prefill kernel (0 = heuristic: no split
+ *                          unless the call has too few query rows to fill the machine); size the workspace
+ *                          AFTER setting it
+ *   "no_small_q_route"     1 = the prefill entry point keeps sequences with few queries (q_len * G <= 16) on
+ *                          the prefill kernel instead of handing them to the decode kernel
  *   "force_generic"        1 = always take the portable VALU kernels
  * Returns PA_ERR_INVALID_ARG for an unknown name or a value out of range.
  */

@@ -16,6 +16,8 @@ struct Options {
     int64_t decode_chunk_tokens = 0;
     int64_t decode_workgroups = 0;
     int64_t force_generic = 0;
+    int64_t prefill_chunk_tokens = 0;
+    int64_t no_small_q_route = 0;
 } g_opt;
 
 // Compute units of the current device (the tile-stream decode launches one workgroup per CU by default).
@@ -92,6 +94,60 @@ SplitPlan plan_decode(int32_t batch, int32_t max_seq_len, int32_t page_size)
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Context split of the MFMA prefill kernel.  The kernel gets one workgroup per (128-row tile, head group); the
+// host knows only total_q and batch, so it bounds the live tiles by total_q * pack / 128 + batch.  When that fills
+// the machine there is no split; a call with few query rows over a long context (a chunk of a long prompt, a
+// mixed batch that is mostly decode rows) is cut along the context into chunks of at least kPrefillMinChunk
+// tokens until about kPrefillTargetWGs work items exist.  A pure function of its arguments: the workspace size is
+// computed from the same rule with the largest packing.
+constexpr int32_t kPrefillMinChunk = 1024;
+constexpr int64_t kPrefillTargetWGs = 1024;
+constexpr int64_t kPrefillFullWGs = 512;
+
+SplitPlan plan_prefill(int32_t batch, int32_t num_q_heads, int32_t log2_pack, int32_t total_q, int32_t max_seq_len,
+                       int32_t page_size)
+{
+    SplitPlan p;
+    p.chunk = max_seq_len > 0 ? max_seq_len : 1;
+    p.nsplit = 1;
+    if (g_opt.prefill_chunk_tokens > 0) {
+        const int64_t unit = page_size > 64 ? page_size : 64;
+        int64_t chunk = (g_opt.prefill_chunk_tokens + unit - 1) / unit * unit;
+        while (((int64_t)max_seq_len + chunk - 1) / chunk > kMaxSplits) chunk *= 2;
+        if (chunk < max_seq_len) {
+            p.chunk = (int32_t)chunk;
+            p.nsplit = (int32_t)(((int64_t)max_seq_len + chunk - 1) / chunk);
+        }
+        return p;
+    }
+    const int64_t wgs = (((int64_t)total_q << log2_pack) / 128 + batch) * (num_q_heads >> log2_pack);
+    if (wgs >= kPrefillFullWGs || max_seq_len < 2 * kPrefillMinChunk) return p;
+    int64_t n = (kPrefillTargetWGs + wgs - 1) / wgs;
+    if (n > max_seq_len / kPrefillMinChunk) n = max_seq_len / kPrefillMinChunk;
+    if (n > kMaxSplits) n = kMaxSplits;
+    if (n < 2) return p;
+    const int64_t unit = page_size > 64 ? page_size : 64;
+    int64_t chunk = ((int64_t)max_seq_len + n - 1) / n;
+    chunk = (chunk + unit - 1) / unit * unit;
+    if (chunk >= max_seq_len) return p;
+    p.chunk = (int32_t)chunk;
+    p.nsplit = (int32_t)(((int64_t)max_seq_len + chunk - 1) / chunk);
+    return p;
+}
+
+// Largest number of chunks plan_prefill can choose for these sizes, whatever the packing and page size.
+int32_t prefill_nsplit_bound(int32_t batch, int32_t num_q_heads, int32_t total_q, int32_t max_seq_len)
+{
+    if (g_opt.prefill_chunk_tokens > 0) return kMaxSplits;
+    int32_t best = 1;
+    for (int32_t lg = 0; lg <= 4; ++lg) {
+        if (num_q_heads % (1 << lg)) break;
+        const SplitPlan p = plan_prefill(batch, num_q_heads, lg, total_q, max_seq_len, 1);
+        if (p.nsplit > best) best = p.nsplit;
+    }
+    return best;
+}
+
 // Workgroups along the tile stream for the MFMA decode kernel: one per compute unit (per KV-head group), but
 // never so many that a workgroup gets fewer than two 32-key tiles of the longest possible stream.
 int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups)
@@ -110,6 +166,18 @@ size_t stream_workspace_bytes(int32_t batch, int32_t hq, int32_t d, int32_t wgs)
 {
     const size_t parts = (size_t)wgs + batch;
     return align256(parts * hq * d * sizeof(float)) + align256(parts * hq * sizeof(float)) +
+           2 * align256((size_t)batch * sizeof(int32_t));
+}
+
+// Workgroups of the decode kernel when it runs the few-query sequences of a prefill call; its partials there take
+// 16 rows per KV head, so the count is kept at one per compute unit of the largest part.
+constexpr int32_t kSmallRouteMaxWGs = 256;
+
+size_t small_route_workspace_bytes(int32_t batch, int32_t hq, int32_t d)
+{
+    // at most hq KV heads (group size 1), 16 rows each
+    const size_t rows = ((size_t)kSmallRouteMaxWGs + batch) * hq * 16;
+    return align256(rows * d * sizeof(float)) + align256(rows * sizeof(float)) +
            2 * align256((size_t)batch * sizeof(int32_t));
 }
 
@@ -168,6 +236,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.stream_split = 0;
     a.num_wgs = 0;
     a.seg_first = a.seg_last = nullptr;
+    a.skip_small = 0;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     if (decode) {
@@ -193,7 +262,49 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         if (a.plan.nsplit > 1) st = launch_merge(a, s);
         return st;
     }
-    if (!g_opt.force_generic && prefill_mfma_supported(a)) return launch_prefill_mfma(a, s);
+    if (!g_opt.force_generic && prefill_mfma_supported(a)) {
+        // Jagged batch: sequences with few queries (q_len * G <= 16: decode rows, a few speculative tokens) are
+        // bound by streaming their context once, which the decode kernel's equal-work tile stream does best; the
+        // others go to the prefill kernel.  Both kernels decide per sequence from cu_q_lens on the device; the
+        // host only skips a launch that cannot find work.
+        const int32_t G = num_q_heads / cache->num_kv_heads;
+        const bool uniform_q = (int64_t)batch * max_q_len == total_q;      // every sequence has max_q_len queries
+        const bool may_have_small = !g_opt.no_small_q_route && decode_mfma_supported(a) &&
+                                    !(uniform_q && (int64_t)max_q_len * G > 16);
+        const bool may_have_large = (int64_t)max_q_len * G > 16 || !may_have_small;
+        char* p = reinterpret_cast<char*>(workspace);
+        if (may_have_large) {
+            AttnArgs b = a;
+            b.skip_small = may_have_small ? 1 : 0;
+            b.plan = plan_prefill(batch, num_q_heads, prefill_mfma_log2_pack(num_q_heads, cache->num_kv_heads),
+                                  total_q, max_seq_len, cache->page_size);
+            b.part_o = reinterpret_cast<float*>(p);
+            b.part_lse = reinterpret_cast<float*>(p + part_o_bytes(total_q, num_q_heads, cache->head_dim, b.plan.nsplit));
+            st = launch_prefill_mfma(b, s);
+            if (st != PA_OK) return st;
+        }
+        if (may_have_small) {
+            const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
+            if (np > 1) p += part_o_bytes(total_q, num_q_heads, cache->head_dim, np) + part_lse_bytes(total_q, num_q_heads, np);
+            AttnArgs b = a;
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads);
+            b.stream_split = 1;
+            b.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
+            if (b.num_wgs > kSmallRouteMaxWGs) b.num_wgs = kSmallRouteMaxWGs;
+            const size_t rows = ((size_t)b.num_wgs + batch) * cache->num_kv_heads * 16;
+            b.part_o = reinterpret_cast<float*>(p);
+            p += align256(rows * cache->head_dim * sizeof(float));
+            b.part_lse = reinterpret_cast<float*>(p);
+            p += align256(rows * sizeof(float));
+            b.seg_first = reinterpret_cast<int32_t*>(p);
+            p += align256((size_t)batch * sizeof(int32_t));
+            b.seg_last = reinterpret_cast<int32_t*>(p);
+            st = launch_decode_mfma(b, s);
+            if (st != PA_OK) return st;
+            st = launch_merge(b, s);
+        }
+        return st;
+    }
     return launch_attention_generic(a, s);
 }
 
@@ -258,12 +369,19 @@ size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32
                                        int32_t max_seq_len)
 {
     if (batch <= 0 || num_q_heads <= 0 || head_dim <= 0 || total_q <= 0) return 256;
-    // Only the decode entry point splits the context; the prefill kernels write their outputs directly.
-    if (total_q > batch) return 256;
+    // prefill entry point: partials of the context split, when the sizes make it split
+    const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
+    size_t need = np > 1 ? part_o_bytes(total_q, num_q_heads, head_dim, np) + part_lse_bytes(total_q, num_q_heads, np)
+                         : 0;
+    need += small_route_workspace_bytes(batch, num_q_heads, head_dim);
+    if (total_q > batch) return need;
+    // decode entry point
     const int32_t ns = nsplit_bound(max_seq_len);
     const size_t chunked = part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
     const size_t stream = stream_workspace_bytes(batch, num_q_heads, head_dim, kMaxDecodeWGs);
-    return chunked > stream ? chunked : stream;
+    if (chunked > need) need = chunked;
+    if (stream > need) need = stream;
+    return need;
 }
 
 pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -309,6 +427,16 @@ pa_status pa_set_option(const char* name, int64_t value)
     if (!strcmp(name, "decode_workgroups")) {
         if (value < 0 || value > kMaxDecodeWGs) return PA_ERR_INVALID_ARG;
         g_opt.decode_workgroups = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "prefill_chunk_tokens")) {
+        if (value < 0 || value > (1 << 24)) return PA_ERR_INVALID_ARG;
+        g_opt.prefill_chunk_tokens = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "no_small_q_route")) {
+        if (value != 0 && value != 1) return PA_ERR_INVALID_ARG;
+        g_opt.no_small_q_route = value;
         return PA_OK;
     }
     if (!strcmp(name, "force_generic")) {

@@ -109,6 +109,7 @@ struct AttnArgs {
     int32_t num_wgs;
     int32_t* seg_first;
     int32_t* seg_last;
+    int32_t skip_small;      // prefill kernel: leave sequences with q_len * G <= 16 to the decode kernel
 };
 
 // Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.
@@ -119,6 +120,7 @@ int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads);
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
 // MFMA prefill kernel: bf16, head_dim 128.
 bool prefill_mfma_supported(const AttnArgs& a);
+int32_t prefill_mfma_log2_pack(int32_t num_q_heads, int32_t num_kv_heads);
 pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream);
 // LSE merge of the split partials into out / lse.
 pa_status launch_merge(const AttnArgs& a, hipStream_t stream);

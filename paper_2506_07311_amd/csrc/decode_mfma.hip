@@ -113,8 +113,11 @@ struct State {
     float l;       // this lane's share of the running sum
 };
 
+// lim = first key this lane's row may not see (the segment end, or less under a per-row causal bound);
+// mask_from <= every lane's lim, wave-uniform: tiles that end at or before it need no mask.
+template <bool RAGGED>
 __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf16x8 (&qf)[4], float sc, int32_t t0,
-                                             int32_t c1, int32_t quad)
+                                             int32_t lim, int32_t mask_from, int32_t quad)
 {
     f32x4 s[2];
 #pragma unroll
@@ -126,27 +129,29 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
                                                             0, 0);
     }
     // s[mt][i] is the score of key t0 + 16*mt + 4*quad + i for head lane%16
-    const bool partial = t0 + kTileKeys > c1;    // wave-uniform
+    const bool partial = t0 + kTileKeys > mask_from;    // wave-uniform
     float tmax = -INFINITY;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float x = s[mt][i] * sc;
-            if (partial && t0 + 16 * mt + 4 * quad + i >= c1) x = -INFINITY;   // mask by selection
+            if (partial && t0 + 16 * mt + 4 * quad + i >= lim) x = -INFINITY;   // mask by selection
             s[mt][i] = x;
             tmax = fmaxf(tmax, x);
         }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(st.m, tmax);       // finite: every tile holds at least one valid key
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    // decode: finite, every tile holds at least one valid key; a row under a causal bound may have seen none yet
+    const float m_new = fmaxf(st.m, tmax);
+    const float m_use = (RAGGED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
     float psum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float p = __builtin_amdgcn_exp2f(s[mt][i] - m_new);
+            const float p = __builtin_amdgcn_exp2f(s[mt][i] - m_use);
             s[mt][i] = p;
             psum += p;
         }
@@ -196,26 +201,44 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ int32_t tiles_of(int32_t len) { return (len + kTileKeys - 1) / kTileKeys; }
 
+// Tiles of sequence i in the stream.  RAGGED (called from the prefill entry point): only sequences whose
+// q_len * G rows fit the 16 columns of the matrix instruction take part; the others hold no tiles here and are
+// left to the prefill kernel.
+template <bool RAGGED>
+__device__ __forceinline__ int32_t seq_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                             int32_t G, int32_t i)
+{
+    if (RAGGED) {
+        const int32_t q_len = cu_q_lens[i + 1] - cu_q_lens[i];
+        if (q_len < 1 || q_len * G > 16) return 0;
+    }
+    return tiles_of(seq_lens[i]);
+}
+
 // Sum of tiles over the batch; every lane returns the same value.
-__device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_lens, int32_t batch, int lane)
+template <bool RAGGED>
+__device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                               int32_t G, int32_t batch, int lane)
 {
     int32_t n = 0;
-    for (int32_t i = lane; i < batch; i += 64) n += tiles_of(seq_lens[i]);
+    for (int32_t i = lane; i < batch; i += 64) n += seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, i);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
     return n;
 }
 
 // Sequence that holds global tile g (0 <= g < total) and the number of tiles before that sequence.
-__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens, int32_t batch, int32_t g, int lane,
-                                            int32_t& seq, int32_t& tiles_before)
+template <bool RAGGED>
+__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                            int32_t G, int32_t batch, int32_t g, int lane, int32_t& seq,
+                                            int32_t& tiles_before)
 {
     int32_t base = 0;
     seq = batch;
     tiles_before = 0;
     for (int32_t blk = 0; blk < batch; blk += 64) {
         const int32_t idx = blk + lane;
-        const int32_t n = idx < batch ? tiles_of(seq_lens[idx]) : 0;
+        const int32_t n = idx < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, idx) : 0;
         int32_t inc = n;                                   // inclusive scan over the 64 lanes
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -234,12 +257,16 @@ __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens
     }
 }
 
-template <int NW, bool UNIFORM>
+// RAGGED: launched from the prefill entry point for the sequences with few queries (q_len * G <= 16): the 16
+// columns are (query, head) pairs, column = query * G + head, each with its own causal bound; q / out / lse rows
+// come from cu_q_lens; partials are 16 rows per KV head.
+template <int NW, bool UNIFORM, bool RAGGED>
 __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch,
     int32_t num_q_heads, int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse,
-    int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last)
+    int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last, const int32_t* __restrict__ cu_q_lens,
+    int32_t causal)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -254,7 +281,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     int32_t total, g, g_end, s, before;
     if (batch <= 64) {
         // one read of the lengths serves both the total and the search for this workgroup's first sequence
-        const int32_t n = lane < batch ? tiles_of(seq_lens[lane]) : 0;
+        const int32_t n = lane < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, lane) : 0;
         int32_t inc = n;                                   // inclusive scan over the 64 lanes
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -270,12 +297,12 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         s = __ffsll((unsigned long long)hit) - 1;
         before = __shfl(inc, s, 64) - __shfl(n, s, 64);
     } else {
-        total = total_tiles(seq_lens, batch, lane);
+        total = total_tiles<RAGGED>(seq_lens, cu_q_lens, G, batch, lane);
         const int32_t nwg = min((int32_t)gridDim.x, total);
         if (w >= nwg) return;
         g = (int32_t)(((int64_t)w * total) / nwg);
         g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
-        locate_tile(seq_lens, batch, g, lane, s, before);
+        locate_tile<RAGGED>(seq_lens, cu_q_lens, G, batch, g, lane, s, before);
     }
     s = __builtin_amdgcn_readfirstlane(s);
     before = __builtin_amdgcn_readfirstlane(before);
@@ -296,14 +323,25 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     while (g < g_end) {
         // segment: tiles [t_begin, t_end) of sequence s
         const int32_t len = seq_lens[s];
-        const int32_t nt = tiles_of(len);
-        if (nt == 0) { ++s; continue; }                    // empty sequences hold no tiles
+        const int32_t nt = seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, s);
+        if (nt == 0) { ++s; continue; }                    // sequences without tiles in this stream
         const int32_t t_begin = g - before;
         const int32_t t_end = min(nt, g_end - before);
         const int32_t c0 = t_begin * kTileKeys;
         const int32_t c1 = min(len, t_end * kTileKeys);
-        const int32_t h = kvh * G + r16;                   // this lane's query head (valid if r16 < G)
-        const int64_t o_idx = (int64_t)s * num_q_heads + h;
+        // this lane's column: query qi of the sequence's q_len, head h (valid if r16 < rows)
+        int32_t rows = G, qi = 0, q_row = s, lim = c1;
+        if (RAGGED) {
+            const int32_t q_begin = cu_q_lens[s];
+            const int32_t q_len = cu_q_lens[s + 1] - q_begin;
+            rows = q_len * G;
+            qi = min(r16, rows - 1) / G;
+            q_row = q_begin + qi;
+            if (causal) lim = min(c1, len - q_len + qi + 1);   // keys 0 .. len - q_len + qi
+        }
+        const int32_t mask_from = RAGGED ? c1 - 16 : c1;   // q_len <= 16: no bound lies further below the end
+        const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16);
+        const int64_t o_idx = (int64_t)q_row * num_q_heads + h;
         a.table = block_table + (int64_t)s * max_blocks;
 
         // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
@@ -312,7 +350,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             uint4 v = uint4{0, 0, 0, 0};
-            if (r16 < G) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
+            if (r16 < rows) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
             qf[ks] = __builtin_bit_cast(bf16x8, v);
         }
         State st;
@@ -327,19 +365,20 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
             if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
-            compute_tile(st, ta, qf, sc, t0, c1, quad);
+            compute_tile<RAGGED>(st, ta, qf, sc, t0, lim, mask_from, quad);
             if (t1 >= c1) break;
             if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
-            compute_tile(st, tb, qf, sc, t1, c1, quad);
+            compute_tile<RAGGED>(st, tb, qf, sc, t1, lim, mask_from, quad);
         }
 
         float l = st.l;
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         const bool whole = t_begin == 0 && t_end == nt;    // the sequence lies inside this workgroup
-        if (r16 < G) {
-            const float inv = 1.f / l;
-            const float lse_nat = (st.m + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
+        if (r16 < rows) {
+            // l == 0: a row whose causal bound lies before this segment (RAGGED only)
+            const float inv = (!RAGGED || l > 0.f) ? 1.f / l : 0.f;
+            const float lse_nat = (!RAGGED || l > 0.f) ? (st.m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
             if (whole) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -352,7 +391,8 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
                 }
                 if (lse && quad == 0) lse[o_idx] = lse_nat;
             } else {
-                const int64_t p_idx = (int64_t)(w + s) * num_q_heads + h;
+                const int64_t p_idx = RAGGED ? ((int64_t)(w + s) * cache.num_kv_heads + kvh) * 16 + r16
+                                             : (int64_t)(w + s) * num_q_heads + h;
                 float* po = part_o + p_idx * kD + 32 * quad;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -379,10 +419,12 @@ void launch_nw(const AttnArgs& a, hipStream_t stream)
 {
     const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), 1);
     const bool uniform = a.cache.page_size >= 16;
-    auto kern = uniform ? paged_decode_mfma_kernel<NW, true> : paged_decode_mfma_kernel<NW, false>;
+    auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true> : paged_decode_mfma_kernel<NW, false, true>)
+                            : (uniform ? paged_decode_mfma_kernel<NW, true, false>
+                                       : paged_decode_mfma_kernel<NW, false, false>);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                        a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.part_o,
-                       a.part_lse, a.seg_first, a.seg_last);
+                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal);
 }
 
 }  // namespace

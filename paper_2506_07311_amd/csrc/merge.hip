@@ -47,36 +47,50 @@ __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
 // with independent loads (eight in flight), so the kernel costs a few memory latencies, not one per partial.
 constexpr int kMergeThreads = 128;
 
-template <bool BF16>
+// RAGGED (the few-query sequences of a prefill call): one workgroup per (sequence, KV head, column); column
+// c of the 16 is query c / G, head c % G of the group; partials are 16 rows per KV head; sequences that did not
+// take that path (q_len * G > 16) are skipped.
+template <bool BF16, bool RAGGED>
 __global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
     float* __restrict__ lse, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ seg_first,
-    const int32_t* __restrict__ seg_last, int32_t num_q_heads, int32_t d)
+    const int32_t* __restrict__ seg_last, int32_t num_q_heads, int32_t d, const int32_t* __restrict__ cu_q_lens,
+    int32_t num_kv_heads)
 {
     __shared__ float w_s[kMaxDecodeWGs + 1];
     __shared__ float red[4];
-    const int32_t s = blockIdx.x / num_q_heads;
-    const int32_t h = blockIdx.x % num_q_heads;
-    const int64_t o_idx = blockIdx.x;
+    const int32_t rows = RAGGED ? num_kv_heads * 16 : num_q_heads;   // partial rows per (workgroup, sequence)
+    const int32_t s = blockIdx.x / rows;
+    const int32_t h = blockIdx.x % rows;
+    int64_t o_idx = blockIdx.x;
+    if (RAGGED) {
+        const int32_t G = num_q_heads / num_kv_heads;
+        const int32_t q_len = cu_q_lens[s + 1] - cu_q_lens[s];
+        const int32_t col = h & 15;
+        if (q_len < 1 || q_len * G > 16 || col >= q_len * G) return;
+        o_idx = (int64_t)(cu_q_lens[s] + col / G) * num_q_heads + (h >> 4) * G + col % G;
+    }
     const int tid = threadIdx.x;
     const int32_t len = seq_lens[s];
     const int32_t first = seg_first[s];
     const int32_t last = seg_last[s];
     if (len > 0 && first < 0) return;                  // already final
     const int32_t n = len > 0 ? last - first + 1 : 0;
-    const int64_t p0 = (int64_t)(first + s) * num_q_heads + h;     // partial c sits num_q_heads rows further each
+    const int64_t p0 = (int64_t)(first + s) * rows + h;            // partial c sits `rows` rows further each
 
     // weights exp(lse_c - M) into LDS
     float mx = -INFINITY;
     for (int32_t c = tid; c < n; c += kMergeThreads) {
-        const float v = part_lse[p0 + (int64_t)c * num_q_heads];
+        const float v = part_lse[p0 + (int64_t)c * rows];
         w_s[c] = v;
         mx = fmaxf(mx, v);
     }
     mx = wave_max(mx);
     if ((tid & 63) == 0) red[tid >> 6] = mx;
     __syncthreads();
-    const float M = fmaxf(red[0], red[1]);
+    float M = fmaxf(red[0], red[1]);
+    const bool no_keys = M == -INFINITY;               // RAGGED: a row whose causal bound excludes every key
+    if (no_keys) M = 0.f;
     float ws = 0.f;
     for (int32_t c = tid; c < n; c += kMergeThreads) {
         const float wgt = expf(w_s[c] - M);
@@ -90,7 +104,7 @@ __global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_ke
 
     for (int e = tid; e < d; e += kMergeThreads) {
         const float* po = part_o + p0 * d + e;
-        const int64_t step = (int64_t)num_q_heads * d;
+        const int64_t step = (int64_t)rows * d;
         float acc = 0.f;
         int32_t c = 0;
         for (; c + 8 <= n; c += 8) {
@@ -101,13 +115,13 @@ __global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_ke
             for (int u = 0; u < 8; ++u) acc = fmaf(w_s[c + u], v[u], acc);
         }
         for (; c < n; ++c) acc = fmaf(w_s[c], po[(int64_t)c * step], acc);
-        const float r = n > 0 ? acc / wsum : 0.f;
+        const float r = (n > 0 && !no_keys) ? acc / wsum : 0.f;
         if (BF16)
             reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
         else
             reinterpret_cast<float*>(out)[o_idx * d + e] = r;
     }
-    if (lse && tid == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
+    if (lse && tid == 0) lse[o_idx] = (n > 0 && !no_keys) ? M + logf(wsum) : -INFINITY;
 }
 
 }  // namespace
@@ -118,15 +132,23 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     const int threads = ((a.cache.head_dim + 63) / 64) * 64;
     ProfileScope prof("paged_attention_merge_kernel", stream);
+    if (a.stream_split && a.cu_q_lens) {   // few-query sequences of a prefill call (bf16 only)
+        const int64_t rblocks = (int64_t)a.batch * a.cache.num_kv_heads * 16;
+        if (rblocks > 0x7fffffffLL || a.dtype != PA_DTYPE_BF16) return PA_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((paged_attention_merge_stream_kernel<true, true>), dim3((uint32_t)rblocks),
+                           dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first,
+                           a.seg_last, a.num_q_heads, a.cache.head_dim, a.cu_q_lens, a.cache.num_kv_heads);
+        return launch_status();
+    }
     if (a.stream_split) {
         if (a.dtype == PA_DTYPE_BF16)
-            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<true>, dim3((uint32_t)blocks), dim3(kMergeThreads), 0,
-                               stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
-                               a.num_q_heads, a.cache.head_dim);
+            hipLaunchKernelGGL((paged_attention_merge_stream_kernel<true, false>), dim3((uint32_t)blocks),
+                               dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens,
+                               a.seg_first, a.seg_last, a.num_q_heads, a.cache.head_dim, nullptr, a.cache.num_kv_heads);
         else
-            hipLaunchKernelGGL(paged_attention_merge_stream_kernel<false>, dim3((uint32_t)blocks), dim3(kMergeThreads), 0,
-                               stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first, a.seg_last,
-                               a.num_q_heads, a.cache.head_dim);
+            hipLaunchKernelGGL((paged_attention_merge_stream_kernel<false, false>), dim3((uint32_t)blocks),
+                               dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens,
+                               a.seg_first, a.seg_last, a.num_q_heads, a.cache.head_dim, nullptr, a.cache.num_kv_heads);
         return launch_status();
     }
     if (a.dtype == PA_DTYPE_BF16)

@@ -2,8 +2,13 @@
 //
 // Prefill is a dense contraction (about 590 flop per byte at 2048 tokens), so it runs on the matrix cores
 // with v_mfma_f32_32x32x16_bf16 in the flash-attention arrangement: one workgroup of 4 waves owns 128
-// consecutive queries of one (sequence, query head); wave w owns 32 of them.  The context is walked in
-// tiles of 64 keys.  A tile's K and V rows are fetched page by page through the block table (Algorithm 1:
+// consecutive ROWS of one (sequence, KV head); wave w owns 32 of them.  A row is a (query, query head) pair:
+// the G query heads that share the KV head are packed next to each other (row = query * G + head; G a power of
+// two up to 16, else one head per workgroup), so K and V are streamed once per KV head whatever G is and a
+// call with few queries per sequence (decode rows, speculative tokens, short chunks) still fills the tile G
+// times better.  "Query" below means such a row.  The context is walked in tiles of 64 keys; the launch may
+// cut it into chunks (one workgroup per chunk, partials merged by the split-KV merge kernel) when the call has
+// too few rows to fill the machine.  A tile's K and V rows are fetched page by page through the block table (Algorithm 1:
 // page = block_table[s][j >> log2 P], slot = j & (P-1)) and written STRAIGHT INTO LDS by the load unit
 // (global_load_lds_dwordx4: 16 bytes per lane, a wave fills 4 consecutive 256-byte rows per instruction), one
 // tile ahead of the one being computed, into the other of two 32 KiB buffers -- no staging registers, no LDS
@@ -65,6 +70,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // ---------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
+
+// How the launch cuts the work: head packing and the context split.
+struct PrefillPlan {
+    int32_t log2_pack;    // query heads of one KV head packed into a row tile (1 << log2_pack divides the group size)
+    int32_t chunk;        // context tokens per workgroup (multiple of 64 and of the page size when nsplit > 1)
+    int32_t nsplit;       // chunks along the grid; > 1: partials go to part_o / part_lse for the merge kernel
+    int32_t skip_small;   // 1: sequences with q_len * G <= 16 are computed by the decode kernel, not here
+    float* part_o;        // [total_q, Hq, nsplit, 128]
+    float* part_lse;      // [total_q, Hq, nsplit]
+};
 
 struct PageIds {
     int32_t p0, p1, p2, p3;
@@ -293,47 +308,63 @@ __device__ __forceinline__ void prefill_body(
     char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
-    float scale, int32_t causal)
+    float scale, int32_t causal, const PrefillPlan& plan)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int ql = lane & 31, hh = lane >> 5;
-    // Workgroups are dispatched in blockIdx.x order: the query-tile index is the slowest-varying part and runs
-    // backwards, so the whole grid is handed out heaviest (latest causal tiles) first.
-    const int32_t hb = num_q_heads * batch;
-    const int32_t tile = num_tiles - 1 - (int32_t)(blockIdx.x / hb);
+    // Rows of a workgroup's 128-row tile are (query, head) pairs: the 2^log2_pack query heads packed into a tile
+    // share one KV head, row r of a sequence is query r >> log2_pack, packed head r & (pack - 1).
+    const int32_t lg = plan.log2_pack;
+    const int32_t heads = num_q_heads >> lg;                 // head groups along the grid
+    // Workgroups are dispatched in blockIdx.x order: the row-tile index is the slowest-varying part and runs
+    // backwards, so the whole grid is handed out heaviest (latest causal tiles) first; the context chunks of a
+    // tile follow each other.
+    const int32_t hb = heads * batch;
+    const int32_t slow = (int32_t)(blockIdx.x / hb);
+    const int32_t tile = num_tiles - 1 - slow / plan.nsplit;
+    const int32_t split = slow % plan.nsplit;
     const int32_t rest = blockIdx.x % hb;
-    const int32_t s = rest / num_q_heads;
-    const int32_t h = rest % num_q_heads;
+    const int32_t s = rest / heads;
+    const int32_t hg = rest % heads;
     const int32_t q_begin = cu_q_lens[s];
     const int32_t q_len = cu_q_lens[s + 1] - q_begin;
+    const int32_t n_rows = q_len << lg;
     const int32_t m0 = tile * kBM;
-    if (m0 >= q_len) return;
+    if (m0 >= n_rows) return;
+    if (plan.skip_small && q_len * (num_q_heads / cache.num_kv_heads) <= 16) return;
     const int32_t len = seq_lens[s];
-    // workgroup-wide key range; it also selects which instantiation handles this query tile
-    const int32_t q_last = min(m0 + kBM, q_len) - 1;
+    // workgroup-wide key range; it also selects which instantiation handles this tile
+    const int32_t q_last = (min(m0 + kBM, n_rows) - 1) >> lg;
     int32_t nk_wg = len;
     if (causal) nk_wg = min(len, len - q_len + q_last + 1);
     nk_wg = max(nk_wg, 0);
     if ((nk_wg <= kPreciseKeys) != PRECISE) return;         // the other instantiation handles this tile
+    // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
+    // reads only the chunks that hold keys of a row)
+    const int32_t k_begin = split * plan.chunk;
+    const int32_t k_end = min(nk_wg, k_begin + plan.chunk);
+    if (plan.nsplit > 1 && k_begin >= nk_wg) return;
 
     const int32_t G = num_q_heads / cache.num_kv_heads;
-    const int32_t kvh = h / G;
     const int32_t* table = block_table + (int64_t)s * max_blocks;
 
-    // this lane's query, its position and key bound
-    const int32_t qi = m0 + 32 * wave + ql;
-    const bool q_valid = qi < q_len;
-    const int32_t qi_c = min(qi, q_len - 1);
+    // this lane's row: query, head, and key bound
+    const int32_t r_lane = m0 + 32 * wave + ql;
+    const bool q_valid = r_lane < n_rows;
+    const int32_t r_c = min(r_lane, n_rows - 1);
+    const int32_t qi_c = r_c >> lg;
+    const int32_t h = (hg << lg) + (r_c & ((1 << lg) - 1));
+    const int32_t kvh = (hg << lg) / G;
     int32_t nk = len;                                        // keys 0 .. nk-1 are allowed
     if (causal) nk = min(len, len - q_len + qi_c + 1);
     nk = max(nk, 0);
-    // per wave: the largest bound of its 32 queries decides which tiles it can skip, the smallest which
+    // per wave: the largest bound of its 32 rows decides which tiles it can skip, the smallest which
     // tiles need no mask
     int32_t nk_wave = len, nk_wave_min = len;
     if (causal) {
-        nk_wave = min(len, len - q_len + min(m0 + 32 * wave + 31, q_len - 1) + 1);
-        nk_wave_min = min(len, len - q_len + min(m0 + 32 * wave, q_len - 1) + 1);
+        nk_wave = min(len, len - q_len + (min(m0 + 32 * wave + 31, n_rows - 1) >> lg) + 1);
+        nk_wave_min = min(len, len - q_len + (min(m0 + 32 * wave, n_rows - 1) >> lg) + 1);
     }
     nk_wave = max(nk_wave, 0);
     nk_wave_min = max(nk_wave_min, 0);
@@ -376,18 +407,18 @@ __device__ __forceinline__ void prefill_body(
     const int32_t last_key = len - 1;
 
     PageIds ids;
-    const int32_t n_tiles = (nk_wg + kBN - 1) / kBN;
+    const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
     if (n_tiles > 0) {
-        load_ids<UNIFORM>(ids, cache, table, 0, frow, last_key);
-        fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, 0, frow, last_key, lane_off);
-        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, kBN, frow, last_key);
+        load_ids<UNIFORM>(ids, cache, table, k_begin, frow, last_key);
+        fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, k_begin, frow, last_key, lane_off);
+        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, k_begin + kBN, frow, last_key);
         __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
     }
     // Two tiles per trip so that each buffer is a distinct LDS object for the compiler: while the matrix cores
     // read one, the load unit fills the other with the next tile; the page ids of the tile after that are requested
     // at the same time.  The barrier at the end of a tile waits for this wave's loads first.
     for (int32_t t = 0; t < n_tiles; t += 2) {
-        const int32_t t0 = t * kBN;
+        const int32_t t0 = k_begin + t * kBN;
         if (t + 1 < n_tiles) {
             fetch_tile<UNIFORM>(buf1 + wrow, ids, cache, t0 + kBN, frow, last_key, lane_off);
             if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
@@ -418,6 +449,24 @@ __device__ __forceinline__ void prefill_body(
     if (!q_valid) return;
     const float inv = l > 0.f ? 1.f / l : 0.f;
     // o[t][r]: column 32*t + 8*(r/4) + 4*hh + r%4 of this lane's query
+    if (plan.nsplit > 1) {
+        // partial of this chunk: normalised output in fp32 and the natural-log LSE over the chunk's keys
+        const int64_t pidx = row * plan.nsplit + split;
+        float* prow = plan.part_o + pidx * kD;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                float4 w;
+                w.x = o[t][4 * a + 0] * inv;
+                w.y = o[t][4 * a + 1] * inv;
+                w.z = o[t][4 * a + 2] * inv;
+                w.w = o[t][4 * a + 3] * inv;
+                *reinterpret_cast<float4*>(prow + 32 * t + 8 * a + 4 * hh) = w;
+            }
+        if (hh == 0) plan.part_lse[pidx] = l > 0.f ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+        return;
+    }
     uint16_t* orow = out + row * kD;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -438,14 +487,14 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
-    float scale, int32_t causal)
+    float scale, int32_t causal, PrefillPlan plan)
 {
     __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
     __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
-    prefill_body<false, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
-                        scale, causal);
-    prefill_body<true, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles, num_q_heads, max_blocks,
-                       scale, causal);
+    prefill_body<false, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+                                 num_q_heads, max_blocks, scale, causal, plan);
+    prefill_body<true, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+                                num_q_heads, max_blocks, scale, causal, plan);
 }
 
 }  // namespace
@@ -457,20 +506,41 @@ bool prefill_mfma_supported(const AttnArgs& a)
     return true;
 }
 
+int32_t prefill_mfma_log2_pack(int32_t num_q_heads, int32_t num_kv_heads)
+{
+    // all heads of a group when the group size is a power of two (up to 16), else no packing
+    const int32_t g = num_q_heads / num_kv_heads;
+    int32_t lg = 0;
+    while ((1 << (lg + 1)) <= g && lg < 4) ++lg;
+    return (1 << lg) == g ? lg : 0;
+}
+
 pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
 {
-    const int32_t tiles = (a.max_q_len + kBM - 1) / kBM;
+    PrefillPlan plan;
+    plan.log2_pack = prefill_mfma_log2_pack(a.num_q_heads, a.cache.num_kv_heads);
+    plan.chunk = a.plan.chunk;
+    plan.nsplit = a.plan.nsplit;
+    plan.skip_small = a.skip_small;
+    plan.part_o = a.part_o;
+    plan.part_lse = a.part_lse;
+    if (plan.nsplit > 1 && (plan.chunk % kBN != 0 || plan.chunk % a.cache.page_size != 0)) return PA_ERR_INVALID_ARG;
+    const int64_t tiles = (((int64_t)a.max_q_len << plan.log2_pack) + kBM - 1) / kBM;
     if (tiles <= 0) return PA_OK;
-    const int64_t blocks = (int64_t)tiles * a.num_q_heads * a.batch;
+    const int64_t blocks = tiles * plan.nsplit * (a.num_q_heads >> plan.log2_pack) * a.batch;
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     const dim3 grid((uint32_t)blocks, 1, 1);
-    ProfileScope prof("paged_prefill_mfma_kernel", stream);
-    // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
-    auto kern = a.cache.page_size >= 16 ? paged_prefill_mfma_kernel<true> : paged_prefill_mfma_kernel<false>;
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
-                       a.cu_q_lens, a.block_table, a.seq_lens, a.batch, tiles, a.num_q_heads, a.max_blocks, a.scale,
-                       a.causal);
-    return launch_status();
+    {
+        ProfileScope prof("paged_prefill_mfma_kernel", stream);
+        // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
+        auto kern = a.cache.page_size >= 16 ? paged_prefill_mfma_kernel<true> : paged_prefill_mfma_kernel<false>;
+        hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                           a.cu_q_lens, a.block_table, a.seq_lens, a.batch, (int32_t)tiles, a.num_q_heads, a.max_blocks,
+                           a.scale, a.causal, plan);
+        const pa_status st = launch_status();
+        if (st != PA_OK || plan.nsplit == 1) return st;
+    }
+    return launch_merge(a, stream);
 }
 
 }  // namespace pa

@@ -170,6 +170,101 @@ def test_prefill_ragged(pa, oracle, dtype, d, P, causal):
     parity.check_step(pa, oracle, w, f"ragged prefill {dtype} d={d} P={P} causal={causal}")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (32, 8), (64, 8), (16, 1), (24, 8), (40, 2), (32, 1)])
+def test_prefill_group_sizes(pa, oracle, Hq, Hkv):
+    """Row tiles pack the query heads of a KV head (group sizes 1..16, and 3, 20, 32 which are not packed)."""
+    w = W.make_workload("t", seq_lens=[300, 77, 513, 40], q_lens=[300, 1, 130, 7], num_q_heads=Hq,
+                        num_kv_heads=Hkv, head_dim=128, page_size=16, dtype=torch.bfloat16, causal=True, seed=45,
+                        device=DEV)
+    parity.check_step(pa, oracle, w, f"prefill Hq={Hq} Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("chunk", [64, 256, 1024, 4096])
+@pytest.mark.parametrize("P", [16, 128, 4])
+def test_prefill_context_split_schedules(pa, oracle, chunk, P):
+    """The matrix-core prefill kernel with its context cut into fixed chunks and merged, rows with and without
+    keys in a chunk, chunks no row reaches, empty sequences."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[2049, 64, 0, 700, 4096, 1], q_lens=[5, 64, 0, 130, 1, 1], num_q_heads=8,
+                        num_kv_heads=2, head_dim=128, page_size=P, dtype=torch.bfloat16, causal=True, seed=46,
+                        device=DEV)
+    binding.pa_set_option("prefill_chunk_tokens", chunk)
+    try:
+        parity.check_step(pa, oracle, w, f"prefill chunk={chunk} P={P}")
+    finally:
+        binding.pa_set_option("prefill_chunk_tokens", 0)
+
+
+def test_prefill_chunk_of_a_long_prompt_is_split_by_default(pa, oracle):
+    """Few query rows over a long context: the default plan cuts the context (no option set)."""
+    w = W.make_workload("t", seq_lens=[20000], q_lens=[200], num_q_heads=32, num_kv_heads=8, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, causal=True, seed=47, device=DEV)
+    parity.check_step(pa, oracle, w, "200 queries over 20000 keys")
+
+
+def test_mixed_prefill_and_decode_rows_in_one_call(pa, oracle):
+    """A jagged batch (Sec. III-B): decode rows over long contexts, a whole prompt, a chunk on top of cached
+    context and an idle sequence in one call."""
+    w = W.make_workload("t", seq_lens=[5000, 300, 1024, 77, 9000, 0, 2048], q_lens=[1, 300, 256, 1, 1, 0, 1],
+                        num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, dtype=torch.bfloat16, causal=True,
+                        seed=48, device=DEV)
+    parity.check_step(pa, oracle, w, "mixed prefill + decode")
+
+
+@pytest.mark.parametrize("Hq,Hkv,q_small", [(32, 8, 4), (8, 8, 16), (16, 1, 1), (16, 8, 8), (24, 8, 5), (64, 8, 2)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_few_query_sequences_take_the_decode_kernel(pa, oracle, Hq, Hkv, q_small, causal):
+    """Sequences whose q_len * G rows fit 16 columns (decode rows, speculative tokens) are computed by the decode
+    kernel inside a prefill call, each row with its own causal bound; longer ones by the prefill kernel.  Lengths
+    straddle tile and segment boundaries so that some rows' bounds fall before a segment starts."""
+    lens = [1000, 33, 64, 2048, 5, 300, 0, 4097, 96, 65]
+    q_lens = [q_small, 1, q_small, 1, min(5, q_small), 300, 0, q_small, 40, q_small]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, causal=causal, seed=50, device=DEV)
+    parity.check_step(pa, oracle, w, f"few-query route Hq={Hq} Hkv={Hkv} q={q_small} causal={causal}")
+
+
+@pytest.mark.parametrize("wgs", [1, 5, 64, 256])
+def test_few_query_route_split_schedules(pa, oracle, wgs):
+    from paper_2506_07311_amd import binding
+    lens = [2049, 64, 0, 31, 1000, 4096, 1, 130]
+    q_lens = [4, 3, 0, 2, 1, 4, 1, 130]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, causal=True, seed=51, device=DEV)
+    binding.pa_set_option("decode_workgroups", wgs)
+    try:
+        parity.check_step(pa, oracle, w, f"few-query route on {wgs} workgroups")
+    finally:
+        binding.pa_set_option("decode_workgroups", 0)
+
+
+def test_few_query_route_many_sequences_and_switch(pa, oracle):
+    """More than 64 sequences, and the same call with the route switched off gives the same answer (two kernels)."""
+    from paper_2506_07311_amd import binding
+    rng = np.random.default_rng(9)
+    lens = [int(x) for x in rng.integers(1, 400, size=150)]
+    q_lens = [int(min(L, rng.choice([1, 1, 1, 2, 4, 60]))) for L in lens]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=16, num_kv_heads=4, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, causal=True, seed=52, device=DEV)
+    parity.check_step(pa, oracle, w, "150 sequences, mixed")
+    out_a, lse_a = parity.gpu_step(pa, w, append=False)
+    binding.pa_set_option("no_small_q_route", 1)
+    try:
+        out_b, lse_b = parity.gpu_step(pa, w, append=False)
+    finally:
+        binding.pa_set_option("no_small_q_route", 0)
+    parity.assert_close(parity.to_f64(out_a), parity.to_f64(out_b), w.dtype, "route on vs off")
+    assert (lse_a - lse_b).abs().max().item() < 1e-3
+
+
+@pytest.mark.parametrize("have", [0, 512, 1024, 3584])
+def test_incremental_prefill_on_cached_context(pa, oracle, have):
+    """Chat growth: 512 new tokens appended behind `have` cached ones and attended causally."""
+    w = W.make_workload("t", seq_lens=[have + 512, have + 100], q_lens=[512, 100], num_q_heads=32, num_kv_heads=8,
+                        head_dim=128, page_size=16, dtype=torch.bfloat16, causal=True, seed=49, device=DEV)
+    parity.check_step(pa, oracle, w, f"chunk of 512 on {have} cached tokens")
+
+
 def test_prefill_row_equals_decode_at_that_length(pa):
     """Bottom-right causal alignment: row i of a causal prefill is the decode result at length i + 1."""
     S = 200
