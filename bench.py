@@ -44,6 +44,10 @@ WORKLOADS = {
     "decode_b8_ctx128": (2, 16, 128),
     "decode_fp32_single": (1, 16, None),
     "prefill_b4_s2048_causal": (3, 16, None),
+    # jagged batches through the prefill entry point
+    "prefill_chunk1024_on_ctx31744": (6, 16, None),
+    "mixed_60_decode_4_prefill512": (7, 16, None),
+    "speculative_4_tokens_b64_mixed": (8, 16, None),
     # plain paged copy of known size (Algorithm 1 Gather over 16 x 65536 tokens): calibrates HBM byte counters
     "gather_copy_calibration": (5, 16, 65536),
     # host-side KV page manager under serving churn (Algorithm 1 Reserve; Sec. III-B): not an attention workload
@@ -194,7 +198,7 @@ def main():
         return run_page_manager(torch, binding, args, P)
     w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
     torch.cuda.synchronize()
-    is_prefill = cfg == 3
+    is_prefill = cfg in (3, 6, 7, 8)
     if args.workload == "gather_copy_calibration":
         return run_gather_calibration(torch, pa, binding, w, args)
     seqs = list(range(min(args.oracle_seqs, w.batch)))
@@ -264,9 +268,24 @@ def main():
         "step_hbm_frac": round(kv_bytes / sec / 1e9 / HBM_PEAK_GBPS, 4),
         "kernels": kernels,
     }
-    if is_prefill:
+    G = w.num_q_heads // w.num_kv_heads
+    # in a prefill call, sequences with q_len * G <= 16 are computed by the decode kernel (bound: their KV bytes),
+    # the others by the prefill kernel (bound: their flops)
+    small = [ql * G <= 16 for ql in w.q_lens_host]
+    t_dec = kernels.get("paged_decode_mfma_kernel", {}).get("avg_us", 0.0)
+    t_pre = max(kernels.get("paged_prefill_mfma_kernel", {}).get("avg_us", 0.0),
+                kernels.get("paged_attention_generic_kernel", {}).get("avg_us", 0.0))
+    if is_prefill and t_dec > t_pre:
+        small_bytes = sum(L for L, sm in zip(w.seq_lens_host, small) if sm) * 2 * w.num_kv_heads * w.head_dim * 2
+        ach = small_bytes / (t_dec * 1e-6) / 1e9
+        result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                              "kernel": "paged_decode_mfma_kernel", "algorithmic_bytes": small_bytes,
+                              "note": "KV bytes of the sequences the decode kernel computes in this call"}
+    elif is_prefill:
+        routed = "paged_decode_mfma_kernel" in kernels
         flops = sum(4 * w.num_q_heads * w.head_dim * (ql * (L - ql) + ql * (ql + 1) // 2 if w.causal else ql * L)
-                    for ql, L in zip(w.q_lens_host, w.seq_lens_host))
+                    for ql, L, sm in zip(w.q_lens_host, w.seq_lens_host, small) if not (sm and routed))
         dom = kernels.get("paged_prefill_mfma_kernel") or kernels.get("paged_attention_generic_kernel")
         ach = flops / (dom["avg_us"] * 1e-6) / 1e12
         result["roofline"] = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
@@ -297,7 +316,8 @@ def main():
         del w, ws, out
         torch.cuda.empty_cache()
         wp = W.config(3, device=dev, poison=False)
-        wsp = torch.empty(256, dtype=torch.uint8, device=dev)
+        wsp = torch.empty(pa.paged_attention_workspace_bytes(wp.batch, wp.num_q_heads, wp.head_dim, wp.total_q,
+                                                             wp.max_seq_len), dtype=torch.uint8, device=dev)
         outp = torch.empty_like(wp.q)
 
         def pstep():

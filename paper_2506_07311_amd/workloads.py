@@ -243,7 +243,7 @@ def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> List[int]:
 
 def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_size: Optional[int] = None,
            shrink: int = 1, poison: bool = True) -> PagedWorkload:
-    """The five benchmark workloads (1-based).  ``shrink`` divides context lengths
+    """The five benchmark workloads (1-based), then three jagged-batch workloads (6-8).  ``shrink`` divides context lengths
     (and config 4's length range) for cases the CPU oracle must finish in seconds."""
     if n == 1:   # single-sequence fp32 decode, 8 of 64 pages used
         L = context or 128
@@ -270,4 +270,21 @@ def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_s
         P = page_size or 16
         return make_workload(f"cfg5_bf16_long_decode_L{L}_P{P}", seq_lens=[L] * 16, num_q_heads=64,
                              num_kv_heads=8, head_dim=128, page_size=P, seed=5, device=device, poison=poison)
+    # Jagged-batch workloads of the prefill entry point (Sec. III-B: ragged queries described by prefix sums).
+    if n == 6:   # chat growth: one 1024-token chunk appended behind 31744 cached tokens (1k -> 32k incremental)
+        L = context or max(128, 32768 // shrink)
+        chunk = max(16, 1024 // shrink)
+        return make_workload(f"cfg6_bf16_chunked_prefill_{chunk}_on_{L - chunk}", seq_lens=[L], q_lens=[chunk],
+                             num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=page_size or 16, causal=True,
+                             seed=6, device=device, poison=poison)
+    if n in (7, 8):   # config 4's length mix; 7: four sequences prefill 512 tokens while sixty decode; 8: four
+        hi = max(128, 32768 // shrink)            # speculative tokens per sequence
+        lens = log_uniform_lengths(64, 64, hi, seed=4)
+        if n == 7:
+            q_lens = [min(L, max(2, 512 // shrink)) if s % 16 == 5 else 1 for s, L in enumerate(lens)]
+        else:
+            q_lens = [min(L, 4) for L in lens]
+        return make_workload(f"cfg{n}_bf16_jagged_max{hi}", seq_lens=lens, q_lens=q_lens, num_q_heads=32,
+                             num_kv_heads=8, head_dim=128, page_size=page_size or 16, causal=True, seed=n,
+                             device=device, poison=poison)
     raise ValueError(f"no config {n}")
