@@ -7,7 +7,7 @@ leg may import this package; the GPU library never does, and this package
 imports nothing from it.
 
 Arrays are numpy, on the host.  bf16 data travels as ``uint16`` bit patterns
-(numpy has no bfloat16); fp32 as ``float32``.  Caches are ``[NP, P, Hkv, d]``
+(numpy has no bfloat16); fp32 as ``float32``; fp16 as ``float16``.  Caches are ``[NP, P, Hkv, d]``
 arrays (token-major, Algorithm 1's flat slot p = page * P + o) unless
 ``head_major=True`` says ``[NP, Hkv, P, d]``.
 """
@@ -23,7 +23,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpaged_oracle.so")
 _lib = None
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -54,7 +54,7 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB_PATH)
         for name in ("oracle_kv_append", "oracle_kv_gather", "oracle_attention",
-                     "oracle_merge_partials", "oracle_num_threads"):
+                     "oracle_merge_partials", "oracle_num_threads", "oracle_attention_mod", "oracle_widen"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -65,7 +65,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"cache dtype must be float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"cache dtype must be float32, float16 or uint16 (bf16 bits), got {a.dtype}")
 
 
 def _ptr(a):
@@ -129,13 +131,23 @@ def kv_gather(k_cache, v_cache, block_table, seq_lens, head_major=False):
     return out_k, out_v
 
 
+class _Mods(ctypes.Structure):
+    _fields_ = [("window", ctypes.c_int32), ("softcap", ctypes.c_double), ("alibi_slopes", ctypes.c_void_p),
+                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64)]
+
+
 def attention(k_cache, v_cache, q, block_table, seq_lens, scale, causal=False, cu_q_lens=None,
-              head_major=False, return_weights=False):
+              head_major=False, return_weights=False, window=0, softcap=0.0, alibi_slopes=None, doc_ids=None):
     """Masked softmax attention over the paged cache by the direct definition, in fp64.
 
     q: ``[total_q, Hq, d]`` (same dtype as the cache).  ``cu_q_lens`` defaults to
     one query per sequence (decode).  Returns ``(out, lse)`` as float64 arrays
     ``[total_q, Hq, d]`` and ``[total_q, Hq]`` (+ weights ``[total_q, Hq, max_len]``).
+
+    Modifications (FlexAttention's mask_mod / score_mod families): ``window`` > 0 keeps keys with
+    |j - pos| < window; ``doc_ids`` int32 ``[batch, >= max len]`` keeps keys of the query's document;
+    ``softcap`` > 0 replaces a score x by softcap * tanh(x / softcap); ``alibi_slopes`` ``[Hq]`` adds
+    slope[h] * (j - pos).
     """
     lib = _load()
     c = _desc(k_cache, v_cache, head_major)
@@ -155,11 +167,20 @@ def attention(k_cache, v_cache, q, block_table, seq_lens, scale, causal=False, c
         wstride = int(lens.max()) if B else 0
         weights = np.zeros((total_q, Hq, max(wstride, 1)), dtype=np.float64)
         wstride = max(wstride, 1)
-    rc = lib.oracle_attention(ctypes.byref(c), _ptr(q), _ptr(out), _ptr(lse), _ptr(weights),
-                              ctypes.c_int64(wstride), _ptr(cu), _ptr(bt), _ptr(lens),
-                              ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(bt.shape[1]),
-                              ctypes.c_double(float(scale)), ctypes.c_int32(1 if causal else 0))
-    _check(rc, "oracle_attention")
+    slopes = None if alibi_slopes is None else np.ascontiguousarray(alibi_slopes, dtype=np.float64)
+    docs = None if doc_ids is None else _i32(doc_ids)
+    if slopes is not None:
+        assert slopes.shape == (Hq,)
+    if docs is not None:
+        assert docs.ndim == 2 and docs.shape[0] == B and (B == 0 or docs.shape[1] >= int(lens.max()))
+    mods = _Mods(int(window), float(softcap), None if slopes is None else slopes.ctypes.data,
+                 None if docs is None else docs.ctypes.data, 0 if docs is None else docs.shape[1])
+    rc = lib.oracle_attention_mod(ctypes.byref(c), _ptr(q), _ptr(out), _ptr(lse), _ptr(weights),
+                                  ctypes.c_int64(wstride), _ptr(cu), _ptr(bt), _ptr(lens),
+                                  ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(bt.shape[1]),
+                                  ctypes.c_double(float(scale)), ctypes.c_int32(1 if causal else 0),
+                                  ctypes.byref(mods))
+    _check(rc, "oracle_attention_mod")
     if return_weights:
         return out, lse, weights
     return out, lse
@@ -177,6 +198,15 @@ def merge_partials(o_parts, lse_parts):
                                    _ptr(out), ctypes.byref(lse))
     _check(rc, "oracle_merge_partials")
     return out, lse.value
+
+
+def widen(a: np.ndarray) -> np.ndarray:
+    """The oracle's own exact widening of an input array (float32, float16, or uint16 bf16 bits) to float64."""
+    a = np.ascontiguousarray(a)
+    out = np.zeros(a.shape, dtype=np.float64)
+    _check(_load().oracle_widen(_ptr(a), ctypes.c_int64(a.size), ctypes.c_int32(_dtype_code(a)), _ptr(out)),
+           "oracle_widen")
+    return out
 
 
 def num_threads() -> int:

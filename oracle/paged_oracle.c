@@ -19,7 +19,7 @@ static int elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
 static int cache_ok(const oracle_cache *c)
 {
     if (!c || !c->k_cache || !c->v_cache) return 0;
-    if (c->dtype != ORACLE_F32 && c->dtype != ORACLE_BF16) return 0;
+    if (c->dtype != ORACLE_F32 && c->dtype != ORACLE_BF16 && c->dtype != ORACLE_F16) return 0;
     if (c->num_pages <= 0 || c->num_kv_heads <= 0 || c->head_dim <= 0) return 0;
     if (c->page_size <= 0 || (c->page_size & (c->page_size - 1)) != 0) return 0; /* Alg. 1: P is a power of two */
     return 1;
@@ -106,7 +106,18 @@ int oracle_kv_gather(const oracle_cache *c, void *out_k, void *out_v,
     return ORACLE_OK;
 }
 
-/* Exact widening: fp32 -> fp64 is exact; bf16 is the upper half of an fp32. */
+/* IEEE binary16 by its definition: sign, 5-bit exponent (bias 15), 10-bit fraction. */
+static double half_value(uint16_t bits)
+{
+    const int sign = bits >> 15, e = (bits >> 10) & 31, f = bits & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);                   /* zero and subnormals: f * 2^-24 */
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
+/* Exact widening: fp32 -> fp64 is exact; bf16 is the upper half of an fp32; binary16 by definition. */
 static double widen(const void *base, int64_t idx, int dtype)
 {
     if (dtype == ORACLE_F32) {
@@ -116,6 +127,7 @@ static double widen(const void *base, int64_t idx, int dtype)
     }
     uint16_t hbits;
     memcpy(&hbits, (const char *)base + idx * 2, 2);
+    if (dtype == ORACLE_F16) return half_value(hbits);
     uint32_t bits = (uint32_t)hbits << 16;
     float f;
     memcpy(&f, &bits, 4);
@@ -128,7 +140,42 @@ int oracle_attention(const oracle_cache *c, const void *q, double *out, double *
                      const int32_t *seq_lens, int32_t batch, int32_t num_q_heads,
                      int32_t max_blocks, double scale, int32_t causal)
 {
+    return oracle_attention_mod(c, q, out, lse, weights, weights_stride, cu_q_lens, block_table, seq_lens, batch,
+                                num_q_heads, max_blocks, scale, causal, NULL);
+}
+
+/* mask_mod: is key j visible to the query at position pos of sequence s? */
+static int visible(const oracle_mods *mods, int32_t s, int64_t pos, int64_t j)
+{
+    if (!mods) return 1;
+    if (mods->window > 0) {
+        const int64_t dist = j > pos ? j - pos : pos - j;
+        if (dist >= mods->window) return 0;
+    }
+    if (mods->doc_ids) {
+        const int32_t *doc = mods->doc_ids + (int64_t)s * mods->doc_stride;
+        if (doc[j] != doc[pos]) return 0;
+    }
+    return 1;
+}
+
+/* score_mod: soft cap first, then the linear position bias. */
+static double modded(const oracle_mods *mods, double x, int32_t h, int64_t pos, int64_t j)
+{
+    if (!mods) return x;
+    if (mods->softcap > 0.0) x = mods->softcap * tanh(x / mods->softcap);
+    if (mods->alibi_slopes) x += mods->alibi_slopes[h] * (double)(j - pos);
+    return x;
+}
+
+int oracle_attention_mod(const oracle_cache *c, const void *q, double *out, double *lse,
+                         double *weights, int64_t weights_stride,
+                         const int32_t *cu_q_lens, const int32_t *block_table,
+                         const int32_t *seq_lens, int32_t batch, int32_t num_q_heads,
+                         int32_t max_blocks, double scale, int32_t causal, const oracle_mods *mods)
+{
     if (!cache_ok(c) || batch < 0 || max_blocks < 0) return ORACLE_BAD_ARG;
+    if (mods && (mods->window < 0 || (mods->doc_ids && mods->doc_stride <= 0))) return ORACLE_BAD_ARG;
     if (batch == 0) return ORACLE_OK;
     if (!q || !out || !cu_q_lens || !block_table || !seq_lens) return ORACLE_BAD_ARG;
     const int32_t Hq = num_q_heads, Hkv = c->num_kv_heads, d = c->head_dim;
@@ -176,12 +223,14 @@ int oracle_attention(const oracle_cache *c, const void *q, double *out, double *
                 if (!x) { failed = 1; continue; }
                 double m = -INFINITY;
                 for (int64_t j = 0; j < nkeys; ++j) {
+                    if (!visible(mods, s, pos, j)) { x[j] = -INFINITY; continue; }
                     const double *kr = Ks + (j * Hkv + kvh) * d;
                     double acc = 0.0;
                     for (int32_t e = 0; e < d; ++e) acc += widen(q, row * d + e, c->dtype) * kr[e];
-                    x[j] = scale * acc;
+                    x[j] = modded(mods, scale * acc, h, pos, j);
                     if (x[j] > m) m = x[j];
                 }
+                if (m == -INFINITY) { if (lse) lse[row] = -INFINITY; free(x); continue; }   /* nothing visible */
                 double Z = 0.0;
                 for (int64_t j = 0; j < nkeys; ++j) { x[j] = exp(x[j] - m); Z += x[j]; }
                 for (int64_t j = 0; j < nkeys; ++j) {
@@ -216,6 +265,14 @@ int oracle_merge_partials(const double *o_parts, const double *lse_parts, int32_
         for (int32_t e = 0; e < d; ++e) out[e] += w * o_parts[(int64_t)c * d + e];
     }
     if (lse) *lse = M + log(Z);
+    return ORACLE_OK;
+}
+
+int oracle_widen(const void *src, int64_t n, int32_t dtype, double *dst)
+{
+    if (!src || !dst || n < 0) return ORACLE_BAD_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F16) return ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < n; ++i) dst[i] = widen(src, i, dtype);
     return ORACLE_OK;
 }
 

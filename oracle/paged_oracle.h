@@ -12,7 +12,8 @@
  * All pointers are HOST pointers.  Caches are addressed through element
  * strides, so both the literal token-major layout [NP, P, Hkv, d] of
  * Algorithm 1 (flat slot p = page * P + o) and a head-major one can be
- * described.  dtype: 0 = IEEE fp32, 1 = bfloat16 (upper 16 bits of an fp32).
+ * described.  dtype: 0 = IEEE fp32, 1 = bfloat16 (upper 16 bits of an fp32),
+ * 2 = IEEE binary16.
  *
  * Every function returns 0 on success and a negative code when an argument
  * or a device-side precondition (page id out of range, position beyond the
@@ -28,7 +29,7 @@
 extern "C" {
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 enum {
     ORACLE_OK = 0,
@@ -48,7 +49,7 @@ typedef struct {
     int32_t page_size;    /* P, a power of two (Algorithm 1, Require)          */
     int32_t num_kv_heads; /* Hkv                                               */
     int32_t head_dim;     /* d, innermost and contiguous                       */
-    int32_t dtype;        /* ORACLE_F32 or ORACLE_BF16                         */
+    int32_t dtype;        /* ORACLE_F32, ORACLE_BF16 or ORACLE_F16             */
 } oracle_cache;
 
 /* Algorithm 1, Assign.  For i = 0..T-1 in order: t = positions[i],
@@ -91,6 +92,31 @@ int oracle_attention(const oracle_cache *c, const void *q, double *out, double *
                      const int32_t *seq_lens, int32_t batch, int32_t num_q_heads,
                      int32_t max_blocks, double scale, int32_t causal);
 
+/* The same with user-defined mask and score modifications in the sense of
+ * FlexAttention's mask_mod / score_mod (Sec. II-C, Sec. III-B), for the three
+ * families this library builds in.  With pos the query's absolute position:
+ *   mask:   key j is also required to satisfy
+ *             |j - pos| < window                       if window > 0  (sliding window)
+ *             doc_ids[s][j] == doc_ids[s][pos]         if doc_ids     (document mask;
+ *                                   doc_ids is int32 [batch, doc_stride], logical positions)
+ *   score:  x_j = scale * <q, k_j>
+ *           x_j <- softcap * tanh(x_j / softcap)       if softcap > 0
+ *           x_j <- x_j + alibi_slopes[h] * (j - pos)   if alibi_slopes (double[Hq])
+ * then softmax over the visible keys as above.  mods == NULL: no modification. */
+typedef struct {
+    int32_t window;
+    double softcap;
+    const double *alibi_slopes;
+    const int32_t *doc_ids;
+    int64_t doc_stride;
+} oracle_mods;
+
+int oracle_attention_mod(const oracle_cache *c, const void *q, double *out, double *lse,
+                         double *weights, int64_t weights_stride,
+                         const int32_t *cu_q_lens, const int32_t *block_table,
+                         const int32_t *seq_lens, int32_t batch, int32_t num_q_heads,
+                         int32_t max_blocks, double scale, int32_t causal, const oracle_mods *mods);
+
 /* Exact merge of softmax partials over disjoint key sets (the split-KV
  * identity): given n partials (o_c normalised, lse_c) returns the result over
  * the union:  M = max lse_c,  o = sum e^{lse_c - M} o_c / sum e^{lse_c - M},
@@ -98,6 +124,9 @@ int oracle_attention(const oracle_cache *c, const void *q, double *out, double *
  * Partials with lse = -inf (empty sets) contribute nothing. */
 int oracle_merge_partials(const double *o_parts, const double *lse_parts, int32_t n,
                           int32_t d, double *out, double *lse);
+
+/* The exact widening the attention applies to its inputs: n elements of `dtype` -> fp64. */
+int oracle_widen(const void *src, int64_t n, int32_t dtype, double *dst);
 
 /* Number of OpenMP threads the attention loop will use. */
 int oracle_num_threads(void);
