@@ -43,7 +43,7 @@ typedef enum {
     PA_ERR_OUT_OF_PAGES = 5          /* the page pool cannot satisfy a reservation (nothing was changed)          */
 } pa_status;
 
-typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
+typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1, PA_DTYPE_F16 = 2 } pa_dtype;
 
 /*
  * The two global pools (Sec. III-B: "two global buffers store K and V pages").
@@ -53,7 +53,9 @@ typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
  * are in ELEMENTS and let a head-major pool [NP, Hkv, P, d] be described too.
  * head_dim is innermost and contiguous; every stride must be a multiple of
  * 16 bytes.  page_size must be a power of two (Algorithm 1, Require).
- * Supported: head_dim a multiple of 8 (bf16) / 4 (fp32), at most 256.
+ * Supported: head_dim a multiple of 8 (bf16, fp16) / 4 (fp32), at most 256.
+ * fp16 (the paper's own precision, Sec. III-B) computes like bf16: fp32 accumulation, outputs rounded to
+ * nearest even.
  */
 typedef struct {
     void*    k_cache;
@@ -141,6 +143,42 @@ pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, 
                                   const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
                                   int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
                                   int32_t causal, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Mask and score modifications in the sense of FlexAttention's mask_mod /
+ * score_mod (Sec. II-C; Sec. III-B builds the paged mask out of one), for the
+ * families this library builds in.  With pos the query's absolute position
+ * (decode: seq_lens[s] - 1), on top of the length mask and the causal bound:
+ *   window > 0       key j is visible only if |j - pos| < window            (sliding window)
+ *   doc_ids != NULL  ... only if doc_ids[s][j] == doc_ids[s][pos]            (document mask); device
+ *                    int32 [batch, doc_stride], indexed by logical position, doc_stride >= max_seq_len
+ *   softcap > 0      score x = scale * <q, k> becomes softcap * tanh(x / softcap)
+ *   alibi_slopes     then x becomes x + alibi_slopes[h] * (j - pos);  device float[Hq]
+ * A query left without any visible key gets out = 0, lse = -inf.  The kernels
+ * are instantiated per combination of hooks at compile time: a call with
+ * mods == NULL, or with every field off, runs exactly the unmodified kernels.
+ * Sliding windows skip the context before the window instead of masking it.
+ */
+typedef struct {
+    int32_t        window;
+    float          softcap;
+    const float*   alibi_slopes;
+    const int32_t* doc_ids;
+    int64_t        doc_stride;
+} pa_attn_mods;
+
+/* paged_attention_decode / paged_attention_prefill with modifications; all other arguments as there. */
+pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                     const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                     int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                     const pa_attn_mods* mods, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                      const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len,
+                                      const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                      int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                      int32_t causal, const pa_attn_mods* mods, void* workspace,
+                                      size_t workspace_bytes, void* stream);
 
 const char* pa_status_string(pa_status status);
 

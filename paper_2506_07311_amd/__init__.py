@@ -9,7 +9,9 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     paged_attention_decode,
+    paged_attention_decode_mod,
     paged_attention_prefill,
+    paged_attention_prefill_mod,
     paged_attention_workspace_bytes,
     paged_kv_append,
     paged_kv_gather,

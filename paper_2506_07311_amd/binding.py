@@ -17,11 +17,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libpagedattn.so"
 _lib = None
 
-PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1}
+PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
-    "paged_attention_prefill", "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
+    "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
     "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
     "pa_pool_make_writable", "pa_pool_num_free", "pa_pool_num_blocks", "pa_pool_get_row", "pa_pool_refcount",
@@ -200,6 +200,79 @@ def paged_attention_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, bloc
                                      ctypes.c_size_t(workspace.numel() * workspace.element_size()),
                                      _stream(stream))
     _check(st, "paged_attention_prefill")
+    return out
+
+
+class _Mods(ctypes.Structure):
+    _fields_ = [("window", ctypes.c_int32), ("softcap", ctypes.c_float), ("alibi_slopes", ctypes.c_void_p),
+                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64)]
+
+
+def _mods(window, softcap, alibi_slopes, doc_ids, Hq, B):
+    if alibi_slopes is not None:
+        _dense(alibi_slopes, "alibi_slopes", torch.float32)
+        if tuple(alibi_slopes.shape) != (Hq,):
+            raise PagedAttnError("alibi_slopes must be float32[Hq]")
+    if doc_ids is not None:
+        _i32(doc_ids, "doc_ids")
+        if doc_ids.dim() != 2 or doc_ids.shape[0] != B:
+            raise PagedAttnError("doc_ids must be int32[batch, doc_stride]")
+    return _Mods(int(window), float(softcap), None if alibi_slopes is None else alibi_slopes.data_ptr(),
+                 None if doc_ids is None else doc_ids.data_ptr(), 0 if doc_ids is None else doc_ids.shape[1])
+
+
+def paged_attention_decode_mod(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
+                               window: int = 0, softcap: float = 0.0, alibi_slopes=None, doc_ids=None,
+                               out=None, lse=None, workspace=None, head_major=False, stream=None):
+    """paged_attention_decode with mask / score modifications (see pa_attn_mods in the header)."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    B, Hq, hd = q.shape
+    if hd != d.head_dim or seq_lens.shape[0] != B or block_table.shape[0] != B:
+        raise PagedAttnError("q must be [B, Hq, d] with B matching seq_lens and block_table")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens")
+    out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    workspace = _workspace(workspace, paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len), q.device)
+    st = lib.paged_attention_decode_mod(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
+                                        ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]),
+                                        ctypes.c_int32(max_seq_len), ctypes.c_float(scale), ctypes.byref(mods),
+                                        _p(workspace),
+                                        ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(st, "paged_attention_decode_mod")
+    return out
+
+
+def paged_attention_prefill_mod(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,
+                                max_seq_len: int, scale: float, causal: bool, *, window: int = 0,
+                                softcap: float = 0.0, alibi_slopes=None, doc_ids=None, out=None, lse=None,
+                                workspace=None, head_major=False, stream=None):
+    """paged_attention_prefill with mask / score modifications (see pa_attn_mods in the header)."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    total_q, Hq, hd = q.shape
+    B = int(seq_lens.shape[0])
+    if hd != d.head_dim or block_table.shape[0] != B or cu_q_lens.shape[0] != B + 1:
+        raise PagedAttnError("q must be [total_q, Hq, d]; cu_q_lens int32[B+1]")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens"), _i32(cu_q_lens, "cu_q_lens")
+    out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    workspace = _workspace(workspace, paged_attention_workspace_bytes(B, Hq, hd, total_q, max_seq_len), q.device)
+    st = lib.paged_attention_prefill_mod(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(cu_q_lens),
+                                         ctypes.c_int32(total_q), ctypes.c_int32(max_q_len), _p(block_table),
+                                         _p(seq_lens), ctypes.c_int32(B), ctypes.c_int32(Hq),
+                                         ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
+                                         ctypes.c_float(scale), ctypes.c_int32(1 if causal else 0),
+                                         ctypes.byref(mods), _p(workspace),
+                                         ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                         _stream(stream))
+    _check(st, "paged_attention_prefill_mod")
     return out
 
 

@@ -50,7 +50,7 @@ bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 pa_status check_cache(const pa_kv_cache_desc* c)
 {
     if (!c || !c->k_cache || !c->v_cache) return PA_ERR_INVALID_ARG;
-    if (c->dtype != PA_DTYPE_F32 && c->dtype != PA_DTYPE_BF16) return PA_ERR_UNSUPPORTED;
+    if (c->dtype != PA_DTYPE_F32 && c->dtype != PA_DTYPE_BF16 && c->dtype != PA_DTYPE_F16) return PA_ERR_UNSUPPORTED;
     if (c->num_pages <= 0 || c->num_kv_heads <= 0 || c->head_dim <= 0) return PA_ERR_INVALID_ARG;
     if (!is_pow2(c->page_size)) return PA_ERR_INVALID_ARG;   // Algorithm 1 requires a power of two
     const int epv = 16 / elem_bytes(c->dtype);
@@ -194,8 +194,8 @@ size_t part_lse_bytes(int64_t rows, int32_t hq, int32_t nsplit)
 pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
                         const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len, const int32_t* block_table,
                         const int32_t* seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks,
-                        int32_t max_seq_len, float scale, int32_t causal, void* workspace, size_t workspace_bytes,
-                        void* stream, bool decode)
+                        int32_t max_seq_len, float scale, int32_t causal, const pa_attn_mods* mods, void* workspace,
+                        size_t workspace_bytes, void* stream, bool decode)
 {
     pa_status st = check_cache(cache);
     if (st != PA_OK) return st;
@@ -206,6 +206,16 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     if (((uintptr_t)q | (uintptr_t)out) & 15) return PA_ERR_UNSUPPORTED;
     if ((int64_t)max_blocks * cache->page_size < max_seq_len) return PA_ERR_INVALID_ARG;
     if (!(scale == scale)) return PA_ERR_INVALID_ARG;
+    ModArgs m = {0, 0.f, nullptr, nullptr, 0};
+    if (mods) {
+        if (mods->window < 0 || !(mods->softcap >= 0.f) || mods->softcap > 3.0e38f) return PA_ERR_INVALID_ARG;
+        if (mods->doc_ids && mods->doc_stride < max_seq_len) return PA_ERR_INVALID_ARG;
+        m.window = mods->window;
+        m.softcap = mods->softcap;
+        m.alibi_slopes = mods->alibi_slopes;
+        m.doc_ids = mods->doc_ids;
+        m.doc_stride = mods->doc_ids ? mods->doc_stride : 0;
+    }
     const size_t need = paged_attention_workspace_bytes(batch, num_q_heads, cache->head_dim, total_q, max_seq_len);
     if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE_TOO_SMALL;
     if ((uintptr_t)workspace & 255) return PA_ERR_INVALID_ARG;
@@ -237,6 +247,8 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.num_wgs = 0;
     a.seg_first = a.seg_last = nullptr;
     a.skip_small = 0;
+    a.mods = m;
+    a.has_mods = m.window > 0 || m.softcap > 0.f || m.alibi_slopes || m.doc_ids;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     if (decode) {
@@ -262,7 +274,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         if (a.plan.nsplit > 1) st = launch_merge(a, s);
         return st;
     }
-    if (!g_opt.force_generic && prefill_mfma_supported(a)) {
+    if (!g_opt.force_generic && prefill_mfma_supported(a) && !a.has_mods) {
         // Jagged batch: sequences with few queries (q_len * G <= 16: decode rows, a few speculative tokens) are
         // bound by streaming their context once, which the decode kernel's equal-work tile stream does best; the
         // others go to the prefill kernel.  Both kernels decide per sequence from cu_q_lens on the device; the
@@ -390,7 +402,27 @@ pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, v
                                  void* workspace, size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
-                         max_seq_len, scale, 0, workspace, workspace_bytes, stream, true);
+                         max_seq_len, scale, 0, nullptr, workspace, workspace_bytes, stream, true);
+}
+
+pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                     const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                     int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                     const pa_attn_mods* mods, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
+                         max_seq_len, scale, 0, mods, workspace, workspace_bytes, stream, true);
+}
+
+pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                      const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len,
+                                      const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                      int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                      int32_t causal, const pa_attn_mods* mods, void* workspace,
+                                      size_t workspace_bytes, void* stream)
+{
+    return run_attention(cache, q, out, lse, cu_q_lens, total_q, max_q_len, block_table, seq_lens, batch, num_q_heads,
+                         max_blocks, max_seq_len, scale, causal, mods, workspace, workspace_bytes, stream, false);
 }
 
 pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -400,7 +432,7 @@ pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, 
                                   int32_t causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, cu_q_lens, total_q, max_q_len, block_table, seq_lens, batch, num_q_heads,
-                         max_blocks, max_seq_len, scale, causal, workspace, workspace_bytes, stream, false);
+                         max_blocks, max_seq_len, scale, causal, nullptr, workspace, workspace_bytes, stream, false);
 }
 
 const char* pa_status_string(pa_status status)

@@ -1,5 +1,5 @@
 // Portable paged attention kernel (VALU, fp32 accumulation) for every shape the MFMA kernels do not
-// cover: fp32 pools, head_dim other than 128, page sizes below 16, group sizes above 16.  One workgroup
+// cover: fp32 pools, head_dim other than 128, group sizes above 16, document masks.  One workgroup
 // computes one (query row, query head, context chunk) by flash-style tiles of 1024 keys:
 //   scores  s_j = scale * <q, K[j]>            one key per thread, 16-byte loads along head_dim
 //   mask    keys >= n_keys are never touched   (length mask / causal bound, Sec. III-B)
@@ -52,6 +52,27 @@ template <> struct Vec<bf16_tag> {
     }
 };
 
+struct f16_tag {};
+template <> struct Vec<f16_tag> {
+    static constexpr int N = 8;
+    typedef float dot_t;
+    __device__ static void load(const void* p, float* f)
+    {
+        typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+        const half8 v = *reinterpret_cast<const half8*>(p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (float)v[i];
+    }
+    __device__ static float load1(const void* base, int64_t i)
+    {
+        return f16_bits_to_float(reinterpret_cast<const uint16_t*>(base)[i]);
+    }
+    __device__ static void store1(void* base, int64_t i, float v)
+    {
+        reinterpret_cast<uint16_t*>(base)[i] = (uint16_t)float_to_f16_bits(v);
+    }
+};
+
 __device__ __forceinline__ float block_max(float v, float* red)
 {
     v = wave_max(v);
@@ -72,12 +93,14 @@ __device__ __forceinline__ float block_sum(float v, float* red)
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-template <typename T>
+// M: compile-time policy naming the mask / score hooks that exist in this instantiation (NoMods: none).
+template <typename T, typename M>
 __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     CacheView cache, const void* __restrict__ q, void* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks, float scale,
-    int32_t causal, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk, int32_t nsplit)
+    int32_t causal, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk, int32_t nsplit,
+    ModArgs mods)
 {
     using V = Vec<T>;
     constexpr int N = V::N;
@@ -97,16 +120,32 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     const RowInfo ri = locate_row(cu_q_lens, seq_lens, batch, row, causal);
     const int32_t s = ri.seq;
     const int32_t n_keys = ri.n_keys;
-    const int32_t c0 = split * chunk;
-    const int32_t c1 = min(n_keys, c0 + chunk);
+    int32_t c0 = split * chunk;
+    int32_t c1 = min(n_keys, c0 + chunk);
     const int64_t o_idx = (int64_t)row * num_q_heads + h;
+    if (M::kWindow && mods.window > 0) {   // keys outside the window are skipped, not masked
+        c0 = max(c0, ri.pos - mods.window + 1);
+        c1 = min(c1, ri.pos + mods.window);
+    }
 
     if (c0 >= c1) {
         if (nsplit == 1) {   // empty context: out = 0, lse = -inf
             for (int e = tid; e < d; e += kThreads) V::store1(out, o_idx * d + e, 0.f);
             if (lse && tid == 0) lse[o_idx] = -INFINITY;
+        } else if (M::kAny && split * chunk < n_keys) {
+            // a chunk the merge will read, emptied by the window: an explicit empty partial
+            for (int e = tid; e < d; e += kThreads) part_o[(o_idx * nsplit + split) * d + e] = 0.f;
+            if (tid == 0) part_lse[o_idx * nsplit + split] = -INFINITY;
         }
         return;             // with nsplit > 1 the merge never reads chunks at or beyond n_keys
+    }
+    float slope = 0.f;
+    const int32_t* doc = nullptr;
+    int32_t my_doc = 0;
+    if (M::kScore && mods.alibi_slopes) slope = mods.alibi_slopes[h];
+    if (M::kDoc && mods.doc_ids) {
+        doc = mods.doc_ids + (int64_t)s * mods.doc_stride;
+        my_doc = doc[ri.pos];
     }
 
     const int32_t G = num_q_heads / cache.num_kv_heads;
@@ -144,11 +183,20 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
 #pragma unroll
                 for (int e = 0; e < N; ++e) dot += (typename V::dot_t)q_s[c * N + e] * (typename V::dot_t)kv[e];
             }
-            const float sj = (float)(dot * scale);
+            float sj = (float)(dot * scale);
+            if (M::kScore) {
+                if (mods.softcap > 0.f) sj = mods.softcap * tanhf(sj / mods.softcap);
+                sj += slope * (float)(j - ri.pos);
+            }
+            if (M::kDoc && doc && doc[j] != my_doc) sj = -INFINITY;
             sc[jj] = sj;
             lmax = fmaxf(lmax, sj);
         }
         const float m_new = fmaxf(m, block_max(lmax, red));
+        if (M::kDoc && m_new == -INFINITY) {       // no visible key so far (uniform over the workgroup)
+            __syncthreads();
+            continue;
+        }
         const float alpha = expf(m - m_new);       // m = -inf on the first tile gives 0
         float lsum = 0.f;
         for (int32_t jj = tid; jj < tn; jj += kThreads) {
@@ -181,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
         for (int e = 0; e < N; ++e) acc_s[kg * d + vc * N + e] = acc[e];
     }
     __syncthreads();
-    const float inv_l = 1.f / l;
+    const float inv_l = (!M::kDoc || l > 0.f) ? 1.f / l : 0.f;
     for (int e = tid; e < d; e += kThreads) {
         float sum = 0.f;
         for (int g = 0; g < kgroups; ++g) sum += acc_s[g * d + e];
@@ -192,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
             part_o[(o_idx * nsplit + split) * d + e] = o;
     }
     if (tid == 0) {
-        const float r = m + logf(l);
+        const float r = (!M::kDoc || l > 0.f) ? m + logf(l) : -INFINITY;
         if (nsplit == 1) { if (lse) lse[o_idx] = r; }
         else part_lse[o_idx * nsplit + split] = r;
     }
@@ -205,17 +253,26 @@ pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream)
     const int64_t blocks = (int64_t)a.total_q * a.num_q_heads * a.plan.nsplit;
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     ProfileScope prof("paged_attention_generic_kernel", stream);
-    if (a.dtype == PA_DTYPE_F32) {
-        hipLaunchKernelGGL(paged_attention_generic_kernel<float>, dim3((uint32_t)blocks), dim3(kThreads), 0, stream,
-                           a.cache, a.q, a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch,
-                           a.num_q_heads, a.max_blocks, a.scale, a.causal, a.part_o, a.part_lse, a.plan.chunk,
-                           a.plan.nsplit);
-    } else {
-        hipLaunchKernelGGL(paged_attention_generic_kernel<bf16_tag>, dim3((uint32_t)blocks), dim3(kThreads), 0,
-                           stream, a.cache, a.q, a.out, a.lse, a.cu_q_lens, a.block_table, a.seq_lens, a.batch,
-                           a.num_q_heads, a.max_blocks, a.scale, a.causal, a.part_o, a.part_lse, a.plan.chunk,
-                           a.plan.nsplit);
-    }
+    // hook combinations instantiated here: none; window and / or score; all (document masks)
+    const int hooks = !a.has_mods ? 0 : a.mods.doc_ids ? 2 : 1;
+    void (*kern)(CacheView, const void*, void*, float*, const int32_t*, const int32_t*, const int32_t*, int32_t,
+                 int32_t, int32_t, float, int32_t, float*, float*, int32_t, int32_t, ModArgs) = nullptr;
+    typedef Mods<true, true, false> WindowScore;
+    if (a.dtype == PA_DTYPE_F32)
+        kern = hooks == 0   ? paged_attention_generic_kernel<float, NoMods>
+               : hooks == 1 ? paged_attention_generic_kernel<float, WindowScore>
+                            : paged_attention_generic_kernel<float, AllMods>;
+    else if (a.dtype == PA_DTYPE_BF16)
+        kern = hooks == 0   ? paged_attention_generic_kernel<bf16_tag, NoMods>
+               : hooks == 1 ? paged_attention_generic_kernel<bf16_tag, WindowScore>
+                            : paged_attention_generic_kernel<bf16_tag, AllMods>;
+    else
+        kern = hooks == 0   ? paged_attention_generic_kernel<f16_tag, NoMods>
+               : hooks == 1 ? paged_attention_generic_kernel<f16_tag, WindowScore>
+                            : paged_attention_generic_kernel<f16_tag, AllMods>;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, a.cache, a.q, a.out, a.lse,
+                       a.cu_q_lens, a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.causal,
+                       a.part_o, a.part_lse, a.plan.chunk, a.plan.nsplit, a.mods);
     return launch_status();
 }
 

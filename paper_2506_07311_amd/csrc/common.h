@@ -83,6 +83,26 @@ pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, 
 
 pa_status launch_kv_copy_page(const pa_kv_cache_desc* c, int32_t src_page, int32_t dst_page, hipStream_t stream);
 
+// Mask / score modifications of a call (pa_attn_mods with the "off" values normalised).  The kernels take a
+// compile-time policy that says which hooks exist at all; NoMods compiles to the unmodified kernel.
+struct ModArgs {
+    int32_t window;              // 0 = off
+    float softcap;               // 0 = off
+    const float* alibi_slopes;   // null = off
+    const int32_t* doc_ids;      // null = off
+    int64_t doc_stride;
+};
+
+template <bool WINDOW, bool SCORE, bool DOC>
+struct Mods {
+    static constexpr bool kWindow = WINDOW;   // sliding window
+    static constexpr bool kScore = SCORE;     // soft cap and / or linear position bias
+    static constexpr bool kDoc = DOC;         // document mask
+    static constexpr bool kAny = WINDOW || SCORE || DOC;
+};
+typedef Mods<false, false, false> NoMods;
+typedef Mods<true, true, true> AllMods;
+
 struct AttnArgs {
     CacheView cache;
     pa_dtype dtype;
@@ -110,6 +130,8 @@ struct AttnArgs {
     int32_t* seg_first;
     int32_t* seg_last;
     int32_t skip_small;      // prefill kernel: leave sequences with q_len * G <= 16 to the decode kernel
+    ModArgs mods;
+    bool has_mods;
 };
 
 // Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.
@@ -134,6 +156,17 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
     return __uint_as_float(bits16 << 16);
 }
 
+__device__ __forceinline__ float f16_bits_to_float(uint32_t bits16)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+}
+
+// Round-to-nearest-even fp32 -> fp16 bit pattern (v_cvt_f16_f32).
+__device__ __forceinline__ uint32_t float_to_f16_bits(float f)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
 // Round-to-nearest-even fp32 -> bf16 bit pattern (NaN stays NaN).
 __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
 {
@@ -143,6 +176,59 @@ __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
     return u >> 16;
 }
 
+// Element traits of the 16-bit matrix-core kernels: packing with round-to-nearest-even, unpacking, and the two
+// matrix instructions.  Operands travel as uint4 (8 elements); the accumulators are fp32.
+typedef __attribute__((ext_vector_type(4))) float mfma_f32x4;
+typedef __attribute__((ext_vector_type(16))) float mfma_f32x16;
+
+struct ElemBf16 {
+    static constexpr pa_dtype kDtype = PA_DTYPE_BF16;
+    typedef __attribute__((ext_vector_type(8))) __bf16 vec8;
+    typedef __attribute__((ext_vector_type(2))) __bf16 vec2;
+    __device__ static __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        typedef __attribute__((ext_vector_type(2))) float f32x2;
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, vec2));   // v_cvt_pk_bf16_f32
+    }
+    __device__ static __forceinline__ float lo_of(uint32_t w) { return __uint_as_float(w << 16); }
+    __device__ static __forceinline__ float hi_of(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    __device__ static __forceinline__ mfma_f32x4 mfma16(const uint4& a, const uint4& b, mfma_f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
+                                                       0);
+    }
+    __device__ static __forceinline__ mfma_f32x16 mfma32(const uint4& a, const uint4& b, mfma_f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
+                                                       0);
+    }
+};
+
+struct ElemF16 {
+    static constexpr pa_dtype kDtype = PA_DTYPE_F16;
+    typedef __attribute__((ext_vector_type(8))) _Float16 vec8;
+    typedef __attribute__((ext_vector_type(2))) _Float16 vec2;
+    __device__ static __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        typedef __attribute__((ext_vector_type(2))) float f32x2;
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, vec2));
+    }
+    __device__ static __forceinline__ float lo_of(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[0]; }
+    __device__ static __forceinline__ float hi_of(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[1]; }
+    __device__ static __forceinline__ mfma_f32x4 mfma16(const uint4& a, const uint4& b, mfma_f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
+                                                      0);
+    }
+    __device__ static __forceinline__ mfma_f32x16 mfma32(const uint4& a, const uint4& b, mfma_f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
+                                                      0);
+    }
+};
+
 // Which sequence a packed query row belongs to and how many keys it may see.  cu_q_lens is the
 // prefix-sum vector of Sec. III-B (null for decode, where row == sequence).  Query i of a sequence with
 // q_len queries sits at position len - q_len + i; keys 0 .. n_keys-1 are allowed: n_keys = len under the
@@ -150,6 +236,8 @@ __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
 struct RowInfo {
     int32_t seq;
     int32_t n_keys;
+    int32_t pos;      // the query's absolute position
+    int32_t len;
 };
 
 __device__ __forceinline__ RowInfo locate_row(const int32_t* __restrict__ cu_q_lens,
@@ -174,6 +262,8 @@ __device__ __forceinline__ RowInfo locate_row(const int32_t* __restrict__ cu_q_l
     int32_t n = len;
     if (causal) n = min(len, len - q_len + qi + 1);
     r.n_keys = max(n, 0);
+    r.pos = len - q_len + qi;
+    r.len = len;
     return r;
 }
 

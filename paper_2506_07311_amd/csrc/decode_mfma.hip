@@ -24,21 +24,12 @@ namespace pa {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef mfma_f32x4 f32x4;
 
 constexpr int kD = 128;
 constexpr int kTileKeys = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));   // v_cvt_pk_bf16_f32, RNE
-}
 
 __device__ __forceinline__ uint4 load16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
 
@@ -113,11 +104,22 @@ struct State {
     float l;       // this lane's share of the running sum
 };
 
+// What the hooks need per row (this lane's column).  Unused members cost nothing without their hook.
+struct RowMods {
+    int32_t lo;         // window: first visible key of this row
+    int32_t lo_until;   // window: tiles that start before this key need the lower mask (wave-uniform)
+    int32_t pos;        // score: the row's absolute position
+    float slope2;       // score: bias slope * log2(e)
+    float cap_in;       // score: scale / softcap, 0 without a cap
+    float cap_out;      // score: softcap * log2(e)
+    float scale;        // score: plain scale (the unmodified path folds log2(e) into it)
+};
+
 // lim = first key this lane's row may not see (the segment end, or less under a per-row causal bound);
 // mask_from <= every lane's lim, wave-uniform: tiles that end at or before it need no mask.
-template <bool RAGGED>
-__device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf16x8 (&qf)[4], float sc, int32_t t0,
-                                             int32_t lim, int32_t mask_from, int32_t quad)
+template <bool RAGGED, typename E, typename M>
+__device__ __forceinline__ void compute_tile(State& st, const Tile& t, const uint4 (&qf)[4], float sc, int32_t t0,
+                                             int32_t lim, int32_t mask_from, int32_t quad, const RowMods& rm)
 {
     f32x4 s[2];
 #pragma unroll
@@ -125,18 +127,33 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
         s[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            s[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[mt][ks]), qf[ks], s[mt], 0,
-                                                            0, 0);
+            s[mt] = E::mfma16(t.k[mt][ks], qf[ks], s[mt]);
     }
     // s[mt][i] is the score of key t0 + 16*mt + 4*quad + i for head lane%16
     const bool partial = t0 + kTileKeys > mask_from;    // wave-uniform
+    const bool below = M::kWindow && t0 < rm.lo_until;  // wave-uniform: the tile holds keys before some window
     float tmax = -INFINITY;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float x = s[mt][i] * sc;
-            if (partial && t0 + 16 * mt + 4 * quad + i >= lim) x = -INFINITY;   // mask by selection
+            const int32_t key = t0 + 16 * mt + 4 * quad + i;
+            float x;
+            if (M::kScore) {
+                // soft cap: c * tanh(y / c) with tanh(z) = 1 - 2 / (1 + e^(2z)); then the linear position bias;
+                // everything lands in the log2 domain
+                if (rm.cap_in > 0.f) {
+                    const float e2z = __builtin_amdgcn_exp2f(s[mt][i] * rm.cap_in * (2.f * kLog2e));
+                    x = rm.cap_out * (1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e2z));
+                } else {
+                    x = s[mt][i] * sc;
+                }
+                x = __builtin_fmaf(rm.slope2, (float)(key - rm.pos), x);
+            } else {
+                x = s[mt][i] * sc;
+            }
+            if (partial && key >= lim) x = -INFINITY;   // mask by selection
+            if (below && key < rm.lo) x = -INFINITY;
             s[mt][i] = x;
             tmax = fmaxf(tmax, x);
         }
@@ -166,16 +183,14 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
     // time in this HBM-bound kernel, so the second product is free and removes the 2^-9 weight rounding that
     // would otherwise dominate the error of short contexts.
     uint4 pb, pl;
-    pb.x = pack_bf16(s[0][0], s[0][1]);
-    pb.y = pack_bf16(s[0][2], s[0][3]);
-    pb.z = pack_bf16(s[1][0], s[1][1]);
-    pb.w = pack_bf16(s[1][2], s[1][3]);
-    pl.x = pack_bf16(s[0][0] - __uint_as_float(pb.x << 16), s[0][1] - __uint_as_float(pb.x & 0xffff0000u));
-    pl.y = pack_bf16(s[0][2] - __uint_as_float(pb.y << 16), s[0][3] - __uint_as_float(pb.y & 0xffff0000u));
-    pl.z = pack_bf16(s[1][0] - __uint_as_float(pb.z << 16), s[1][1] - __uint_as_float(pb.z & 0xffff0000u));
-    pl.w = pack_bf16(s[1][2] - __uint_as_float(pb.w << 16), s[1][3] - __uint_as_float(pb.w & 0xffff0000u));
-    const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pb);
-    const bf16x8 pfrag_lo = __builtin_bit_cast(bf16x8, pl);
+    pb.x = E::pack(s[0][0], s[0][1]);
+    pb.y = E::pack(s[0][2], s[0][3]);
+    pb.z = E::pack(s[1][0], s[1][1]);
+    pb.w = E::pack(s[1][2], s[1][3]);
+    pl.x = E::pack(s[0][0] - E::lo_of(pb.x), s[0][1] - E::hi_of(pb.x));
+    pl.y = E::pack(s[0][2] - E::lo_of(pb.y), s[0][3] - E::hi_of(pb.y));
+    pl.z = E::pack(s[1][0] - E::lo_of(pb.z), s[1][1] - E::hi_of(pb.z));
+    pl.w = E::pack(s[1][2] - E::lo_of(pb.w), s[1][3] - E::hi_of(pb.w));
     // in-register 8x8 transpose of V, one head_dim column (j) at a time, feeding the A operand
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -185,8 +200,8 @@ __device__ __forceinline__ void compute_tile(State& st, const Tile& t, const bf1
         a.y = __builtin_amdgcn_perm(word(t.v[3], j / 2), word(t.v[2], j / 2), sel);
         a.z = __builtin_amdgcn_perm(word(t.v[5], j / 2), word(t.v[4], j / 2), sel);
         a.w = __builtin_amdgcn_perm(word(t.v[7], j / 2), word(t.v[6], j / 2), sel);
-        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pfrag, st.o[j], 0, 0, 0);
-        st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pfrag_lo, st.o[j], 0, 0, 0);
+        st.o[j] = E::mfma16(a, pb, st.o[j]);
+        st.o[j] = E::mfma16(a, pl, st.o[j]);
     }
 }
 
@@ -204,24 +219,34 @@ __device__ __forceinline__ int32_t tiles_of(int32_t len) { return (len + kTileKe
 // Tiles of sequence i in the stream.  RAGGED (called from the prefill entry point): only sequences whose
 // q_len * G rows fit the 16 columns of the matrix instruction take part; the others hold no tiles here and are
 // left to the prefill kernel.
+// A sliding window (window > 0) removes the tiles that lie wholly before the earliest window of the sequence's
+// queries from the stream: the work of a sequence is ceil((len - first_key) / 32) tiles, first_key a multiple of 32.
+__device__ __forceinline__ int32_t first_key_of(int32_t len, int32_t q_len, int32_t window)
+{
+    if (window <= 0) return 0;
+    return max(len - q_len - window + 1, 0) & ~(kTileKeys - 1);
+}
+
 template <bool RAGGED>
 __device__ __forceinline__ int32_t seq_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
-                                             int32_t G, int32_t i)
+                                             int32_t G, int32_t i, int32_t window)
 {
+    int32_t q_len = 1;
     if (RAGGED) {
-        const int32_t q_len = cu_q_lens[i + 1] - cu_q_lens[i];
+        q_len = cu_q_lens[i + 1] - cu_q_lens[i];
         if (q_len < 1 || q_len * G > 16) return 0;
     }
-    return tiles_of(seq_lens[i]);
+    const int32_t len = seq_lens[i];
+    return tiles_of(len - first_key_of(len, q_len, window));
 }
 
 // Sum of tiles over the batch; every lane returns the same value.
 template <bool RAGGED>
 __device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
-                                               int32_t G, int32_t batch, int lane)
+                                               int32_t G, int32_t batch, int lane, int32_t window)
 {
     int32_t n = 0;
-    for (int32_t i = lane; i < batch; i += 64) n += seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, i);
+    for (int32_t i = lane; i < batch; i += 64) n += seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, i, window);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
     return n;
@@ -230,15 +255,15 @@ __device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_l
 // Sequence that holds global tile g (0 <= g < total) and the number of tiles before that sequence.
 template <bool RAGGED>
 __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
-                                            int32_t G, int32_t batch, int32_t g, int lane, int32_t& seq,
-                                            int32_t& tiles_before)
+                                            int32_t G, int32_t batch, int32_t g, int lane, int32_t window,
+                                            int32_t& seq, int32_t& tiles_before)
 {
     int32_t base = 0;
     seq = batch;
     tiles_before = 0;
     for (int32_t blk = 0; blk < batch; blk += 64) {
         const int32_t idx = blk + lane;
-        const int32_t n = idx < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, idx) : 0;
+        const int32_t n = idx < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, idx, window) : 0;
         int32_t inc = n;                                   // inclusive scan over the 64 lanes
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -260,14 +285,17 @@ __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens
 // RAGGED: launched from the prefill entry point for the sequences with few queries (q_len * G <= 16): the 16
 // columns are (query, head) pairs, column = query * G + head, each with its own causal bound; q / out / lse rows
 // come from cu_q_lens; partials are 16 rows per KV head.
-template <int NW, bool UNIFORM, bool RAGGED>
+// E: element traits (bf16 / fp16).  M: compile-time policy of the mask / score hooks (document masks are not
+// taken here).
+template <int NW, bool UNIFORM, bool RAGGED, typename E, typename M>
 __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch,
     int32_t num_q_heads, int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse,
     int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last, const int32_t* __restrict__ cu_q_lens,
-    int32_t causal)
+    int32_t causal, ModArgs mods)
 {
+    const int32_t window = M::kWindow ? mods.window : 0;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int32_t w = blockIdx.x;
@@ -281,7 +309,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     int32_t total, g, g_end, s, before;
     if (batch <= 64) {
         // one read of the lengths serves both the total and the search for this workgroup's first sequence
-        const int32_t n = lane < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, lane) : 0;
+        const int32_t n = lane < batch ? seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, lane, window) : 0;
         int32_t inc = n;                                   // inclusive scan over the 64 lanes
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -297,12 +325,12 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         s = __ffsll((unsigned long long)hit) - 1;
         before = __shfl(inc, s, 64) - __shfl(n, s, 64);
     } else {
-        total = total_tiles<RAGGED>(seq_lens, cu_q_lens, G, batch, lane);
+        total = total_tiles<RAGGED>(seq_lens, cu_q_lens, G, batch, lane, window);
         const int32_t nwg = min((int32_t)gridDim.x, total);
         if (w >= nwg) return;
         g = (int32_t)(((int64_t)w * total) / nwg);
         g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
-        locate_tile<RAGGED>(seq_lens, cu_q_lens, G, batch, g, lane, s, before);
+        locate_tile<RAGGED>(seq_lens, cu_q_lens, G, batch, g, lane, window, s, before);
     }
     s = __builtin_amdgcn_readfirstlane(s);
     before = __builtin_amdgcn_readfirstlane(before);
@@ -323,21 +351,45 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     while (g < g_end) {
         // segment: tiles [t_begin, t_end) of sequence s
         const int32_t len = seq_lens[s];
-        const int32_t nt = seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, s);
+        const int32_t nt = seq_tiles<RAGGED>(seq_lens, cu_q_lens, G, s, window);
         if (nt == 0) { ++s; continue; }                    // sequences without tiles in this stream
         const int32_t t_begin = g - before;
         const int32_t t_end = min(nt, g_end - before);
-        const int32_t c0 = t_begin * kTileKeys;
-        const int32_t c1 = min(len, t_end * kTileKeys);
         // this lane's column: query qi of the sequence's q_len, head h (valid if r16 < rows)
-        int32_t rows = G, qi = 0, q_row = s, lim = c1;
+        int32_t rows = G, qi = 0, q_row = s, q_len = 1;
         if (RAGGED) {
             const int32_t q_begin = cu_q_lens[s];
-            const int32_t q_len = cu_q_lens[s + 1] - q_begin;
+            q_len = cu_q_lens[s + 1] - q_begin;
             rows = q_len * G;
             qi = min(r16, rows - 1) / G;
             q_row = q_begin + qi;
-            if (causal) lim = min(c1, len - q_len + qi + 1);   // keys 0 .. len - q_len + qi
+        }
+        const int32_t key0 = first_key_of(len, q_len, window);   // the stream's first key of this sequence
+        const int32_t c0 = key0 + t_begin * kTileKeys;
+        const int32_t c1 = min(len, key0 + t_end * kTileKeys);
+        const int32_t pos = len - q_len + qi;              // this row's position
+        int32_t lim = c1;
+        if (RAGGED && causal) lim = min(c1, pos + 1);      // keys 0 .. pos
+        RowMods rm;
+        rm.lo = 0;
+        rm.lo_until = 0;
+        rm.pos = pos;
+        rm.slope2 = 0.f;
+        rm.cap_in = 0.f;
+        rm.cap_out = 0.f;
+        rm.scale = scale;
+        if (M::kWindow && window > 0) {
+            rm.lo = pos - window + 1;                      // |j - pos| < window, lower side
+            rm.lo_until = len - window;                    // the last row's lower bound is the largest
+            if (RAGGED && !causal) lim = min(lim, pos + window);
+        }
+        if (M::kScore) {
+            if (mods.alibi_slopes && r16 < rows)
+                rm.slope2 = mods.alibi_slopes[kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16)] * kLog2e;
+            if (mods.softcap > 0.f) {
+                rm.cap_in = scale / mods.softcap;
+                rm.cap_out = mods.softcap * kLog2e;
+            }
         }
         const int32_t mask_from = RAGGED ? c1 - 16 : c1;   // q_len <= 16: no bound lies further below the end
         const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16);
@@ -346,12 +398,11 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 
         // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
         // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
-        bf16x8 qf[4];
+        uint4 qf[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            uint4 v = uint4{0, 0, 0, 0};
-            if (r16 < rows) v = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
-            qf[ks] = __builtin_bit_cast(bf16x8, v);
+            qf[ks] = uint4{0, 0, 0, 0};
+            if (r16 < rows) qf[ks] = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
         }
         State st;
 #pragma unroll
@@ -365,16 +416,16 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
             if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
-            compute_tile<RAGGED>(st, ta, qf, sc, t0, lim, mask_from, quad);
+            compute_tile<RAGGED, E, M>(st, ta, qf, sc, t0, lim, mask_from, quad, rm);
             if (t1 >= c1) break;
             if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
-            compute_tile<RAGGED>(st, tb, qf, sc, t1, lim, mask_from, quad);
+            compute_tile<RAGGED, E, M>(st, tb, qf, sc, t1, lim, mask_from, quad, rm);
         }
 
         float l = st.l;
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
-        const bool whole = t_begin == 0 && t_end == nt;    // the sequence lies inside this workgroup
+        const bool whole = t_begin == 0 && t_end == nt;    // the sequence's stream lies inside this workgroup
         if (r16 < rows) {
             // l == 0: a row whose causal bound lies before this segment (RAGGED only)
             const float inv = (!RAGGED || l > 0.f) ? 1.f / l : 0.f;
@@ -383,10 +434,10 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     uint4 wv;
-                    wv.x = pack_bf16(st.o[0][r] * inv, st.o[1][r] * inv);
-                    wv.y = pack_bf16(st.o[2][r] * inv, st.o[3][r] * inv);
-                    wv.z = pack_bf16(st.o[4][r] * inv, st.o[5][r] * inv);
-                    wv.w = pack_bf16(st.o[6][r] * inv, st.o[7][r] * inv);
+                    wv.x = E::pack(st.o[0][r] * inv, st.o[1][r] * inv);
+                    wv.y = E::pack(st.o[2][r] * inv, st.o[3][r] * inv);
+                    wv.z = E::pack(st.o[4][r] * inv, st.o[5][r] * inv);
+                    wv.w = E::pack(st.o[6][r] * inv, st.o[7][r] * inv);
                     *reinterpret_cast<uint4*>(out + o_idx * kD + 32 * quad + 8 * r) = wv;
                 }
                 if (lse && quad == 0) lse[o_idx] = lse_nat;
@@ -414,17 +465,29 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     }
 }
 
-template <int NW>
+template <int NW, typename E, typename M>
 void launch_nw(const AttnArgs& a, hipStream_t stream)
 {
     const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), 1);
     const bool uniform = a.cache.page_size >= 16;
-    auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true> : paged_decode_mfma_kernel<NW, false, true>)
-                            : (uniform ? paged_decode_mfma_kernel<NW, true, false>
-                                       : paged_decode_mfma_kernel<NW, false, false>);
+    auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true, E, M>
+                                       : paged_decode_mfma_kernel<NW, false, true, E, M>)
+                            : (uniform ? paged_decode_mfma_kernel<NW, true, false, E, M>
+                                       : paged_decode_mfma_kernel<NW, false, false, E, M>);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                        a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.part_o,
-                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal);
+                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal, a.mods);
+}
+
+template <typename E, typename M>
+void launch_em(const AttnArgs& a, hipStream_t stream)
+{
+    switch (decode_mfma_heads_per_wg(a.cache.num_kv_heads)) {
+        case 8: launch_nw<8, E, M>(a, stream); break;
+        case 4: launch_nw<4, E, M>(a, stream); break;
+        case 2: launch_nw<2, E, M>(a, stream); break;
+        default: launch_nw<1, E, M>(a, stream); break;
+    }
 }
 
 }  // namespace
@@ -436,7 +499,8 @@ int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads)
 
 bool decode_mfma_supported(const AttnArgs& a)
 {
-    if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
+    if ((a.dtype != PA_DTYPE_BF16 && a.dtype != PA_DTYPE_F16) || a.cache.head_dim != kD) return false;
+    if (a.has_mods && a.mods.doc_ids) return false;    // document masks: portable kernel
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
     if (G > 16) return false;
     if (a.cache.num_kv_heads > 65535 * 8) return false;
@@ -450,11 +514,13 @@ bool decode_mfma_supported(const AttnArgs& a)
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream)
 {
     ProfileScope prof("paged_decode_mfma_kernel", stream);
-    switch (decode_mfma_heads_per_wg(a.cache.num_kv_heads)) {
-        case 8: launch_nw<8>(a, stream); break;
-        case 4: launch_nw<4>(a, stream); break;
-        case 2: launch_nw<2>(a, stream); break;
-        default: launch_nw<1>(a, stream); break;
+    typedef Mods<true, true, false> WindowScore;
+    if (a.dtype == PA_DTYPE_BF16) {
+        if (a.has_mods) launch_em<ElemBf16, WindowScore>(a, stream);
+        else launch_em<ElemBf16, NoMods>(a, stream);
+    } else {
+        if (a.has_mods) launch_em<ElemF16, WindowScore>(a, stream);
+        else launch_em<ElemF16, NoMods>(a, stream);
     }
     return launch_status();
 }

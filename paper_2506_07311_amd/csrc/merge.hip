@@ -8,7 +8,19 @@ namespace pa {
 
 namespace {
 
-template <bool BF16>
+// OUT: element type of `out` as a pa_dtype value.
+template <int OUT>
+__device__ __forceinline__ void store_out(void* out, int64_t i, float r)
+{
+    if (OUT == PA_DTYPE_BF16)
+        reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)float_to_bf16_bits(r);
+    else if (OUT == PA_DTYPE_F16)
+        reinterpret_cast<uint16_t*>(out)[i] = (uint16_t)float_to_f16_bits(r);
+    else
+        reinterpret_cast<float*>(out)[i] = r;
+}
+
+template <int OUT>
 __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
     float* __restrict__ lse, const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ seq_lens,
@@ -24,20 +36,16 @@ __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
 
     float M = -INFINITY;
     for (int32_t c = 0; c < n; ++c) M = fmaxf(M, pl[c]);
+    const bool none = M == -INFINITY;            // no chunk holds a visible key (masks can empty every chunk)
     float wsum = 0.f, acc = 0.f;
-    for (int32_t c = 0; c < n; ++c) {
+    for (int32_t c = 0; c < n && !none; ++c) {
         const float w = expf(pl[c] - M);
         wsum += w;
         if (e < d) acc = fmaf(w, po[(int64_t)c * d + e], acc);
     }
-    const float r = n > 0 ? acc / wsum : 0.f;
-    if (e < d) {
-        if (BF16)
-            reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
-        else
-            reinterpret_cast<float*>(out)[o_idx * d + e] = r;
-    }
-    if (lse && e == 0) lse[o_idx] = n > 0 ? M + logf(wsum) : -INFINITY;
+    const float r = !none ? acc / wsum : 0.f;
+    if (e < d) store_out<OUT>(out, o_idx * d + e, r);
+    if (lse && e == 0) lse[o_idx] = !none ? M + logf(wsum) : -INFINITY;
 }
 
 // Tile-stream layout: sequence s was cut by the workgroups seg_first[s] .. seg_last[s]; workgroup w left its
@@ -50,7 +58,7 @@ constexpr int kMergeThreads = 128;
 // RAGGED (the few-query sequences of a prefill call): one workgroup per (sequence, KV head, column); column
 // c of the 16 is query c / G, head c % G of the group; partials are 16 rows per KV head; sequences that did not
 // take that path (q_len * G > 16) are skipped.
-template <bool BF16, bool RAGGED>
+template <int OUT, bool RAGGED>
 __global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
     float* __restrict__ lse, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ seg_first,
@@ -116,10 +124,7 @@ __global__ __launch_bounds__(kMergeThreads) void paged_attention_merge_stream_ke
         }
         for (; c < n; ++c) acc = fmaf(w_s[c], po[(int64_t)c * step], acc);
         const float r = (n > 0 && !no_keys) ? acc / wsum : 0.f;
-        if (BF16)
-            reinterpret_cast<uint16_t*>(out)[o_idx * d + e] = (uint16_t)float_to_bf16_bits(r);
-        else
-            reinterpret_cast<float*>(out)[o_idx * d + e] = r;
+        store_out<OUT>(out, o_idx * d + e, r);
     }
     if (lse && tid == 0) lse[o_idx] = (n > 0 && !no_keys) ? M + logf(wsum) : -INFINITY;
 }
@@ -132,33 +137,28 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     const int threads = ((a.cache.head_dim + 63) / 64) * 64;
     ProfileScope prof("paged_attention_merge_kernel", stream);
-    if (a.stream_split && a.cu_q_lens) {   // few-query sequences of a prefill call (bf16 only)
-        const int64_t rblocks = (int64_t)a.batch * a.cache.num_kv_heads * 16;
-        if (rblocks > 0x7fffffffLL || a.dtype != PA_DTYPE_BF16) return PA_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((paged_attention_merge_stream_kernel<true, true>), dim3((uint32_t)rblocks),
-                           dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens, a.seg_first,
-                           a.seg_last, a.num_q_heads, a.cache.head_dim, a.cu_q_lens, a.cache.num_kv_heads);
-        return launch_status();
-    }
     if (a.stream_split) {
-        if (a.dtype == PA_DTYPE_BF16)
-            hipLaunchKernelGGL((paged_attention_merge_stream_kernel<true, false>), dim3((uint32_t)blocks),
-                               dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens,
-                               a.seg_first, a.seg_last, a.num_q_heads, a.cache.head_dim, nullptr, a.cache.num_kv_heads);
-        else
-            hipLaunchKernelGGL((paged_attention_merge_stream_kernel<false, false>), dim3((uint32_t)blocks),
-                               dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out, a.lse, a.seq_lens,
-                               a.seg_first, a.seg_last, a.num_q_heads, a.cache.head_dim, nullptr, a.cache.num_kv_heads);
+        // tile-stream partials of the MFMA decode kernel (16-bit pools only); with cu_q_lens: the few-query
+        // sequences of a prefill call
+        const bool ragged = a.cu_q_lens != nullptr;
+        const int64_t sblocks = ragged ? (int64_t)a.batch * a.cache.num_kv_heads * 16 : blocks;
+        if (sblocks > 0x7fffffffLL || a.dtype == PA_DTYPE_F32) return PA_ERR_UNSUPPORTED;
+        auto kern = a.dtype == PA_DTYPE_BF16
+                        ? (ragged ? paged_attention_merge_stream_kernel<PA_DTYPE_BF16, true>
+                                  : paged_attention_merge_stream_kernel<PA_DTYPE_BF16, false>)
+                        : (ragged ? paged_attention_merge_stream_kernel<PA_DTYPE_F16, true>
+                                  : paged_attention_merge_stream_kernel<PA_DTYPE_F16, false>);
+        hipLaunchKernelGGL(kern, dim3((uint32_t)sblocks), dim3(kMergeThreads), 0, stream, a.part_o, a.part_lse, a.out,
+                           a.lse, a.seq_lens, a.seg_first, a.seg_last, a.num_q_heads, a.cache.head_dim, a.cu_q_lens,
+                           a.cache.num_kv_heads);
         return launch_status();
     }
-    if (a.dtype == PA_DTYPE_BF16)
-        hipLaunchKernelGGL(paged_attention_merge_kernel<true>, dim3((uint32_t)blocks), dim3(threads), 0, stream,
-                           a.part_o, a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads,
-                           a.cache.head_dim, a.causal, a.plan.chunk, a.plan.nsplit);
-    else
-        hipLaunchKernelGGL(paged_attention_merge_kernel<false>, dim3((uint32_t)blocks), dim3(threads), 0, stream,
-                           a.part_o, a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads,
-                           a.cache.head_dim, a.causal, a.plan.chunk, a.plan.nsplit);
+    auto kern = a.dtype == PA_DTYPE_BF16  ? paged_attention_merge_kernel<PA_DTYPE_BF16>
+                : a.dtype == PA_DTYPE_F16 ? paged_attention_merge_kernel<PA_DTYPE_F16>
+                                          : paged_attention_merge_kernel<PA_DTYPE_F32>;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(threads), 0, stream, a.part_o, a.part_lse, a.out, a.lse,
+                       a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads, a.cache.head_dim, a.causal, a.plan.chunk,
+                       a.plan.nsplit);
     return launch_status();
 }
 

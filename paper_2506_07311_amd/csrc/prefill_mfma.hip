@@ -36,11 +36,8 @@ namespace pa {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef mfma_f32x16 f32x16;
 
 constexpr int kD = 128;
 constexpr int kBM = 128;              // queries per workgroup
@@ -55,12 +52,6 @@ constexpr int kBufBytes = 2 * kTileBytes;
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 // ---------------------------------------------------------------------------------------------------
 // Tile fetch.  Wave w issues, for i < 4, one load-to-LDS instruction for K and one for V that fill rows
@@ -129,9 +120,9 @@ __device__ __forceinline__ void fetch_tile(char* dst, const PageIds& p, const Ca
     fetch_rows<UNIFORM>(dst + 48 * kRow, cache, p.p3, t0 + row + 48, last_key, lane_off);
 }
 
-__device__ __forceinline__ bf16x8 lds_frag(const char* p)
+__device__ __forceinline__ uint4 lds_frag(const char* p)
 {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+    return *reinterpret_cast<const uint4*>(p);
 }
 
 // V^T operand of the second product for 32 head_dim columns and one 16-key step, from row-major V.
@@ -142,13 +133,13 @@ __device__ __forceinline__ bf16x8 lds_frag(const char* p)
 struct tr_pair {
     s16x4 lo, hi;
 };
-__device__ __forceinline__ bf16x8 lds_frag_tr(const char* lo, const char* hi)
+__device__ __forceinline__ uint4 lds_frag_tr(const char* lo, const char* hi)
 {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     tr_pair r;
     r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lo));
     r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(hi));
-    return __builtin_bit_cast(bf16x8, r);
+    return __builtin_bit_cast(uint4, r);
 }
 
 // max over the two lanes that share a query (lane and lane ^ 32) without an LDS round trip
@@ -227,11 +218,11 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4
 // O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps).  vbuf = V part of the tile buffer,
 // vx[2t], vx[2t+1] = this lane's swizzled transpose-load offsets (slots 0-3 / 4-7) for the 32 columns t.  P^T as B operand of a step:
 // elements e = 0..7 <-> weights 8*step + e.
-template <bool PRECISE>
+template <bool PRECISE, typename E>
 __device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const char* vbuf, int half,
                                         const uint32_t (&vx)[8])
 {
-    bf16x8 va[4], vb[4];
+    uint4 va[4], vb[4];
     const char* v0 = vbuf + (32 * half) * kRow;
 #pragma unroll
     for (int t = 0; t < 4; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
@@ -241,46 +232,45 @@ __device__ __forceinline__ void half_pv(f32x16 (&o)[4], const f32x16& s, const c
     for (int st = 0; st < 2; ++st) {
         const int r0 = 8 * st;
         uint4 w, wl;
-        w.x = pack_bf16(s[r0 + 0], s[r0 + 1]);
-        w.y = pack_bf16(s[r0 + 2], s[r0 + 3]);
-        w.z = pack_bf16(s[r0 + 4], s[r0 + 5]);
-        w.w = pack_bf16(s[r0 + 6], s[r0 + 7]);
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, w);
-        if (PRECISE) {   // second bf16 term of the weights: p = hi + lo, lo = bf16(p - hi)
-            wl.x = pack_bf16(s[r0 + 0] - __uint_as_float(w.x << 16), s[r0 + 1] - __uint_as_float(w.x & 0xffff0000u));
-            wl.y = pack_bf16(s[r0 + 2] - __uint_as_float(w.y << 16), s[r0 + 3] - __uint_as_float(w.y & 0xffff0000u));
-            wl.z = pack_bf16(s[r0 + 4] - __uint_as_float(w.z << 16), s[r0 + 5] - __uint_as_float(w.z & 0xffff0000u));
-            wl.w = pack_bf16(s[r0 + 6] - __uint_as_float(w.w << 16), s[r0 + 7] - __uint_as_float(w.w & 0xffff0000u));
+        w.x = E::pack(s[r0 + 0], s[r0 + 1]);
+        w.y = E::pack(s[r0 + 2], s[r0 + 3]);
+        w.z = E::pack(s[r0 + 4], s[r0 + 5]);
+        w.w = E::pack(s[r0 + 6], s[r0 + 7]);
+        if (PRECISE) {   // second 16-bit term of the weights: p = hi + lo, lo = round(p - hi)
+            wl.x = E::pack(s[r0 + 0] - E::lo_of(w.x), s[r0 + 1] - E::hi_of(w.x));
+            wl.y = E::pack(s[r0 + 2] - E::lo_of(w.y), s[r0 + 3] - E::hi_of(w.y));
+            wl.z = E::pack(s[r0 + 4] - E::lo_of(w.z), s[r0 + 5] - E::hi_of(w.z));
+            wl.w = E::pack(s[r0 + 6] - E::lo_of(w.w), s[r0 + 7] - E::hi_of(w.w));
         } else {
             wl = w;
         }
-        const bf16x8 pl = __builtin_bit_cast(bf16x8, wl);
-        const bf16x8 (&cur)[4] = st ? vb : va;
+        const uint4 (&cur)[4] = st ? vb : va;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pf, o[t], 0, 0, 0);
-            if (PRECISE) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[t], pl, o[t], 0, 0, 0);
+            o[t] = E::mfma32(cur[t], w, o[t]);
+            if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
         }
     }
 }
 
 // S^T of half tile `half` (32 keys) against the wave's 32 queries: 8 chained matrix instructions, the K operand
 // reads kept four ahead.  kx[ks] = this lane's swizzled operand offset for head_dim step ks.
+template <typename E>
 __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int half, const uint32_t (&kx)[8],
-                                            const bf16x8 (&qf)[8])
+                                            const uint4 (&qf)[8])
 {
     s = (f32x16)(0.f);   // folded into the first matrix instruction's accumulator operand
     const char* kh = kbuf + (32 * half) * kRow;
-    bf16x8 ka[4];
+    uint4 ka[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) ka[i] = lds_frag(kh + kx[i]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i], s, 0, 0, 0);
+        s = E::mfma32(ka[i], qf[i], s);
         ka[i] = lds_frag(kh + kx[i + 4]);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qf[i + 4], s, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) s = E::mfma32(ka[i], qf[i + 4], s);
 }
 
 // One 64-key tile for one wave, processed as two half tiles of 32 keys so that, within the wave, the softmax of
@@ -289,21 +279,21 @@ __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int hal
 //     vector ALU:            softmax(h0)    softmax(h1)
 // buf = tile buffer (K rows, then V rows); key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's
 // query may see (MASK only); sc = scale * log2(e) > 0.
-template <bool PRECISE, bool MASK>
+template <bool PRECISE, bool MASK, typename E>
 __device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[8], const uint32_t (&vx)[8],
-                                            const bf16x8 (&qf)[8], f32x16 (&o)[4], float& m, float& l, float sc,
+                                            const uint4 (&qf)[8], f32x16 (&o)[4], float& m, float& l, float sc,
                                             int32_t key0, int32_t nk)
 {
     f32x16 s0, s1, p;
-    half_scores(s0, buf, 0, kx, qf);
-    half_scores(s1, buf, 1, kx, qf);
+    half_scores<E>(s0, buf, 0, kx, qf);
+    half_scores<E>(s1, buf, 1, kx, qf);
     half_softmax<MASK, true>(p, s0, o, m, l, sc, key0, nk);
-    half_pv<PRECISE>(o, p, buf + kTileBytes, 0, vx);
+    half_pv<PRECISE, E>(o, p, buf + kTileBytes, 0, vx);
     half_softmax<MASK, false>(p, s1, o, m, l, sc, key0 + 32, nk);
-    half_pv<PRECISE>(o, p, buf + kTileBytes, 1, vx);
+    half_pv<PRECISE, E>(o, p, buf + kTileBytes, 1, vx);
 }
 
-template <bool PRECISE, bool UNIFORM>
+template <bool PRECISE, bool UNIFORM, typename E>
 __device__ __forceinline__ void prefill_body(
     char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
@@ -371,10 +361,9 @@ __device__ __forceinline__ void prefill_body(
 
     const int64_t row = (int64_t)(q_begin + qi_c) * num_q_heads + h;
     // Q as B operand: lane%32 = query, step ks covers head_dim elements 16*ks + 8*hh .. +7
-    bf16x8 qf[8];
+    uint4 qf[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-        qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(q + row * kD + 16 * ks + 8 * hh));
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(q + row * kD + 16 * ks + 8 * hh);
 
     f32x16 o[4];
 #pragma unroll
@@ -425,9 +414,9 @@ __device__ __forceinline__ void prefill_body(
         }
         if (t0 < nk_wave) {                                  // wave-uniform: else nothing for this wave here
             if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
-                attend_tile<PRECISE, true>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, true, E>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
             else
-                attend_tile<PRECISE, false>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, false, E>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
         }
         __syncthreads();
         if (t + 1 >= n_tiles) break;
@@ -438,9 +427,9 @@ __device__ __forceinline__ void prefill_body(
         }
         if (t1 < nk_wave) {
             if (t1 + kBN > nk_wave_min)
-                attend_tile<PRECISE, true>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
+                attend_tile<PRECISE, true, E>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
             else
-                attend_tile<PRECISE, false>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
+                attend_tile<PRECISE, false, E>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
         }
         __syncthreads();
     }
@@ -473,8 +462,8 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             uint2 w;
-            w.x = pack_bf16(o[t][4 * a + 0] * inv, o[t][4 * a + 1] * inv);
-            w.y = pack_bf16(o[t][4 * a + 2] * inv, o[t][4 * a + 3] * inv);
+            w.x = E::pack(o[t][4 * a + 0] * inv, o[t][4 * a + 1] * inv);
+            w.y = E::pack(o[t][4 * a + 2] * inv, o[t][4 * a + 3] * inv);
             *reinterpret_cast<uint2*>(orow + 32 * t + 8 * a + 4 * hh) = w;
         }
     if (lse && hh == 0) lse[row] = l > 0.f ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
@@ -482,7 +471,7 @@ __device__ __forceinline__ void prefill_body(
 
 // Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
 // workgroup runs exactly one of them, decided by its context length.
-template <bool UNIFORM>
+template <bool UNIFORM, typename E>
 __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
@@ -491,9 +480,9 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
 {
     __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
     __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
-    prefill_body<false, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    prefill_body<false, UNIFORM, E>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                  num_q_heads, max_blocks, scale, causal, plan);
-    prefill_body<true, UNIFORM>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    prefill_body<true, UNIFORM, E>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                 num_q_heads, max_blocks, scale, causal, plan);
 }
 
@@ -501,7 +490,7 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
 
 bool prefill_mfma_supported(const AttnArgs& a)
 {
-    if (a.dtype != PA_DTYPE_BF16 || a.cache.head_dim != kD) return false;
+    if ((a.dtype != PA_DTYPE_BF16 && a.dtype != PA_DTYPE_F16) || a.cache.head_dim != kD) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
     return true;
 }
@@ -533,7 +522,10 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     {
         ProfileScope prof("paged_prefill_mfma_kernel", stream);
         // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
-        auto kern = a.cache.page_size >= 16 ? paged_prefill_mfma_kernel<true> : paged_prefill_mfma_kernel<false>;
+        const bool uniform = a.cache.page_size >= 16;
+        auto kern = a.dtype == PA_DTYPE_BF16
+                        ? (uniform ? paged_prefill_mfma_kernel<true, ElemBf16> : paged_prefill_mfma_kernel<false, ElemBf16>)
+                        : (uniform ? paged_prefill_mfma_kernel<true, ElemF16> : paged_prefill_mfma_kernel<false, ElemF16>);
         hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                            a.cu_q_lens, a.block_table, a.seq_lens, a.batch, (int32_t)tiles, a.num_q_heads, a.max_blocks,
                            a.scale, a.causal, plan);

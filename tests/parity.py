@@ -10,7 +10,10 @@ from paper_2506_07311_amd import workloads as W
 #   max-rel  = max |g - r| / max(|r|, rms(r))   -- floored at the reference tensor's RMS so that zero
 #              crossings do not blow the ratio up and an all-zero output cannot pass on max-abs alone
 # bf16 I/O with fp32 accumulation: 1e-2 / 2e-2.  fp32 I/O: 1e-5 / 1e-5.
-TOL = {torch.bfloat16: (1e-2, 2e-2), torch.float32: (1e-5, 1e-5)}
+# fp16 I/O with fp32 accumulation: the output's own rounding is 2^-11 relative (4.9e-4 at |out| = 1, 2e-3 at 4);
+# softmax weights enter the matrix cores with the same 2^-11: 2e-3 / 4e-3 (a fifth of the bf16 bound, as the
+# formats' mantissas suggest: 2^-11 vs 2^-8 would allow an eighth).
+TOL = {torch.bfloat16: (1e-2, 2e-2), torch.float32: (1e-5, 1e-5), torch.float16: (2e-3, 4e-3)}
 
 
 def errors(got: np.ndarray, ref: np.ndarray):
@@ -35,29 +38,44 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().double().cpu().numpy()
 
 
-def oracle_step(oracle, w: W.PagedWorkload, append=True):
-    """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse)."""
+def oracle_step(oracle, w: W.PagedWorkload, append=True, mods=None):
+    """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse).
+    mods: dict with any of window, softcap, alibi_slopes (numpy [Hq]), doc_ids (numpy int32 [B, stride])."""
     k, v = W.to_numpy(w.k_cache).copy(), W.to_numpy(w.v_cache).copy()
     bt = W.to_numpy(w.block_table)
     if append and w.seq_ids.numel():
         oracle.kv_append(k, v, W.to_numpy(w.k_new), W.to_numpy(w.v_new), W.to_numpy(w.seq_ids),
                          W.to_numpy(w.positions), bt)
     out, lse = oracle.attention(k, v, W.to_numpy(w.q), bt, W.to_numpy(w.seq_lens), w.scale, causal=w.causal,
-                                cu_q_lens=W.to_numpy(w.cu_q_lens))
+                                cu_q_lens=W.to_numpy(w.cu_q_lens), **(mods or {}))
     return k, v, out, lse
 
 
-def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True):
+def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, mods=None):
     """Append then attention through the C-ABI binding, in place on the workload's pools."""
+    kw = {}
+    if mods:
+        dev = w.q.device
+        kw = dict(window=mods.get("window", 0), softcap=mods.get("softcap", 0.0))
+        if mods.get("alibi_slopes") is not None:
+            kw["alibi_slopes"] = torch.tensor(np.asarray(mods["alibi_slopes"]), dtype=torch.float32, device=dev)
+        if mods.get("doc_ids") is not None:
+            kw["doc_ids"] = torch.tensor(np.asarray(mods["doc_ids"]), dtype=torch.int32, device=dev)
     if append and w.seq_ids.numel():
         pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
     if prefill is None:
         prefill = w.causal or w.max_q_len > 1 or w.total_q != w.batch
     lse = torch.full((w.total_q, w.num_q_heads), float("nan"), dtype=torch.float32, device=w.q.device) \
         if with_lse else None
-    if prefill:
+    if prefill and mods:
+        out = pa.paged_attention_prefill_mod(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
+                                             w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse, **kw)
+    elif prefill:
         out = pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
                                          w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse)
+    elif mods:
+        out = pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+                                            w.scale, lse=lse, **kw)
     else:
         out = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
                                         w.scale, lse=lse)
@@ -66,17 +84,19 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True):
 
 
 def _bits(a):
-    return a.view(np.uint32) if a.dtype == np.float32 else a      # NaN-poisoned slots compare by bit pattern
+    # NaN-poisoned slots compare by bit pattern
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16) if a.dtype == np.float16 else a
 
 
-def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None, tol=None):
+def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None, tol=None, mods=None):
     """Full parity of one step: pools bit-exact after the append, attention within tolerance.
     With ``seqs`` the oracle sees only those sequences (their pages copied out BEFORE the GPU path runs);
     the GPU path always runs the whole workload."""
     # the oracle runs first, on host copies taken before the GPU path touches the pools
     ref_w = w if seqs is None else W.restrict(w, seqs, device="cpu")
-    k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, ref_w)
-    out, lse = gpu_step(pa, w, prefill=prefill)
+    assert mods is None or seqs is None
+    k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, ref_w, mods=mods)
+    out, lse = gpu_step(pa, w, prefill=prefill, mods=mods)
     after = w if seqs is None else W.restrict(w, seqs, device="cpu")
     assert np.array_equal(_bits(W.to_numpy(after.k_cache)), _bits(k_ref)), f"{what}: K pool differs after append"
     assert np.array_equal(_bits(W.to_numpy(after.v_cache)), _bits(v_ref)), f"{what}: V pool differs after append"

@@ -486,3 +486,126 @@ def test_runtime_argument_errors(pa):
     with pytest.raises(binding.PagedAttnError):                        # q heads not a multiple of kv heads
         pa.paged_attention_decode(w.k_cache, w.v_cache, w.q[:, :7].contiguous(), w.block_table, w.seq_lens, 64, w.scale)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------ fp16 pools
+@pytest.mark.parametrize("d,P", [(128, 16), (128, 4), (64, 16), (256, 64)])
+def test_fp16_append_gather_decode_and_prefill(pa, oracle, d, P):
+    """fp16 pools (the paper's own precision): bit-exact data movement, attention on the matrix-core kernels
+    (head_dim 128) and on the portable kernel (other head dims)."""
+    lens = [300, 77, 1025, 0, 5]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=P,
+                        dtype=torch.float16, seed=60, device=DEV)
+    parity.check_step(pa, oracle, w, f"fp16 decode d={d} P={P}")
+    w = W.make_workload("t", seq_lens=lens, q_lens=[300, 3, 130, 0, 5], num_q_heads=8, num_kv_heads=2, head_dim=d,
+                        page_size=P, dtype=torch.float16, causal=True, seed=61, device=DEV)
+    parity.check_step(pa, oracle, w, f"fp16 prefill d={d} P={P}")
+    a = W.to_numpy(w.k_cache)
+    ok, ov = oracle.kv_gather(a, W.to_numpy(w.v_cache), W.to_numpy(w.block_table), W.to_numpy(w.seq_lens))
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=DEV)
+    gk, gv = pa.paged_kv_gather(w.k_cache, w.v_cache, w.block_table, w.seq_lens, cu, sum(lens), max(lens))
+    torch.cuda.synchronize()
+    assert np.array_equal(W.to_numpy(gk).view(np.uint16), ok.view(np.uint16))
+    assert np.array_equal(W.to_numpy(gv).view(np.uint16), ov.view(np.uint16))
+
+
+def test_fp16_configs_small(pa, oracle):
+    for n in (2, 3, 4, 5):
+        w = W.config(n, device=DEV, shrink=16)
+        for name in ("k_cache", "v_cache", "q", "k_new", "v_new"):
+            setattr(w, name, getattr(w, name).to(torch.float16))
+        w.dtype = torch.float16
+        parity.check_step(pa, oracle, w, f"fp16 config {n} / 16")
+
+
+def test_fp16_long_context_decode_sampled(pa, oracle):
+    """Many small weights: 16 x 32768 tokens; two sequences against the oracle."""
+    w = W.config(5, device=DEV, context=32768)
+    for name in ("k_cache", "v_cache", "q", "k_new", "v_new"):
+        setattr(w, name, getattr(w, name).to(torch.float16))
+    w.dtype = torch.float16
+    parity.check_step(pa, oracle, w, "fp16 16 x 32768", seqs=[3, 12])
+
+
+# ------------------------------------------------------------------------------------ mask / score hooks
+def alibi(Hq):
+    return np.array([2.0 ** (-8.0 * (h + 1) / Hq) for h in range(Hq)])
+
+
+def doc_ids(lens, seed, width=None):
+    rng = np.random.default_rng(seed)
+    width = width or max(lens) + 1
+    ids = np.zeros((len(lens), width), dtype=np.int32)
+    for s in range(len(lens)):
+        cuts = np.sort(rng.integers(0, max(lens[s], 1), size=4))
+        ids[s] = np.searchsorted(cuts, np.arange(width), side="right")
+    return ids
+
+
+MOD_CASES = [
+    dict(window=100),
+    dict(window=1),
+    dict(window=33),
+    dict(window=5000),
+    dict(softcap=2.0),
+    dict(alibi=True),
+    dict(window=257, softcap=5.0, alibi=True),
+    dict(docs=True),
+    dict(docs=True, window=300, alibi=True, softcap=3.0),
+]
+
+
+def build_mods(case, Hq, lens):
+    m = {}
+    if "window" in case:
+        m["window"] = case["window"]
+    if "softcap" in case:
+        m["softcap"] = case["softcap"]
+    if case.get("alibi"):
+        m["alibi_slopes"] = alibi(Hq)
+    if case.get("docs"):
+        m["doc_ids"] = doc_ids(lens, 7)
+    return m
+
+
+@pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 128), (torch.float32, 64)])
+def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
+    lens = [700, 64, 2049, 33, 1, 0, 300]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16, dtype=dtype,
+                        seed=70, device=DEV)
+    parity.check_step(pa, oracle, w, f"decode hooks {case}", mods=build_mods(case, 8, lens))
+
+
+@pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+@pytest.mark.parametrize("causal", [True, False])
+def test_prefill_with_mask_and_score_hooks(pa, oracle, case, causal):
+    lens = [400, 64, 700, 33, 0]
+    q_lens = [400, 10, 130, 1, 0]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, causal=causal, seed=71, device=DEV)
+    parity.check_step(pa, oracle, w, f"prefill hooks {case} causal={causal}", mods=build_mods(case, 8, lens))
+
+
+@pytest.mark.parametrize("wgs", [1, 7, 256])
+def test_windowed_decode_split_schedules(pa, oracle, wgs):
+    """The tile stream starts at the window: segments, merge and direct writes with a window in place."""
+    from paper_2506_07311_amd import binding
+    lens = [2049, 64, 0, 31, 1000, 4096, 1]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=72, device=DEV)
+    binding.pa_set_option("decode_workgroups", wgs)
+    try:
+        parity.check_step(pa, oracle, w, f"window 700 on {wgs} workgroups",
+                          mods=dict(window=700, alibi_slopes=alibi(32)))
+    finally:
+        binding.pa_set_option("decode_workgroups", 0)
+
+
+def test_hooks_switched_off_equal_the_plain_entry_points(pa):
+    w = W.make_workload("t", seq_lens=[700, 64, 300], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=73, device=DEV)
+    a = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale)
+    b = pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
