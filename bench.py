@@ -64,6 +64,11 @@ def parse():
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU-oracle baseline / parity leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the extra prefill measurement")
     ap.add_argument("--oracle-seqs", type=int, default=4, help="sequences of the workload the oracle is timed on")
+    ap.add_argument("--dtype", choices=["default", "bf16", "fp16"], default="default",
+                    help="16-bit element type of the pools (fp16 is the paper's own precision)")
+    ap.add_argument("--page-size", type=int, default=0, help="override the workload's page size (power of two)")
+    ap.add_argument("--window", type=int, default=0, help="decode workloads: sliding window in tokens (0 = off)")
+    ap.add_argument("--alibi", action="store_true", help="decode workloads: add a linear position bias per head")
     ap.add_argument("--launch", choices=["direct", "graph"], default="direct",
                     help="graph: capture one step (append + attention + merge) in a HIP graph and replay it; for the "
                          "small workloads, whose step is shorter than the host's launch overhead")
@@ -81,13 +86,13 @@ def time_steps(torch, step, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
-def run_oracle_sample(sub, out_gpu_rows):
+def run_oracle_sample(sub, out_gpu_rows, mods=None):
     """Time the CPU oracle (append + attention) on whole sequences of the workload (host copies taken
     before the GPU path ran) and compare the GPU rows of those sequences with it."""
     import oracle
     from tests import parity
     t0 = time.perf_counter()
-    _, _, ref, _ = parity.oracle_step(oracle, sub)
+    _, _, ref, _ = parity.oracle_step(oracle, sub, mods=mods)
     dt = time.perf_counter() - t0
     max_abs, max_rel = parity.errors(parity.to_f64(out_gpu_rows), ref)
     return dt, max_abs, max_rel, oracle.num_threads()
@@ -196,7 +201,20 @@ def main():
     cfg, P, ctx = WORKLOADS[args.workload]
     if args.workload == "page_manager_serving":
         return run_page_manager(torch, binding, args, P)
+    if args.page_size:
+        P = args.page_size
     w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
+    if args.dtype == "fp16" and w.dtype == torch.bfloat16:
+        # the same N(0,1) draws rounded to fp16 instead of bf16 (NaN poison survives the conversion)
+        for name in ("k_cache", "v_cache", "q", "k_new", "v_new"):
+            setattr(w, name, getattr(w, name).to(torch.float16))
+        w.dtype = torch.float16
+    mods = {}
+    if args.window:
+        mods["window"] = args.window
+    if args.alibi:
+        mods["alibi_slopes"] = torch.tensor([2.0 ** (-8.0 * (h + 1) / w.num_q_heads) for h in range(w.num_q_heads)],
+                                            dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     is_prefill = cfg in (3, 6, 7, 8)
     if args.workload == "gather_copy_calibration":
@@ -213,6 +231,9 @@ def main():
         if is_prefill:
             pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table, w.seq_lens,
                                        w.max_seq_len, w.scale, w.causal, out=out, workspace=ws)
+        elif mods:
+            pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+                                          w.scale, out=out, workspace=ws, **mods)
         else:
             pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
                                       out=out, workspace=ws)
@@ -252,16 +273,19 @@ def main():
 
     us = sec * 1e6
     kv_bytes = w.logical_kv_bytes()
+    if args.window and not is_prefill:   # only the window is read
+        kv_bytes = sum(min(L, args.window) for L in w.seq_lens_host) * 2 * w.num_kv_heads * w.head_dim * 2
     tokens = w.total_q                      # tokens produced (decode) / processed (prefill) per step
     result = {
         "metric": "paged_prefill_us_per_step" if is_prefill else "paged_decode_us_per_step",
         "value": round(us, 2), "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "dtype": {torch.bfloat16: "bf16", torch.float16: "f16", torch.float32: "f32"}[w.dtype], "data": "synthetic",
         "config": {"workload": args.workload, "batch": w.batch, "context": w.max_seq_len,
                    "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
                    "page_size": w.page_size, "pool_pages": w.num_pages, "step": "append + attention (+ merge)",
-                   "launch": args.launch},
+                   "launch": args.launch, **({"window": args.window} if args.window else {}),
+                   **({"alibi": True} if args.alibi else {})},
         "tokens_per_s": round(tokens / sec, 1),
         "kv_bytes_per_step": kv_bytes,
         "step_hbm_gbps": round(kv_bytes / sec / 1e9, 1),
@@ -304,7 +328,8 @@ def main():
     if not args.no_oracle:
         cu = w.cu_q_lens.cpu().tolist()
         rows = [r for s_ in seqs for r in range(cu[s_], cu[s_ + 1])]
-        dt, max_abs, max_rel, cores = run_oracle_sample(sub, out[rows])
+        omods = {k: (v.cpu().numpy() if hasattr(v, "cpu") else v) for k, v in mods.items()} or None
+        dt, max_abs, max_rel, cores = run_oracle_sample(sub, out[rows], omods)
         scale_up = w.batch / len(seqs)
         result["cpu_baseline"] = {"value": round(dt * scale_up * 1e6, 1), "unit": "us/step", "cores": cores,
                                   "kind": "oracle",
