@@ -177,7 +177,7 @@ __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
 }
 
 // Element traits of the 16-bit matrix-core kernels: packing with round-to-nearest-even, unpacking, and the two
-// matrix instructions.  Operands travel as uint4 (8 elements); the accumulators are fp32.
+// matrix instructions.  Operands travel as any 16-byte type (8 elements); the accumulators are fp32.
 typedef __attribute__((ext_vector_type(4))) float mfma_f32x4;
 typedef __attribute__((ext_vector_type(16))) float mfma_f32x16;
 
@@ -193,12 +193,14 @@ struct ElemBf16 {
     }
     __device__ static __forceinline__ float lo_of(uint32_t w) { return __uint_as_float(w << 16); }
     __device__ static __forceinline__ float hi_of(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-    __device__ static __forceinline__ mfma_f32x4 mfma16(const uint4& a, const uint4& b, mfma_f32x4 c)
+    template <typename A, typename B>
+    __device__ static __forceinline__ mfma_f32x4 mfma16(const A& a, const B& b, mfma_f32x4 c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
                                                        0);
     }
-    __device__ static __forceinline__ mfma_f32x16 mfma32(const uint4& a, const uint4& b, mfma_f32x16 c)
+    template <typename A, typename B>
+    __device__ static __forceinline__ mfma_f32x16 mfma32(const A& a, const B& b, mfma_f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
                                                        0);
@@ -217,12 +219,14 @@ struct ElemF16 {
     }
     __device__ static __forceinline__ float lo_of(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[0]; }
     __device__ static __forceinline__ float hi_of(uint32_t w) { return (float)__builtin_bit_cast(vec2, w)[1]; }
-    __device__ static __forceinline__ mfma_f32x4 mfma16(const uint4& a, const uint4& b, mfma_f32x4 c)
+    template <typename A, typename B>
+    __device__ static __forceinline__ mfma_f32x4 mfma16(const A& a, const B& b, mfma_f32x4 c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
                                                       0);
     }
-    __device__ static __forceinline__ mfma_f32x16 mfma32(const uint4& a, const uint4& b, mfma_f32x16 c)
+    template <typename A, typename B>
+    __device__ static __forceinline__ mfma_f32x16 mfma32(const A& a, const B& b, mfma_f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(vec8, a), __builtin_bit_cast(vec8, b), c, 0, 0,
                                                       0);
