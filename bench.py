@@ -67,8 +67,8 @@ def parse():
     ap.add_argument("--dtype", choices=["default", "bf16", "fp16"], default="default",
                     help="16-bit element type of the pools (fp16 is the paper's own precision)")
     ap.add_argument("--page-size", type=int, default=0, help="override the workload's page size (power of two)")
-    ap.add_argument("--window", type=int, default=0, help="decode workloads: sliding window in tokens (0 = off)")
-    ap.add_argument("--alibi", action="store_true", help="decode workloads: add a linear position bias per head")
+    ap.add_argument("--window", type=int, default=0, help="sliding window in tokens (0 = off)")
+    ap.add_argument("--alibi", action="store_true", help="add a linear position bias per head")
     ap.add_argument("--launch", choices=["direct", "graph"], default="direct",
                     help="graph: capture one step (append + attention + merge) in a HIP graph and replay it; for the "
                          "small workloads, whose step is shorter than the host's launch overhead")
@@ -228,7 +228,10 @@ def main():
 
     def step():
         pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
-        if is_prefill:
+        if is_prefill and mods:
+            pa.paged_attention_prefill_mod(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
+                                           w.seq_lens, w.max_seq_len, w.scale, w.causal, out=out, workspace=ws, **mods)
+        elif is_prefill:
             pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table, w.seq_lens,
                                        w.max_seq_len, w.scale, w.causal, out=out, workspace=ws)
         elif mods:
@@ -308,7 +311,17 @@ def main():
                               "note": "KV bytes of the sequences the decode kernel computes in this call"}
     elif is_prefill:
         routed = "paged_decode_mfma_kernel" in kernels
-        flops = sum(4 * w.num_q_heads * w.head_dim * (ql * (L - ql) + ql * (ql + 1) // 2 if w.causal else ql * L)
+        def pairs(ql, L):
+            # (query, visible key) pairs of one head
+            if not args.window:
+                return ql * (L - ql) + ql * (ql + 1) // 2 if w.causal else ql * L
+            n = 0
+            for i in range(ql):
+                pos = L - ql + i
+                lo, hi = max(0, pos - args.window + 1), (pos + 1 if w.causal else min(L, pos + args.window))
+                n += hi - lo
+            return n
+        flops = sum(4 * w.num_q_heads * w.head_dim * pairs(ql, L)
                     for ql, L, sm in zip(w.q_lens_host, w.seq_lens_host, small) if not (sm and routed))
         dom = kernels.get("paged_prefill_mfma_kernel") or kernels.get("paged_attention_generic_kernel")
         ach = flops / (dom["avg_us"] * 1e-6) / 1e12

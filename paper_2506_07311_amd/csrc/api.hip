@@ -274,7 +274,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         if (a.plan.nsplit > 1) st = launch_merge(a, s);
         return st;
     }
-    if (!g_opt.force_generic && prefill_mfma_supported(a) && !a.has_mods) {
+    if (!g_opt.force_generic && prefill_mfma_supported(a)) {
         // Jagged batch: sequences with few queries (q_len * G <= 16: decode rows, a few speculative tokens) are
         // bound by streaming their context once, which the decode kernel's equal-work tile stream does best; the
         // others go to the prefill kernel.  Both kernels decide per sequence from cu_q_lens on the device; the

@@ -68,14 +68,43 @@ __device__ __forceinline__ uint4 lds_frag_tr(const char* lo, const char* hi)
 // query's max jumps more than kJump above its reference (always on its first keys, rarely later) is the
 // reference raised, O and l rescaled and the half's weights recomputed -- a wave-uniform slow path that keeps
 // the common path free of branches between the score and the value products.
-template <bool MASK, bool FIRST>
+// What the mask / score hooks need per row (this lane's).  Unused without their hook.
+struct RowMods {
+    int32_t lo;         // window: first visible key of this row
+    int32_t lo_until;   // window: tiles that start before this key need the lower mask (wave-uniform)
+    int32_t pos;        // score: the row's absolute position
+    float slope2;       // score: bias slope * log2(e)
+    float cap_in;       // score: scale / softcap, 0 without a cap
+    float cap_out;      // score: softcap * log2(e)
+};
+
+// M: compile-time policy of the hooks.  With score hooks the scores are first rewritten in place as
+// log2(e) * (cap(scale * s) + slope * (key - pos)) and the rest runs with a unit scale.
+template <bool MASK, bool FIRST, typename M>
 __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[4], float& m_ref, float& l, float sc,
-                                             int32_t key0, int32_t nk)
+                                             int32_t key0, int32_t nk, const RowMods& rm)
 {
+    if (M::kScore) {
+        const float b0 = rm.slope2 * (float)(key0 - rm.pos);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float x;
+            if (rm.cap_in > 0.f) {   // c * tanh(y / c) with tanh(z) = 1 - 2 / (1 + e^(2z))
+                const float e2z = __builtin_amdgcn_exp2f(s[r] * rm.cap_in * (2.f * kLog2e));
+                x = rm.cap_out * (1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e2z));
+            } else {
+                x = s[r] * sc;
+            }
+            s[r] = x + __builtin_fmaf(rm.slope2, (float)(8 * (r / 4) + (r % 4)), b0);
+        }
+        sc = 1.f;
+    }
+    const bool below = M::kWindow && key0 < rm.lo_until;      // wave-uniform up to the lane's 4-key offset
     float tmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         if (MASK && key0 + 8 * (r / 4) + (r % 4) >= nk) s[r] = -INFINITY;   // mask by selection
+        if (below && key0 + 8 * (r / 4) + (r % 4) < rm.lo) s[r] = -INFINITY;
         tmax = fmaxf(tmax, s[r]);
     }
     float psum = 0.f;
@@ -188,21 +217,21 @@ __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int hal
 //     vector ALU:            softmax(h0)    softmax(h1)
 // buf = tile buffer (K rows, then V rows); key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's
 // query may see (MASK only); sc = scale * log2(e) > 0.
-template <bool PRECISE, bool MASK, typename E>
+template <bool PRECISE, bool MASK, typename E, typename M>
 __device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[8], const uint32_t (&vx)[8],
                                             const uint4 (&qf)[8], f32x16 (&o)[4], float& m, float& l, float sc,
-                                            int32_t key0, int32_t nk)
+                                            int32_t key0, int32_t nk, const RowMods& rm)
 {
     f32x16 s0, s1, p;
     half_scores<E>(s0, buf, 0, kx, qf);
     half_scores<E>(s1, buf, 1, kx, qf);
-    half_softmax<MASK, true>(p, s0, o, m, l, sc, key0, nk);
+    half_softmax<MASK, true, M>(p, s0, o, m, l, sc, key0, nk, rm);
     half_pv<PRECISE, E>(o, p, buf + kTileBytes, 0, vx);
-    half_softmax<MASK, false>(p, s1, o, m, l, sc, key0 + 32, nk);
+    half_softmax<MASK, false, M>(p, s1, o, m, l, sc, key0 + 32, nk, rm);
     half_pv<PRECISE, E>(o, p, buf + kTileBytes, 1, vx);
 }
 
-template <bool PRECISE, bool UNIFORM, typename E>
+template <bool PRECISE, bool UNIFORM, typename E, typename M>
 __device__ __forceinline__ void prefill_body(
     char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
@@ -238,12 +267,23 @@ __device__ __forceinline__ void prefill_body(
     int32_t nk_wg = len;
     if (causal) nk_wg = min(len, len - q_len + q_last + 1);
     nk_wg = max(nk_wg, 0);
-    if ((nk_wg <= kPreciseKeys) != PRECISE) return;         // the other instantiation handles this tile
+    // sliding window: |key - pos| < window.  The workgroup starts at the 64-aligned key before the window of its
+    // first row and, without a causal bound, ends with the window of its last row.
+    const int32_t window = (M::kWindow && plan.mods.window > 0) ? plan.mods.window : 0;
+    int32_t k_lo = 0;
+    if (window > 0) {
+        k_lo = max(len - q_len + (m0 >> lg) - window + 1, 0) & ~(kBN - 1);
+        if (!causal) nk_wg = max(min(nk_wg, len - q_len + q_last + window), 0);
+    }
+    // Few effective keys mean few, large weights whose 16-bit rounding shows: short contexts and windows, and any
+    // position bias (a steep slope concentrates the weight on a handful of keys however long the context is).
+    const bool few_keys = nk_wg - k_lo <= kPreciseKeys || (M::kScore && plan.mods.alibi_slopes != nullptr);
+    if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
     // reads only the chunks that hold keys of a row)
-    const int32_t k_begin = split * plan.chunk;
-    const int32_t k_end = min(nk_wg, k_begin + plan.chunk);
-    if (plan.nsplit > 1 && k_begin >= nk_wg) return;
+    if (plan.nsplit > 1 && split * plan.chunk >= nk_wg) return;
+    const int32_t k_begin = max(split * plan.chunk, k_lo);
+    const int32_t k_end = min(nk_wg, split * plan.chunk + plan.chunk);
 
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t* table = block_table + (int64_t)s * max_blocks;
@@ -255,18 +295,45 @@ __device__ __forceinline__ void prefill_body(
     const int32_t qi_c = r_c >> lg;
     const int32_t h = (hg << lg) + (r_c & ((1 << lg) - 1));
     const int32_t kvh = (hg << lg) / G;
+    const int32_t pos = len - q_len + qi_c;                  // the row's absolute position
     int32_t nk = len;                                        // keys 0 .. nk-1 are allowed
-    if (causal) nk = min(len, len - q_len + qi_c + 1);
+    if (causal) nk = min(len, pos + 1);
+    else if (window > 0) nk = min(len, pos + window);
     nk = max(nk, 0);
     // per wave: the largest bound of its 32 rows decides which tiles it can skip, the smallest which
     // tiles need no mask
+    const int32_t pos_first = len - q_len + (min(m0 + 32 * wave, n_rows - 1) >> lg);
+    const int32_t pos_last = len - q_len + (min(m0 + 32 * wave + 31, n_rows - 1) >> lg);
     int32_t nk_wave = len, nk_wave_min = len;
     if (causal) {
-        nk_wave = min(len, len - q_len + (min(m0 + 32 * wave + 31, n_rows - 1) >> lg) + 1);
-        nk_wave_min = min(len, len - q_len + (min(m0 + 32 * wave, n_rows - 1) >> lg) + 1);
+        nk_wave = min(len, pos_last + 1);
+        nk_wave_min = min(len, pos_first + 1);
+    } else if (window > 0) {
+        nk_wave = min(len, pos_last + window);
+        nk_wave_min = min(len, pos_first + window);
     }
     nk_wave = max(nk_wave, 0);
     nk_wave_min = max(nk_wave_min, 0);
+    RowMods rm;
+    rm.lo = 0;
+    rm.lo_until = 0;
+    rm.pos = pos;
+    rm.slope2 = 0.f;
+    rm.cap_in = 0.f;
+    rm.cap_out = 0.f;
+    int32_t lo_wave = 0;                                     // tiles that end at or before it hold nothing for the wave
+    if (window > 0) {
+        rm.lo = pos - window + 1;
+        rm.lo_until = pos_last - window + 1;
+        lo_wave = pos_first - window + 1;
+    }
+    if (M::kScore) {
+        if (plan.mods.alibi_slopes) rm.slope2 = plan.mods.alibi_slopes[h] * kLog2e;
+        if (plan.mods.softcap > 0.f) {
+            rm.cap_in = scale / plan.mods.softcap;
+            rm.cap_out = plan.mods.softcap * kLog2e;
+        }
+    }
 
     const int64_t row = (int64_t)(q_begin + qi_c) * num_q_heads + h;
     // Q as B operand: lane%32 = query, step ks covers head_dim elements 16*ks + 8*hh .. +7
@@ -321,11 +388,11 @@ __device__ __forceinline__ void prefill_body(
             fetch_tile<UNIFORM>(buf1 + wrow, ids, cache, t0 + kBN, frow, last_key, lane_off);
             if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
         }
-        if (t0 < nk_wave) {                                  // wave-uniform: else nothing for this wave here
+        if (t0 < nk_wave && t0 + kBN > lo_wave) {            // wave-uniform: else nothing for this wave here
             if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
-                attend_tile<PRECISE, true, E>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, true, E, M>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
             else
-                attend_tile<PRECISE, false, E>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk);
+                attend_tile<PRECISE, false, E, M>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
         }
         __syncthreads();
         if (t + 1 >= n_tiles) break;
@@ -334,11 +401,11 @@ __device__ __forceinline__ void prefill_body(
             fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, t1 + kBN, frow, last_key, lane_off);
             if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
         }
-        if (t1 < nk_wave) {
+        if (t1 < nk_wave && t1 + kBN > lo_wave) {
             if (t1 + kBN > nk_wave_min)
-                attend_tile<PRECISE, true, E>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
+                attend_tile<PRECISE, true, E, M>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
             else
-                attend_tile<PRECISE, false, E>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk);
+                attend_tile<PRECISE, false, E, M>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
         }
         __syncthreads();
     }
@@ -380,7 +447,7 @@ __device__ __forceinline__ void prefill_body(
 
 // Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
 // workgroup runs exactly one of them, decided by its context length.
-template <bool UNIFORM, typename E>
+template <bool UNIFORM, typename E, typename M>
 __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
@@ -389,9 +456,9 @@ __global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
 {
     __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
     __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
-    prefill_body<false, UNIFORM, E>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    prefill_body<false, UNIFORM, E, M>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                  num_q_heads, max_blocks, scale, causal, plan);
-    prefill_body<true, UNIFORM, E>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    prefill_body<true, UNIFORM, E, M>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                 num_q_heads, max_blocks, scale, causal, plan);
 }
 
@@ -401,6 +468,7 @@ bool prefill_mfma_supported(const AttnArgs& a)
 {
     if ((a.dtype != PA_DTYPE_BF16 && a.dtype != PA_DTYPE_F16) || a.cache.head_dim != kD) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
+    if (a.has_mods && a.mods.doc_ids) return false;   // document masks: portable kernel
     return true;
 }
 
@@ -422,6 +490,7 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     plan.skip_small = a.skip_small;
     plan.part_o = a.part_o;
     plan.part_lse = a.part_lse;
+    plan.mods = a.mods;
     if (plan.nsplit > 1 && (plan.chunk % kBN != 0 || plan.chunk % a.cache.page_size != 0)) return PA_ERR_INVALID_ARG;
     const int64_t tiles = (((int64_t)a.max_q_len << plan.log2_pack) + kBM - 1) / kBM;
     if (tiles <= 0) return PA_OK;
@@ -432,9 +501,18 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
         ProfileScope prof("paged_prefill_mfma_kernel", stream);
         // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
         const bool uniform = a.cache.page_size >= 16;
-        auto kern = a.dtype == PA_DTYPE_BF16
-                        ? (uniform ? paged_prefill_mfma_kernel<true, ElemBf16> : paged_prefill_mfma_kernel<false, ElemBf16>)
-                        : (uniform ? paged_prefill_mfma_kernel<true, ElemF16> : paged_prefill_mfma_kernel<false, ElemF16>);
+        typedef Mods<true, true, false> WindowScore;
+        auto kern = paged_prefill_mfma_kernel<true, ElemBf16, NoMods>;
+        if (a.dtype == PA_DTYPE_BF16) {
+            if (a.has_mods) kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, WindowScore>
+                                           : paged_prefill_mfma_kernel<false, ElemBf16, WindowScore>;
+            else if (!uniform) kern = paged_prefill_mfma_kernel<false, ElemBf16, NoMods>;
+        } else {
+            if (a.has_mods) kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, WindowScore>
+                                           : paged_prefill_mfma_kernel<false, ElemF16, WindowScore>;
+            else kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, NoMods>
+                                : paged_prefill_mfma_kernel<false, ElemF16, NoMods>;
+        }
         hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                            a.cu_q_lens, a.block_table, a.seq_lens, a.batch, (int32_t)tiles, a.num_q_heads, a.max_blocks,
                            a.scale, a.causal, plan);

@@ -41,6 +41,7 @@ struct PrefillPlan {
     int32_t skip_small;   // 1: sequences with q_len * G <= 16 are computed by the decode kernel, not here
     float* part_o;        // [total_q, Hq, nsplit, 128]
     float* part_lse;      // [total_q, Hq, nsplit]
+    ModArgs mods;         // mask / score hooks (used by the instantiations that have them)
 };
 
 struct PageIds {

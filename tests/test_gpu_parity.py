@@ -587,6 +587,33 @@ def test_prefill_with_mask_and_score_hooks(pa, oracle, case, causal):
     parity.check_step(pa, oracle, w, f"prefill hooks {case} causal={causal}", mods=build_mods(case, 8, lens))
 
 
+@pytest.mark.parametrize("window", [64, 500, 1025])
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_prefill_sliding_window_over_many_tiles(pa, oracle, window, causal, dtype):
+    """The matrix-core prefill kernel with a window: workgroups start at their first row's window, waves skip the
+    tiles before theirs, rows mask their own lower bound; with a soft cap and a position bias on top."""
+    w = W.make_workload("t", seq_lens=[1500, 700, 130], q_lens=[1500, 300, 7], num_q_heads=8, num_kv_heads=2,
+                        head_dim=128, page_size=16, dtype=dtype, causal=causal, seed=75, device=DEV)
+    parity.check_step(pa, oracle, w, f"window {window} causal={causal} {dtype}", mods=dict(window=window))
+    parity.check_step(pa, oracle, w, f"window {window} + cap + bias causal={causal} {dtype}",
+                      mods=dict(window=window, softcap=4.0, alibi_slopes=alibi(8)))
+
+
+@pytest.mark.parametrize("chunk", [256, 1024])
+def test_prefill_window_with_context_split(pa, oracle, chunk):
+    """Chunks that lie wholly before a row's window leave empty partials; the merge must ignore them."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[4096, 700], q_lens=[40, 130], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                        page_size=16, dtype=torch.bfloat16, causal=True, seed=76, device=DEV)
+    binding.pa_set_option("prefill_chunk_tokens", chunk)
+    try:
+        parity.check_step(pa, oracle, w, f"window 600, chunk {chunk}", mods=dict(window=600))
+        parity.check_step(pa, oracle, w, f"bias, chunk {chunk}", mods=dict(alibi_slopes=alibi(8)))
+    finally:
+        binding.pa_set_option("prefill_chunk_tokens", 0)
+
+
 @pytest.mark.parametrize("wgs", [1, 7, 256])
 def test_windowed_decode_split_schedules(pa, oracle, wgs):
     """The tile stream starts at the window: segments, merge and direct writes with a window in place."""
