@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 MEASURED_TRAFFIC = {
     "decode_b16_ctx131072_p16": {"read_bytes": 8589673000, "write_bytes": 8474500,
                                  "source": "profiles/decode_b16_ctx131072_p16.md"},
-    "prefill_b4_s2048_causal": {"read_bytes": 686753000, "write_bytes": 78185000,
+    "prefill_b4_s2048_causal": {"read_bytes": 154503000, "write_bytes": 67109000,
                                 "source": "profiles/prefill_b4_s2048_causal.md"},
 }
 
