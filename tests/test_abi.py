@@ -50,6 +50,17 @@ def _desc(**kw):
     return binding._Desc(**d)
 
 
+def test_prefill_workspace_covers_the_split_and_the_few_query_route(lib):
+    """A call with few query rows over a long context is cut along the context: its workspace must hold the
+    partials (total_q * Hq * nsplit * (d + 1) floats) on top of the few-query route's; a call with many rows is not
+    cut and needs only the latter."""
+    few = binding.paged_attention_workspace_bytes(1, 32, 128, 128, 131072)
+    many = binding.paged_attention_workspace_bytes(4, 32, 128, 8192, 2048)
+    route = binding.paged_attention_workspace_bytes(4, 32, 128, 8192, 64)
+    assert many == route                                   # no split: same as a context too short to split
+    assert few > binding.paged_attention_workspace_bytes(1, 32, 128, 128, 64) + 128 * 32 * 2 * 129 * 4
+
+
 def test_workspace_bytes_is_positive_multiple_of_256(lib):
     for args in [(16, 64, 128, 16, 131072), (1, 8, 64, 1, 128), (4, 32, 128, 8192, 2048), (0, 8, 64, 0, 0)]:
         n = binding.paged_attention_workspace_bytes(*args)
@@ -90,6 +101,20 @@ def test_host_validation_rejects_before_launch(lib):
     # prefill: missing cu_q_lens
     assert lib.paged_attention_prefill(ctypes.byref(d), p, p, null, null, i32(8), i32(4), p, p, i32(2), i32(32),
                                        i32(4), i32(64), f, i32(1), ws, big, null) == 1
+    # hooks: negative window, NaN cap, document ids narrower than the context
+    m = binding._Mods(-1, 0.0, None, None, 0)
+    assert lib.paged_attention_decode_mod(ctypes.byref(d), p, p, null, p, p, i32(2), i32(32), i32(4), i32(64), f,
+                                          ctypes.byref(m), ws, big, null) == 1
+    m = binding._Mods(0, float("nan"), None, None, 0)
+    assert lib.paged_attention_decode_mod(ctypes.byref(d), p, p, null, p, p, i32(2), i32(32), i32(4), i32(64), f,
+                                          ctypes.byref(m), ws, big, null) == 1
+    m = binding._Mods(0, 0.0, None, 0x8000, 63)
+    assert lib.paged_attention_prefill_mod(ctypes.byref(d), p, p, null, p, i32(8), i32(4), p, p, i32(2), i32(32),
+                                           i32(4), i32(64), f, i32(1), ctypes.byref(m), ws, big, null) == 1
+    # fp16 pools are accepted by the descriptor check (batch == 0: nothing is launched)
+    d16 = _desc(dtype=2)
+    assert lib.paged_attention_decode(ctypes.byref(d16), p, p, null, p, p, i32(0), i32(32), i32(4), i32(64), f, ws,
+                                      big, null) == 0
     # options
     assert lib.pa_set_option(b"no_such_knob", ctypes.c_int64(1)) == 1
     assert lib.pa_set_option(b"decode_chunk_tokens", ctypes.c_int64(0)) == 0
