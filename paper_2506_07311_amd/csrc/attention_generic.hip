@@ -73,15 +73,25 @@ template <> struct Vec<f16_tag> {
     }
 };
 
-__device__ __forceinline__ float block_max(float v, float* red)
+// Workgroup-wide max in the score type of the instantiation (double for fp32 I/O).
+template <typename S>
+__device__ __forceinline__ S block_max_t(S v, S* red)
 {
-    v = wave_max(v);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const S u = __shfl_xor(v, o, 64);
+        v = u > v ? u : v;
+    }
     const int w = threadIdx.x >> 6;
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[w] = v;
     __syncthreads();
-    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    S a = red[0] > red[1] ? red[0] : red[1];
+    S b = red[2] > red[3] ? red[2] : red[3];
+    return a > b ? a : b;
 }
+__device__ __forceinline__ float tanh_t(float x) { return tanhf(x); }
+__device__ __forceinline__ double tanh_t(double x) { return tanh(x); }
 
 __device__ __forceinline__ float block_sum(float v, float* red)
 {
@@ -106,8 +116,10 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     constexpr int N = V::N;
     constexpr int EB = 16 / N;   // bytes per element
     __shared__ float q_s[kMaxD];
-    __shared__ float sc[kTile];
+    typedef typename V::dot_t score_t;   // fp32 I/O keeps scores (and their distance to the max) in fp64
+    __shared__ score_t sc[kTile];
     __shared__ float red[4];
+    __shared__ score_t red_t[4];
     __shared__ float acc_s[kThreads * 8];
 
     const int tid = threadIdx.x;
@@ -163,7 +175,8 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     const char* kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * EB;
     const char* vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * EB;
 
-    float m = -INFINITY, l = 0.f;
+    score_t m = -INFINITY;
+    float l = 0.f;
     float acc[N];
 #pragma unroll
     for (int e = 0; e < N; ++e) acc[e] = 0.f;
@@ -171,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     for (int32_t t0 = c0; t0 < c1; t0 += kTile) {
         const int32_t tn = min(kTile, c1 - t0);
         // scores: one key per thread
-        float lmax = -INFINITY;
+        score_t lmax = -INFINITY;
         for (int32_t jj = tid; jj < tn; jj += kThreads) {
             const int32_t j = t0 + jj;
             const int64_t page = table[j >> cache.log2_page];
@@ -183,24 +196,24 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
 #pragma unroll
                 for (int e = 0; e < N; ++e) dot += (typename V::dot_t)q_s[c * N + e] * (typename V::dot_t)kv[e];
             }
-            float sj = (float)(dot * scale);
+            score_t sj = dot * (score_t)scale;
             if (M::kScore) {
-                if (mods.softcap > 0.f) sj = mods.softcap * tanhf(sj / mods.softcap);
-                sj += slope * (float)(j - ri.pos);
+                if (mods.softcap > 0.f) sj = (score_t)mods.softcap * tanh_t(sj / (score_t)mods.softcap);
+                sj += (score_t)slope * (score_t)(j - ri.pos);
             }
             if (M::kDoc && doc && doc[j] != my_doc) sj = -INFINITY;
             sc[jj] = sj;
-            lmax = fmaxf(lmax, sj);
+            lmax = sj > lmax ? sj : lmax;
         }
-        const float m_new = fmaxf(m, block_max(lmax, red));
+        const score_t m_new = block_max_t(m > lmax ? m : lmax, red_t);
         if (M::kDoc && m_new == -INFINITY) {       // no visible key so far (uniform over the workgroup)
             __syncthreads();
             continue;
         }
-        const float alpha = expf(m - m_new);       // m = -inf on the first tile gives 0
+        const float alpha = expf((float)(m - m_new));   // m = -inf on the first tile gives 0
         float lsum = 0.f;
         for (int32_t jj = tid; jj < tn; jj += kThreads) {
-            const float p = expf(sc[jj] - m_new);
+            const float p = expf((float)(sc[jj] - m_new));
             sc[jj] = p;
             lsum += p;
         }
@@ -215,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
                 const char* vr = vbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
                 float vv[N];
                 V::load(vr + vc * 16, vv);
-                const float p = sc[jj];
+                const float p = (float)sc[jj];
 #pragma unroll
                 for (int e = 0; e < N; ++e) acc[e] = fmaf(p, vv[e], acc[e]);
             }
@@ -240,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
             part_o[(o_idx * nsplit + split) * d + e] = o;
     }
     if (tid == 0) {
-        const float r = (!M::kDoc || l > 0.f) ? m + logf(l) : -INFINITY;
+        const float r = (!M::kDoc || l > 0.f) ? (float)(m + (score_t)logf(l)) : -INFINITY;
         if (nsplit == 1) { if (lse) lse[o_idx] = r; }
         else part_lse[o_idx * nsplit + split] = r;
     }

@@ -281,7 +281,9 @@ __device__ __forceinline__ void prefill_body(
     if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
     // reads only the chunks that hold keys of a row)
-    if (plan.nsplit > 1 && split * plan.chunk >= nk_wg) return;
+    // (without a causal bound a window also cuts the END of a row's range, which the merge does not know: those
+    // chunks must leave explicit empty partials, so the workgroup goes on with zero tiles)
+    if (plan.nsplit > 1 && split * plan.chunk >= nk_wg && !(window > 0 && !causal)) return;
     const int32_t k_begin = max(split * plan.chunk, k_lo);
     const int32_t k_end = min(nk_wg, split * plan.chunk + plan.chunk);
 

@@ -67,18 +67,23 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, m
         prefill = w.causal or w.max_q_len > 1 or w.total_q != w.batch
     lse = torch.full((w.total_q, w.num_q_heads), float("nan"), dtype=torch.float32, device=w.q.device) \
         if with_lse else None
+    # the workspace's contents are unspecified on entry: poison it (all-ones bytes: NaN as float, -1 as int), so a
+    # partial that is read without having been written shows up
+    ws = torch.full((pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.total_q,
+                                                        w.max_seq_len),), 0xFF, dtype=torch.uint8, device=w.q.device)
+    kw["workspace"] = ws
     if prefill and mods:
         out = pa.paged_attention_prefill_mod(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
                                              w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse, **kw)
     elif prefill:
         out = pa.paged_attention_prefill(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
-                                         w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse)
+                                         w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse, **kw)
     elif mods:
         out = pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
                                             w.scale, lse=lse, **kw)
     else:
         out = pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len,
-                                        w.scale, lse=lse)
+                                        w.scale, lse=lse, **kw)
     torch.cuda.synchronize()
     return out, lse
 

@@ -614,6 +614,27 @@ def test_prefill_window_with_context_split(pa, oracle, chunk):
         binding.pa_set_option("prefill_chunk_tokens", 0)
 
 
+def test_prefill_window_without_causal_bound_and_context_split(pa, oracle):
+    """Without a causal bound a window also ends a row's key range early: context chunks behind that end must
+    leave empty partials (the merge counts chunks by the sequence length).  The workspace is filled with NaN first."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[2446, 651], q_lens=[2401, 123], num_q_heads=5, num_kv_heads=1, head_dim=128,
+                        page_size=1, dtype=torch.bfloat16, causal=False, seed=77, device=DEV)
+    k_ref, v_ref, o_ref, lse_ref = parity.oracle_step(oracle, w, mods=dict(window=64))
+    pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+    for chunk in (0, 256):
+        binding.pa_set_option("prefill_chunk_tokens", chunk)
+        try:
+            nbytes = pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.total_q, w.max_seq_len)
+            ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device=DEV).view(torch.uint8)
+            out = pa.paged_attention_prefill_mod(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
+                                                 w.seq_lens, w.max_seq_len, w.scale, False, window=64, workspace=ws)
+            torch.cuda.synchronize()
+        finally:
+            binding.pa_set_option("prefill_chunk_tokens", 0)
+        parity.assert_close(parity.to_f64(out), o_ref, w.dtype, f"non-causal window, chunk option {chunk}")
+
+
 @pytest.mark.parametrize("wgs", [1, 7, 256])
 def test_windowed_decode_split_schedules(pa, oracle, wgs):
     """The tile stream starts at the window: segments, merge and direct writes with a window in place."""
