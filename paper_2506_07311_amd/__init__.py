@@ -15,4 +15,7 @@ from .binding import (  # noqa: F401
     paged_attention_workspace_bytes,
     paged_kv_append,
     paged_kv_gather,
+    prepare_decode,
+    prepare_kv_append,
+    prepare_prefill,
 )

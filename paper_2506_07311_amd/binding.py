@@ -110,8 +110,26 @@ def _dense(t: torch.Tensor, what: str, dtype) -> torch.Tensor:
     return t
 
 
-def paged_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table, *, head_major=False,
-                    stream=None) -> None:
+class PreparedCall:
+    """One entry point with its arguments already marshalled (pointers, sizes and the stream as of preparation).
+    Calling it repeats exactly that call: for steady-state loops over the same buffers, where checking and
+    converting the arguments again would cost more host time than the step takes on the GPU.  The tensors are kept
+    alive by the object; their contents may change between calls, their addresses and shapes may not."""
+
+    __slots__ = ("_fn", "_args", "_keep", "_what", "result")
+
+    def __init__(self, fn, args, keep, what, result=None):
+        self._fn, self._args, self._keep, self._what, self.result = fn, args, keep, what, result
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st:
+            _check(st, self._what)
+        return self.result
+
+
+def prepare_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table, *, head_major=False,
+                      stream=None) -> PreparedCall:
     lib = load_library()
     d = cache_desc(k_cache, v_cache, head_major)
     T = int(seq_ids.shape[0])
@@ -119,10 +137,16 @@ def paged_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_ta
     if tuple(k_new.shape) != (T, d.num_kv_heads, d.head_dim) or k_new.shape != v_new.shape:
         raise PagedAttnError("k_new/v_new must be [T, Hkv, d]")
     _i32(seq_ids, "seq_ids"), _i32(positions, "positions"), _i32(block_table, "block_table")
-    st = lib.paged_kv_append(ctypes.byref(d), _p(k_new), _p(v_new), _p(seq_ids), _p(positions), ctypes.c_int32(T),
-                             _p(block_table), ctypes.c_int32(block_table.shape[0]),
-                             ctypes.c_int32(block_table.shape[1]), _stream(stream))
-    _check(st, "paged_kv_append")
+    args = (ctypes.byref(d), _p(k_new), _p(v_new), _p(seq_ids), _p(positions), ctypes.c_int32(T), _p(block_table),
+            ctypes.c_int32(block_table.shape[0]), ctypes.c_int32(block_table.shape[1]), _stream(stream))
+    return PreparedCall(lib.paged_kv_append, args, (d, k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table),
+                        "paged_kv_append")
+
+
+def paged_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table, *, head_major=False,
+                    stream=None) -> None:
+    prepare_kv_append(k_cache, v_cache, k_new, v_new, seq_ids, positions, block_table, head_major=head_major,
+                      stream=stream)()
 
 
 def paged_kv_gather(k_cache, v_cache, block_table, seq_lens, cu_seq_lens, total_tokens: int, max_seq_len: int, *,
@@ -155,6 +179,13 @@ def _workspace(workspace, nbytes, device):
 def paged_attention_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
                            out=None, lse=None, workspace=None, head_major=False, stream=None):
     """Returns ``out`` ([B, Hq, d], dtype of q).  ``lse`` (float32 [B, Hq]) is filled when given."""
+    return prepare_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_len, scale, out=out, lse=lse,
+                          workspace=workspace, head_major=head_major, stream=stream)()
+
+
+def prepare_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
+                   out=None, lse=None, workspace=None, head_major=False, stream=None) -> PreparedCall:
+    """paged_attention_decode with its arguments marshalled once; the call returns ``out``."""
     lib = load_library()
     d = cache_desc(k_cache, v_cache, head_major)
     _dense(q, "q", k_cache.dtype)
@@ -165,20 +196,29 @@ def paged_attention_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_l
     out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
     if lse is not None:
         _dense(lse, "lse", torch.float32)
-    need = paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len)
-    workspace = _workspace(workspace, need, q.device)
-    st = lib.paged_attention_decode(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
-                                    ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]),
-                                    ctypes.c_int32(max_seq_len), ctypes.c_float(scale), _p(workspace),
-                                    ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
-    _check(st, "paged_attention_decode")
-    return out
+    if workspace is None:   # (a workspace that is passed in is checked by the library itself)
+        workspace = _workspace(None, paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len), q.device)
+    args = (ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens), ctypes.c_int32(B),
+            ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
+            ctypes.c_float(scale), _p(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+            _stream(stream))
+    return PreparedCall(lib.paged_attention_decode, args,
+                        (d, k_cache, v_cache, q, out, lse, block_table, seq_lens, workspace), "paged_attention_decode",
+                        out)
 
 
 def paged_attention_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,
                             max_seq_len: int, scale: float, causal: bool, *, out=None, lse=None, workspace=None,
                             head_major=False, stream=None):
     """Returns ``out`` ([total_q, Hq, d], dtype of q).  ``lse`` (float32 [total_q, Hq]) is filled when given."""
+    return prepare_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len, block_table, seq_lens, max_seq_len, scale,
+                           causal, out=out, lse=lse, workspace=workspace, head_major=head_major, stream=stream)()
+
+
+def prepare_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens, max_seq_len: int,
+                    scale: float, causal: bool, *, out=None, lse=None, workspace=None, head_major=False,
+                    stream=None) -> PreparedCall:
+    """paged_attention_prefill with its arguments marshalled once; the call returns ``out``."""
     lib = load_library()
     d = cache_desc(k_cache, v_cache, head_major)
     _dense(q, "q", k_cache.dtype)
@@ -190,17 +230,16 @@ def paged_attention_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, bloc
     out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
     if lse is not None:
         _dense(lse, "lse", torch.float32)
-    need = paged_attention_workspace_bytes(B, Hq, hd, total_q, max_seq_len)
-    workspace = _workspace(workspace, need, q.device)
-    st = lib.paged_attention_prefill(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(cu_q_lens),
-                                     ctypes.c_int32(total_q), ctypes.c_int32(max_q_len), _p(block_table),
-                                     _p(seq_lens), ctypes.c_int32(B), ctypes.c_int32(Hq),
-                                     ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
-                                     ctypes.c_float(scale), ctypes.c_int32(1 if causal else 0), _p(workspace),
-                                     ctypes.c_size_t(workspace.numel() * workspace.element_size()),
-                                     _stream(stream))
-    _check(st, "paged_attention_prefill")
-    return out
+    if workspace is None:
+        workspace = _workspace(None, paged_attention_workspace_bytes(B, Hq, hd, total_q, max_seq_len), q.device)
+    args = (ctypes.byref(d), _p(q), _p(out), _p(lse), _p(cu_q_lens), ctypes.c_int32(total_q),
+            ctypes.c_int32(max_q_len), _p(block_table), _p(seq_lens), ctypes.c_int32(B), ctypes.c_int32(Hq),
+            ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len), ctypes.c_float(scale),
+            ctypes.c_int32(1 if causal else 0), _p(workspace),
+            ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    return PreparedCall(lib.paged_attention_prefill, args,
+                        (d, k_cache, v_cache, q, out, lse, cu_q_lens, block_table, seq_lens, workspace),
+                        "paged_attention_prefill", out)
 
 
 class _Mods(ctypes.Structure):

@@ -41,7 +41,18 @@ struct ProfileRecord {
 };
 bool g_profile_on = false;
 std::vector<ProfileRecord> g_records;
+std::vector<hipEvent_t> g_spare_events;   // events of records that were reset, reused instead of created anew
 std::mutex g_profile_mutex;
+
+bool take_event(hipEvent_t* e)
+{
+    if (!g_spare_events.empty()) {
+        *e = g_spare_events.back();
+        g_spare_events.pop_back();
+        return true;
+    }
+    return hipEventCreate(e) == hipSuccess;
+}
 
 inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
 
@@ -329,7 +340,11 @@ void profile_begin(const char* kernel, hipStream_t stream)
     std::lock_guard<std::mutex> lock(g_profile_mutex);
     ProfileRecord r;
     r.kernel = kernel;
-    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
+    if (!take_event(&r.start)) return;
+    if (!take_event(&r.stop)) {
+        g_spare_events.push_back(r.start);
+        return;
+    }
     (void)hipEventRecord(r.start, stream);
     g_records.push_back(r);
 }
@@ -491,8 +506,8 @@ pa_status pa_profile_reset(void)
     std::lock_guard<std::mutex> lock(g_profile_mutex);
     for (auto& r : g_records) {
         (void)hipEventSynchronize(r.stop);
-        (void)hipEventDestroy(r.start);
-        (void)hipEventDestroy(r.stop);
+        g_spare_events.push_back(r.start);
+        g_spare_events.push_back(r.stop);
     }
     g_records.clear();
     return PA_OK;
