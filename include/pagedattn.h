@@ -180,6 +180,20 @@ pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void*
                                       int32_t causal, const pa_attn_mods* mods, void* workspace,
                                       size_t workspace_bytes, void* stream);
 
+/*
+ * Debug utility: checks on the device the preconditions about device-side CONTENTS that the other entry points
+ * assume and do not check.  counts (host, int64[3]) receives
+ *   [0] block-table entries among the first ceil(seq_lens[s] / page_size) of a row that lie outside [0, num_pages)
+ *   [1] sequences whose length is negative or exceeds max_blocks * page_size
+ *   [2] appended tokens (seq_ids / positions, both NULL with T = 0) whose sequence id is outside [0, batch) or
+ *       whose position is outside [0, max_blocks * page_size)
+ * scratch : device memory, at least 32 bytes, 8-byte aligned (e.g. the attention workspace).  The call
+ * SYNCHRONISES `stream` and returns PA_OK when the check ran, whatever it found.
+ */
+pa_status pa_debug_check(const pa_kv_cache_desc* cache, const int32_t* block_table, const int32_t* seq_lens,
+                         int32_t batch, int32_t max_blocks, const int32_t* seq_ids, const int32_t* positions, int32_t T,
+                         void* scratch, int64_t* counts, void* stream);
+
 const char* pa_status_string(pa_status status);
 
 /*

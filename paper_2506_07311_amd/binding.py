@@ -21,7 +21,8 @@ PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
-    "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
+    "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "pa_debug_check",
+    "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
     "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
     "pa_pool_make_writable", "pa_pool_num_free", "pa_pool_num_blocks", "pa_pool_get_row", "pa_pool_refcount",
@@ -313,6 +314,26 @@ def paged_attention_prefill_mod(k_cache, v_cache, q, cu_q_lens, max_q_len: int, 
                                          _stream(stream))
     _check(st, "paged_attention_prefill_mod")
     return out
+
+
+def pa_debug_check(k_cache, v_cache, block_table, seq_lens, seq_ids=None, positions=None, *, head_major=False,
+                   stream=None) -> Tuple[int, int, int]:
+    """Counts of violated device-side preconditions: (page ids out of range, lengths out of range, appended tokens
+    out of range).  Synchronises the stream."""
+    d = cache_desc(k_cache, v_cache, head_major)
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens")
+    T = 0
+    if seq_ids is not None:
+        _i32(seq_ids, "seq_ids"), _i32(positions, "positions")
+        T = int(seq_ids.shape[0])
+    scratch = torch.empty(4, dtype=torch.int64, device=k_cache.device)
+    counts = (ctypes.c_int64 * 3)()
+    st = load_library().pa_debug_check(ctypes.byref(d), _p(block_table), _p(seq_lens),
+                                       ctypes.c_int32(block_table.shape[0]), ctypes.c_int32(block_table.shape[1]),
+                                       _p(seq_ids), _p(positions), ctypes.c_int32(T), _p(scratch), counts,
+                                       _stream(stream))
+    _check(st, "pa_debug_check")
+    return int(counts[0]), int(counts[1]), int(counts[2])
 
 
 def pa_set_option(name: str, value: int) -> None:

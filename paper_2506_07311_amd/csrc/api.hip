@@ -392,6 +392,25 @@ pa_status paged_kv_gather(const pa_kv_cache_desc* cache, void* out_k, void* out_
                             reinterpret_cast<hipStream_t>(stream));
 }
 
+pa_status pa_debug_check(const pa_kv_cache_desc* cache, const int32_t* block_table, const int32_t* seq_lens,
+                         int32_t batch, int32_t max_blocks, const int32_t* seq_ids, const int32_t* positions, int32_t T,
+                         void* scratch, int64_t* counts, void* stream)
+{
+    pa_status st = check_cache(cache);
+    if (st != PA_OK) return st;
+    if (batch < 0 || max_blocks < 0 || T < 0 || !counts || !scratch) return PA_ERR_INVALID_ARG;
+    if (((uintptr_t)scratch & 7) || (batch > 0 && (!block_table || !seq_lens)) || (T > 0 && (!seq_ids || !positions)))
+        return PA_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    st = launch_debug_check(cache, block_table, seq_lens, batch, max_blocks, seq_ids, positions, T, scratch, s);
+    if (st != PA_OK) return st;
+    unsigned long long host[4] = {0, 0, 0, 0};
+    if (hipMemcpyAsync(host, scratch, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return PA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return PA_ERR_HIP;
+    for (int i = 0; i < 3; ++i) counts[i] = (int64_t)host[i];
+    return PA_OK;
+}
+
 size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t total_q,
                                        int32_t max_seq_len)
 {

@@ -79,6 +79,40 @@ __global__ __launch_bounds__(kThreads) void paged_kv_copy_page_kernel(
     pool[dst_page * page_stride_v + in_page] = pool[src_page * page_stride_v + in_page];
 }
 
+// Precondition check of the device-side contents (debug utility).  counts: [0] dereferenced block-table entries
+// outside [0, num_pages), [1] lengths outside [0, max_blocks * P], [2] appended tokens with a sequence id or a
+// position out of range.
+__global__ __launch_bounds__(kThreads) void paged_debug_check_kernel(
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_blocks,
+    int32_t num_pages, int32_t log2_page, const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ positions,
+    int32_t T, unsigned long long* __restrict__ counts)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t table_entries = (int64_t)batch * max_blocks;
+    const int64_t capacity = (int64_t)max_blocks << log2_page;
+    if (idx < table_entries) {
+        const int32_t s = (int32_t)(idx / max_blocks);
+        const int32_t b = (int32_t)(idx % max_blocks);
+        const int64_t len = seq_lens[s];
+        if (b == 0 && (len < 0 || len > capacity)) atomicAdd(&counts[1], 1ULL);
+        const int64_t used = (min(max(len, (int64_t)0), capacity) + (1 << log2_page) - 1) >> log2_page;
+        if (b < used) {
+            const int32_t page = block_table[idx];
+            if (page < 0 || page >= num_pages) atomicAdd(&counts[0], 1ULL);
+        }
+    } else if (idx - table_entries < T) {
+        const int64_t i = idx - table_entries;
+        const int32_t s = seq_ids[i];
+        const int32_t t = positions[i];
+        if (s < 0 || s >= batch || t < 0 || t >= capacity) atomicAdd(&counts[2], 1ULL);
+    }
+}
+
+__global__ void paged_debug_clear_kernel(unsigned long long* counts)
+{
+    if (threadIdx.x < 4) counts[threadIdx.x] = 0ULL;
+}
+
 inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
 
 }  // namespace
@@ -119,6 +153,22 @@ pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, 
                        (const uint4*)c->k_cache, (const uint4*)c->v_cache, (uint4*)out_k, (uint4*)out_v, block_table,
                        seq_lens, cu_seq_lens, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
                        c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
+    return launch_status();
+}
+
+pa_status launch_debug_check(const pa_kv_cache_desc* c, const int32_t* block_table, const int32_t* seq_lens,
+                             int32_t batch, int32_t max_blocks, const int32_t* seq_ids, const int32_t* positions,
+                             int32_t T, void* scratch, hipStream_t stream)
+{
+    const CacheView v = make_view(c);
+    const int64_t items = (int64_t)batch * max_blocks + T;
+    const int64_t blocks = (items + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    unsigned long long* counts = reinterpret_cast<unsigned long long*>(scratch);
+    hipLaunchKernelGGL(paged_debug_clear_kernel, dim3(1), dim3(64), 0, stream, counts);
+    if (blocks > 0)
+        hipLaunchKernelGGL(paged_debug_check_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, block_table,
+                           seq_lens, batch, max_blocks, c->num_pages, v.log2_page, seq_ids, positions, T, counts);
     return launch_status();
 }
 

@@ -657,3 +657,25 @@ def test_hooks_switched_off_equal_the_plain_entry_points(pa):
     b = pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def test_debug_check_counts_violated_preconditions(pa):
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[70, 33, 0, 16], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=80, device=DEV)
+    args = (w.k_cache, w.v_cache, w.block_table, w.seq_lens, w.seq_ids, w.positions)
+    assert binding.pa_debug_check(*args) == (0, 0, 0)
+    bt = w.block_table.clone()
+    bt[0, 1] = w.num_pages              # dereferenced (70 tokens = 5 blocks): out of range
+    bt[1, 2] = -7                       # dereferenced (33 tokens = 3 blocks)
+    bt[3, 1] = 10 ** 6                  # NOT dereferenced (16 tokens = 1 block)
+    assert binding.pa_debug_check(w.k_cache, w.v_cache, bt, w.seq_lens, w.seq_ids, w.positions) == (2, 0, 0)
+    lens = w.seq_lens.clone()
+    lens[2] = -1
+    lens[3] = bt.shape[1] * 16 + 1
+    assert binding.pa_debug_check(w.k_cache, w.v_cache, w.block_table, lens)[1] == 2
+    pos = w.positions.clone()
+    pos[0] = bt.shape[1] * 16
+    ids = w.seq_ids.clone()
+    ids[1] = 4
+    assert binding.pa_debug_check(w.k_cache, w.v_cache, w.block_table, w.seq_lens, ids, pos) == (0, 0, 2)
