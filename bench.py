@@ -63,7 +63,7 @@ def parse():
     ap.add_argument("--workload", default="decode_b16_ctx131072_p16", choices=sorted(WORKLOADS))
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU-oracle baseline / parity leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the extra prefill measurement")
-    ap.add_argument("--oracle-seqs", type=int, default=4, help="sequences of the workload the oracle is timed on")
+    ap.add_argument("--oracle-seqs", type=int, default=12, help="sequences of the workload the oracle is timed on")
     ap.add_argument("--dtype", choices=["default", "bf16", "fp16"], default="default",
                     help="16-bit element type of the pools (fp16 is the paper's own precision)")
     ap.add_argument("--page-size", type=int, default=0, help="override the workload's page size (power of two)")
