@@ -28,8 +28,8 @@
 // same order.  Online softmax runs in the log2 domain; masking (length, causal, ragged rows) is by selection.
 //
 // Softmax weights enter the matrix cores as bf16.  With few keys the individual weights are large and their
-// 2^-9 rounding shows in the output, so query tiles whose context is at most kPreciseKeys keys carry the weights
-// as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
+// 2^-9 rounding shows in the output, so query tiles whose context is at most max(kPreciseKeys, len / 8) keys carry
+// the weights as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
 #include "prefill_tiles.h"
 
 namespace pa {
@@ -277,7 +277,11 @@ __device__ __forceinline__ void prefill_body(
     }
     // Few effective keys mean few, large weights whose 16-bit rounding shows: short contexts and windows, and any
     // position bias (a steep slope concentrates the weight on a handful of keys however long the context is).
-    const bool few_keys = nk_wg - k_lo <= kPreciseKeys || (M::kScore && plan.mods.alibi_slopes != nullptr);
+    // "Few" is relative to the sequence: a row's rounding error falls as 1/sqrt(keys) while the scale its
+    // sequence's outputs are judged on falls with the sequence length, so the bound grows as len / 8 (the rows
+    // below it see at most 1/64 of a causal sequence's tile work).
+    const bool few_keys = nk_wg - k_lo <= max(kPreciseKeys, len >> 3) ||
+                          (M::kScore && plan.mods.alibi_slopes != nullptr);
     if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
     // reads only the chunks that hold keys of a row)

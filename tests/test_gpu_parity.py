@@ -265,6 +265,14 @@ def test_incremental_prefill_on_cached_context(pa, oracle, have):
     parity.check_step(pa, oracle, w, f"chunk of 512 on {have} cached tokens")
 
 
+def test_short_sequence_beside_long_ones_per_sequence_measure(pa, oracle):
+    """A 291-key sequence batched with several-thousand-key ones: the long sequences' small outputs pull the
+    tensor-wide RMS well below the short sequence's own scale, so each sequence is measured on its own rows."""
+    w = W.make_workload("t", seq_lens=[2930, 4200, 291], q_lens=[436, 2100, 251], num_q_heads=16, num_kv_heads=4,
+                        head_dim=128, page_size=64, dtype=torch.bfloat16, causal=True, seed=50, device=DEV)
+    parity.check_step(pa, oracle, w, "short beside long", per_seq=True)
+
+
 def test_prefill_row_equals_decode_at_that_length(pa):
     """Bottom-right causal alignment: row i of a causal prefill is the decode result at length i + 1."""
     S = 200
