@@ -13,9 +13,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpagedattn.so")
-SOURCES = ["api.hip", "kv_copy.hip", "attention_generic.hip", "merge.hip", "decode_mfma.hip", "prefill_mfma.hip",
-           "page_pool.hip"]
+SOURCES = ["api.hip", "kv_copy.hip", "attention_generic.hip", "merge.hip", "decode_mfma.hip", "decode_mfma_d64.hip",
+           "decode_mfma_d256.hip", "prefill_mfma.hip", "page_pool.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "prefill_tiles.h"),
+           os.path.join(CSRC, "decode_mfma_impl.h"),
            os.path.join(HERE, "..", "include", "pagedattn.h")]
 # packed-fp32 VALU forms are disabled on purpose (they have produced wrong results on these machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
@@ -45,7 +46,7 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = False, jobs: int = 6) -> str:
+def build(force: bool = False, jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))

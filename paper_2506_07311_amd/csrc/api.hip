@@ -264,7 +264,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
 
     if (decode) {
         if (!g_opt.force_generic && decode_mfma_supported(a)) {
-            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads);
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
             a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
             const size_t parts = (size_t)a.num_wgs + batch;
@@ -310,7 +310,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
             const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
             if (np > 1) p += part_o_bytes(total_q, num_q_heads, cache->head_dim, np) + part_lse_bytes(total_q, num_q_heads, np);
             AttnArgs b = a;
-            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads);
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             b.stream_split = 1;
             b.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
             if (b.num_wgs > kSmallRouteMaxWGs) b.num_wgs = kSmallRouteMaxWGs;

@@ -141,7 +141,7 @@ struct AttnArgs {
 pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream);
 // MFMA decode kernel: bf16, head_dim 128, group size <= 16.
 bool decode_mfma_supported(const AttnArgs& a);
-int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads);
+int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads, int32_t head_dim);
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
 // MFMA prefill kernel: bf16, head_dim 128.
 bool prefill_mfma_supported(const AttnArgs& a);

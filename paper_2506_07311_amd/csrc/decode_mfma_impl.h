@@ -1,0 +1,561 @@
+// Split-KV paged decode for bf16 / fp16 pools with head_dim D = 64, 128 or 256 on gfx950 (CDNA4), group size
+// G = Hq/Hkv <= 16.  Internal header: the kernel templates; one translation unit per head_dim instantiates them.
+// (The description below is written for D = 128; what changes with D is listed at Geo.)
+//
+// Decode is bound by streaming every resident K/V byte once from HBM, so the design is about memory:
+//   * one wave owns one KV head of one (sequence, context chunk); the NW waves of a workgroup own NW
+//     adjacent KV heads, so that together they read whole contiguous token rows of a page;
+//   * each wave walks its chunk in tiles of 32 keys; every K/V byte is fetched by one 16-byte load per
+//     lane straight into the registers the MFMA reads -- no LDS round trip -- and the next tile's 16
+//     loads (16 KB per wave) are in flight while the current tile is computed;
+//   * page translation (Algorithm 1: page = block_table[s][j >> log2 P], slot = j & (P-1)) is wave-uniform
+//     for P >= 16, i.e. scalar: page base in SGPRs plus loop-invariant per-lane offsets.
+// The G grouped query heads turn q.K^T and P.V into small dense contractions, which run on the matrix
+// cores (v_mfma_f32_16x16x32_bf16, G padded to 16 columns):
+//   S^T[key, head] = K[key, :] . Q[head, :]^T    A = K rows exactly as loaded (lane%16 = key)
+//   O^T[dcol, head] += V^T[dcol, key] . P^T[key, head]
+// For P.V the contraction index is the key, while memory is contiguous along head_dim.  Each lane loads
+// 8 keys x 8 head_dim columns and transposes that 8x8 block of 16-bit values in its own registers with
+// 32 byte-permutes; since any key order is valid for a sum, the 8 keys a lane holds are chosen to be the
+// ones whose probabilities the S^T accumulator layout already left in the matching lanes.
+// Softmax statistics are lane-local per head (lane%16 = head in both accumulators); the only cross-lane
+// traffic is a 4-way max per tile and one 4-way sum at the end.
+#pragma once
+
+#include "common.h"
+
+namespace pa {
+
+namespace {
+
+typedef mfma_f32x4 f32x4;
+
+// Tile geometry per head_dim.  A wave's tile is kBlocks blocks of 16 keys; a K row is read in KS steps of 32
+// elements; a lane's V loads cover 4 keys per block and kPasses 16-byte column pieces (piece = lane%16 + 16*pass).
+//   D = 64:  rows hold 8 pieces, so lanes 8-15 of each 16 repeat the loads of lanes 0-7 and the matching half of
+//            every P.V result (output rows 8-15) is unused -- the matrix cores idle in this kernel anyway.
+//   D = 256: two column passes; tiles of 16 keys keep two tiles in registers (the second block's contraction slots
+//            carry zero weights and zero values).
+template <int D>
+struct Geo {
+    static constexpr int kD = D;
+    static constexpr int kKS = D / 32;
+    static constexpr int kBlocks = D == 256 ? 1 : 2;
+    static constexpr int kTileKeys = 16 * kBlocks;
+    static constexpr int kPasses = D == 256 ? 2 : 1;
+    static constexpr int kPieceMask = D == 64 ? 7 : 15;
+};
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ uint4 load16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
+
+__device__ __forceinline__ uint32_t word(const uint4& v, int w)
+{
+    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+}
+
+template <typename GE>
+struct Tile {
+    uint4 k[GE::kBlocks][GE::kKS];        // [16-key block][32-element step of head_dim]: lane%16 = key, lane/16 = 8-element piece
+    uint4 v[GE::kPasses][4 * GE::kBlocks];   // 4 keys per block x 8 head_dim columns per lane and pass
+};
+
+// Everything a wave needs to address its KV head's rows.
+struct Addr {
+    const char* kbase;          // pool base + kv head offset
+    const char* vbase;
+    const int32_t* table;       // block-table row of the sequence
+    int64_t page_bytes;
+    int64_t token_bytes;
+    int32_t log2_page;
+    int32_t pmask;
+    uint32_t koff;              // UNIFORM: lane-invariant byte offset of the lane's K piece inside a 16-key block
+    uint32_t voff[4];           // UNIFORM: same for the lane's 4 V rows of a 16-key block
+    int32_t r16, quad;
+};
+
+// Issue the 16 loads of the tile that starts at key `t0`.  Keys at or beyond `c1` are clamped to the last
+// valid key, so every address is a live slot; their scores are masked by the caller.
+template <bool UNIFORM, typename GE>
+__device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0, int32_t c1)
+{
+    constexpr int kTileKeys = GE::kTileKeys;
+    if constexpr (UNIFORM) {
+        if (t0 + kTileKeys <= c1) {   // full tile: 16-key blocks, each inside one page
+#pragma unroll
+            for (int mt = 0; mt < GE::kBlocks; ++mt) {
+                const int32_t kb = t0 + 16 * mt;
+                const int64_t page = __builtin_amdgcn_readfirstlane(a.table[kb >> a.log2_page]);
+                const int64_t blk = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
+                const char* kp = a.kbase + blk;
+                const char* vp = a.vbase + blk;
+#pragma unroll
+                for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + a.koff + 64 * ks);
+#pragma unroll
+                for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) t.v[c][4 * mt + i] = load16(vp + a.voff[i] + 256 * c);
+            }
+            return;
+        }
+    }
+    // ragged tail (or page size below 16): per-lane translation of clamped keys
+    const int32_t last = c1 - 1;
+#pragma unroll
+    for (int mt = 0; mt < GE::kBlocks; ++mt) {
+        const int32_t key = min(t0 + 16 * mt + a.r16, last);
+        const int64_t page = a.table[key >> a.log2_page];
+        const char* kp = a.kbase + page * a.page_bytes + (int64_t)(key & a.pmask) * a.token_bytes + a.quad * 16;
+#pragma unroll
+        for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + 64 * ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int32_t vkey = min(t0 + 16 * mt + 4 * a.quad + i, last);
+            const int64_t vpage = a.table[vkey >> a.log2_page];
+            const char* vp = a.vbase + vpage * a.page_bytes + (int64_t)(vkey & a.pmask) * a.token_bytes +
+                             (a.r16 & GE::kPieceMask) * 16;
+#pragma unroll
+            for (int c = 0; c < GE::kPasses; ++c) t.v[c][4 * mt + i] = load16(vp + 256 * c);
+        }
+    }
+}
+
+template <typename GE>
+struct State {
+    f32x4 o[GE::kPasses][8];   // O^T accumulator: o[c][j][r] = column 128*c + 32*quad + 8*r + j of head lane%16
+    float m;       // running max of the log2-domain scores of head lane%16
+    float l;       // this lane's share of the running sum
+};
+
+// What the hooks need per row (this lane's column).  Unused members cost nothing without their hook.
+struct RowMods {
+    int32_t lo;         // window: first visible key of this row
+    int32_t lo_until;   // window: tiles that start before this key need the lower mask (wave-uniform)
+    int32_t pos;        // score: the row's absolute position
+    float slope2;       // score: bias slope * log2(e)
+    float cap_in;       // score: scale / softcap, 0 without a cap
+    float cap_out;      // score: softcap * log2(e)
+    float scale;        // score: plain scale (the unmodified path folds log2(e) into it)
+};
+
+// lim = first key this lane's row may not see (the segment end, or less under a per-row causal bound);
+// mask_from <= every lane's lim, wave-uniform: tiles that end at or before it need no mask.
+template <bool RAGGED, typename E, typename M, typename GE>
+__device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, const uint4 (&qf)[GE::kKS], float sc,
+                                             int32_t t0, int32_t lim, int32_t mask_from, int32_t quad,
+                                             const RowMods& rm)
+{
+    constexpr int kTileKeys = GE::kTileKeys;
+    constexpr int kBlocks = GE::kBlocks;
+    f32x4 s[2];
+    s[1] = f32x4{0.f, 0.f, 0.f, 0.f};                  // a block the tile does not have: zero weights
+#pragma unroll
+    for (int mt = 0; mt < kBlocks; ++mt) {
+        s[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < GE::kKS; ++ks)
+            s[mt] = E::mfma16(t.k[mt][ks], qf[ks], s[mt]);
+    }
+    // s[mt][i] is the score of key t0 + 16*mt + 4*quad + i for head lane%16
+    const bool partial = t0 + kTileKeys > mask_from;    // wave-uniform
+    const bool below = M::kWindow && t0 < rm.lo_until;  // wave-uniform: the tile holds keys before some window
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < kBlocks; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int32_t key = t0 + 16 * mt + 4 * quad + i;
+            float x;
+            if (M::kScore) {
+                // soft cap: c * tanh(y / c) with tanh(z) = 1 - 2 / (1 + e^(2z)); then the linear position bias;
+                // everything lands in the log2 domain
+                if (rm.cap_in > 0.f) {
+                    const float e2z = __builtin_amdgcn_exp2f(s[mt][i] * rm.cap_in * (2.f * kLog2e));
+                    x = rm.cap_out * (1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e2z));
+                } else {
+                    x = s[mt][i] * sc;
+                }
+                x = __builtin_fmaf(rm.slope2, (float)(key - rm.pos), x);
+            } else {
+                x = s[mt][i] * sc;
+            }
+            if (partial && key >= lim) x = -INFINITY;   // mask by selection
+            if (below && key < rm.lo) x = -INFINITY;
+            s[mt][i] = x;
+            tmax = fmaxf(tmax, x);
+        }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    // decode: finite, every tile holds at least one valid key; a row under a causal bound may have seen none yet
+    const float m_new = fmaxf(st.m, tmax);
+    const float m_use = (RAGGED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
+    float psum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < kBlocks; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(s[mt][i] - m_use);
+            s[mt][i] = p;
+            psum += p;
+        }
+    st.m = m_new;
+    st.l = st.l * alpha + psum;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st.o[c][j] *= alpha;
+    }
+    // Probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4).
+    // They are carried as TWO bf16 terms (p = hi + lo, lo = bf16(p - hi)): the matrix cores idle most of the
+    // time in this HBM-bound kernel, so the second product is free and removes the 2^-9 weight rounding that
+    // would otherwise dominate the error of short contexts.
+    uint4 pb, pl;
+    pb.x = E::pack(s[0][0], s[0][1]);
+    pb.y = E::pack(s[0][2], s[0][3]);
+    pb.z = E::pack(s[1][0], s[1][1]);
+    pb.w = E::pack(s[1][2], s[1][3]);
+    pl.x = E::pack(s[0][0] - E::lo_of(pb.x), s[0][1] - E::hi_of(pb.x));
+    pl.y = E::pack(s[0][2] - E::lo_of(pb.y), s[0][3] - E::hi_of(pb.y));
+    pl.z = E::pack(s[1][0] - E::lo_of(pb.z), s[1][1] - E::hi_of(pb.z));
+    pl.w = E::pack(s[1][2] - E::lo_of(pb.w), s[1][3] - E::hi_of(pb.w));
+    // in-register 8x8 transpose of V, one head_dim column (j) at a time, feeding the A operand
+#pragma unroll
+    for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+            uint4 a;   // columns j of rows (0,1), (2,3), (4,5), (6,7): word j/2 of each row, low or high half
+            a.x = __builtin_amdgcn_perm(word(t.v[c][1], j / 2), word(t.v[c][0], j / 2), sel);
+            a.y = __builtin_amdgcn_perm(word(t.v[c][3], j / 2), word(t.v[c][2], j / 2), sel);
+            if constexpr (kBlocks == 2) {
+                a.z = __builtin_amdgcn_perm(word(t.v[c][5], j / 2), word(t.v[c][4], j / 2), sel);
+                a.w = __builtin_amdgcn_perm(word(t.v[c][7], j / 2), word(t.v[c][6], j / 2), sel);
+            } else {
+                a.z = 0u;   // the absent block: zero values under zero weights
+                a.w = 0u;
+            }
+            st.o[c][j] = E::mfma16(a, pb, st.o[c][j]);
+            st.o[c][j] = E::mfma16(a, pl, st.o[c][j]);
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Work distribution.  The context of the whole batch is one stream of 32-key tiles (sequence after sequence,
+// ceil(len/32) tiles each); workgroup w of the nwg launched owns the contiguous tile range
+// [w*T/nwg, (w+1)*T/nwg).  Every workgroup therefore streams the same number of bytes whatever the length
+// mix is, and a sequence is cut only where a workgroup boundary falls inside it.  Each (workgroup, sequence)
+// intersection is one softmax partial; partial id = w + s is unique because w and s only grow along the
+// stream.  The workgroup that holds a sequence's first / last tile records itself in seg_first / seg_last for
+// the merge kernel; a sequence that lies inside one workgroup is written to `out` directly (seg_first = -1).
+// ---------------------------------------------------------------------------------------------------
+template <int TK>
+__device__ __forceinline__ int32_t tiles_of(int32_t len) { return (len + TK - 1) / TK; }
+
+// Tiles of sequence i in the stream.  RAGGED (called from the prefill entry point): only sequences whose
+// q_len * G rows fit the 16 columns of the matrix instruction take part; the others hold no tiles here and are
+// left to the prefill kernel.
+// A sliding window (window > 0) removes the tiles that lie wholly before the earliest window of the sequence's
+// queries from the stream: the work of a sequence is ceil((len - first_key) / 32) tiles, first_key a multiple of 32.
+template <int TK>
+__device__ __forceinline__ int32_t first_key_of(int32_t len, int32_t q_len, int32_t window)
+{
+    if (window <= 0) return 0;
+    return max(len - q_len - window + 1, 0) & ~(TK - 1);
+}
+
+template <bool RAGGED, int TK>
+__device__ __forceinline__ int32_t seq_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                             int32_t G, int32_t i, int32_t window)
+{
+    int32_t q_len = 1;
+    if (RAGGED) {
+        q_len = cu_q_lens[i + 1] - cu_q_lens[i];
+        if (q_len < 1 || q_len * G > 16) return 0;
+    }
+    const int32_t len = seq_lens[i];
+    return tiles_of<TK>(len - first_key_of<TK>(len, q_len, window));
+}
+
+// Sum of tiles over the batch; every lane returns the same value.
+template <bool RAGGED, int TK>
+__device__ __forceinline__ int32_t total_tiles(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                               int32_t G, int32_t batch, int lane, int32_t window)
+{
+    int32_t n = 0;
+    for (int32_t i = lane; i < batch; i += 64) n += seq_tiles<RAGGED, TK>(seq_lens, cu_q_lens, G, i, window);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+    return n;
+}
+
+// Sequence that holds global tile g (0 <= g < total) and the number of tiles before that sequence.
+template <bool RAGGED, int TK>
+__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ cu_q_lens,
+                                            int32_t G, int32_t batch, int32_t g, int lane, int32_t window,
+                                            int32_t& seq, int32_t& tiles_before)
+{
+    int32_t base = 0;
+    seq = batch;
+    tiles_before = 0;
+    for (int32_t blk = 0; blk < batch; blk += 64) {
+        const int32_t idx = blk + lane;
+        const int32_t n = idx < batch ? seq_tiles<RAGGED, TK>(seq_lens, cu_q_lens, G, idx, window) : 0;
+        int32_t inc = n;                                   // inclusive scan over the 64 lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += t;
+        }
+        const int32_t blk_total = __shfl(inc, 63, 64);
+        if (g < base + blk_total) {
+            const uint64_t hit = __ballot(base + inc > g);
+            const int first = __ffsll((unsigned long long)hit) - 1;
+            seq = blk + first;
+            tiles_before = base + __shfl(inc, first, 64) - __shfl(n, first, 64);
+            return;
+        }
+        base += blk_total;
+    }
+}
+
+// RAGGED: launched from the prefill entry point for the sequences with few queries (q_len * G <= 16): the 16
+// columns are (query, head) pairs, column = query * G + head, each with its own causal bound; q / out / lse rows
+// come from cu_q_lens; partials are 16 rows per KV head.
+// E: element traits (bf16 / fp16).  M: compile-time policy of the mask / score hooks (document masks are not
+// taken here).
+template <int NW, bool UNIFORM, bool RAGGED, typename E, typename M, typename GE>
+__global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
+    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch,
+    int32_t num_q_heads, int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse,
+    int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last, const int32_t* __restrict__ cu_q_lens,
+    int32_t causal, ModArgs mods)
+{
+    constexpr int kD = GE::kD;
+    constexpr int kTileKeys = GE::kTileKeys;
+    const int32_t window = M::kWindow ? mods.window : 0;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int32_t w = blockIdx.x;
+    const int32_t kvh = blockIdx.y * NW + wave;
+    const int32_t G = num_q_heads / cache.num_kv_heads;
+    const int32_t r16 = lane & 15, quad = lane >> 4;
+    const float sc = scale * kLog2e;
+
+    // Only min(nwg, total) workgroups take part, so that every participating one holds at least one tile
+    // and the partials of a sequence belong to consecutive workgroups with none missing.
+    int32_t total, g, g_end, s, before;
+    if (batch <= 64) {
+        // one read of the lengths serves both the total and the search for this workgroup's first sequence
+        const int32_t n = lane < batch ? seq_tiles<RAGGED, kTileKeys>(seq_lens, cu_q_lens, G, lane, window) : 0;
+        int32_t inc = n;                                   // inclusive scan over the 64 lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += t;
+        }
+        total = __shfl(inc, 63, 64);
+        const int32_t nwg = min((int32_t)gridDim.x, total);
+        if (w >= nwg) return;
+        g = (int32_t)(((int64_t)w * total) / nwg);
+        g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
+        const uint64_t hit = __ballot(inc > g);
+        s = __ffsll((unsigned long long)hit) - 1;
+        before = __shfl(inc, s, 64) - __shfl(n, s, 64);
+    } else {
+        total = total_tiles<RAGGED, kTileKeys>(seq_lens, cu_q_lens, G, batch, lane, window);
+        const int32_t nwg = min((int32_t)gridDim.x, total);
+        if (w >= nwg) return;
+        g = (int32_t)(((int64_t)w * total) / nwg);
+        g_end = (int32_t)(((int64_t)(w + 1) * total) / nwg);
+        locate_tile<RAGGED, kTileKeys>(seq_lens, cu_q_lens, G, batch, g, lane, window, s, before);
+    }
+    s = __builtin_amdgcn_readfirstlane(s);
+    before = __builtin_amdgcn_readfirstlane(before);
+
+    Addr a;
+    a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
+    a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
+    a.page_bytes = cache.page_stride * 2;
+    a.token_bytes = cache.token_stride * 2;
+    a.log2_page = cache.log2_page;
+    a.pmask = cache.page_size - 1;
+    a.r16 = r16;
+    a.quad = quad;
+    a.koff = (uint32_t)(r16 * a.token_bytes + quad * 16);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + (r16 & GE::kPieceMask) * 16);
+
+    while (g < g_end) {
+        // segment: tiles [t_begin, t_end) of sequence s
+        const int32_t len = seq_lens[s];
+        const int32_t nt = seq_tiles<RAGGED, kTileKeys>(seq_lens, cu_q_lens, G, s, window);
+        if (nt == 0) { ++s; continue; }                    // sequences without tiles in this stream
+        const int32_t t_begin = g - before;
+        const int32_t t_end = min(nt, g_end - before);
+        // this lane's column: query qi of the sequence's q_len, head h (valid if r16 < rows)
+        int32_t rows = G, qi = 0, q_row = s, q_len = 1;
+        if (RAGGED) {
+            const int32_t q_begin = cu_q_lens[s];
+            q_len = cu_q_lens[s + 1] - q_begin;
+            rows = q_len * G;
+            qi = min(r16, rows - 1) / G;
+            q_row = q_begin + qi;
+        }
+        const int32_t key0 = first_key_of<kTileKeys>(len, q_len, window);   // the stream's first key of this sequence
+        const int32_t c0 = key0 + t_begin * kTileKeys;
+        const int32_t c1 = min(len, key0 + t_end * kTileKeys);
+        const int32_t pos = len - q_len + qi;              // this row's position
+        int32_t lim = c1;
+        if (RAGGED && causal) lim = min(c1, pos + 1);      // keys 0 .. pos
+        RowMods rm;
+        rm.lo = 0;
+        rm.lo_until = 0;
+        rm.pos = pos;
+        rm.slope2 = 0.f;
+        rm.cap_in = 0.f;
+        rm.cap_out = 0.f;
+        rm.scale = scale;
+        if (M::kWindow && window > 0) {
+            rm.lo = pos - window + 1;                      // |j - pos| < window, lower side
+            rm.lo_until = len - window;                    // the last row's lower bound is the largest
+            if (RAGGED && !causal) lim = min(lim, pos + window);
+        }
+        if (M::kScore) {
+            if (mods.alibi_slopes && r16 < rows)
+                rm.slope2 = mods.alibi_slopes[kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16)] * kLog2e;
+            if (mods.softcap > 0.f) {
+                rm.cap_in = scale / mods.softcap;
+                rm.cap_out = mods.softcap * kLog2e;
+            }
+        }
+        const int32_t mask_from = RAGGED ? c1 - 16 : c1;   // q_len <= 16: no bound lies further below the end
+        const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16);
+        const int64_t o_idx = (int64_t)q_row * num_q_heads + h;
+        a.table = block_table + (int64_t)s * max_blocks;
+
+        // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
+        // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
+        uint4 qf[GE::kKS];
+#pragma unroll
+        for (int ks = 0; ks < GE::kKS; ++ks) {
+            qf[ks] = uint4{0, 0, 0, 0};
+            if (r16 < rows) qf[ks] = *reinterpret_cast<const uint4*>(q + o_idx * kD + 32 * ks + 8 * quad);
+        }
+        State<GE> st;
+#pragma unroll
+        for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st.o[c][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.m = -INFINITY;
+        st.l = 0.f;
+
+        // two tiles in registers: while one is computed the other's loads are in flight
+        Tile<GE> ta, tb;
+        load_tile<UNIFORM>(ta, a, c0, c1);
+        for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
+            const int32_t t1 = t0 + kTileKeys;
+            if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
+            compute_tile<RAGGED, E, M, GE>(st, ta, qf, sc, t0, lim, mask_from, quad, rm);
+            if (t1 >= c1) break;
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
+            compute_tile<RAGGED, E, M, GE>(st, tb, qf, sc, t1, lim, mask_from, quad, rm);
+        }
+
+        float l = st.l;
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const bool whole = t_begin == 0 && t_end == nt;    // the sequence's stream lies inside this workgroup
+        // D = 64: accumulator rows 8-15 (lanes of quads 2 and 3) repeat rows 0-7 and are not stored
+        if (r16 < rows && (kD != 64 || quad < 2)) {
+            // l == 0: a row whose causal bound lies before this segment (RAGGED only)
+            const float inv = (!RAGGED || l > 0.f) ? 1.f / l : 0.f;
+            const float lse_nat = (!RAGGED || l > 0.f) ? (st.m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+            if (whole) {
+#pragma unroll
+                for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        uint4 wv;
+                        wv.x = E::pack(st.o[c][0][r] * inv, st.o[c][1][r] * inv);
+                        wv.y = E::pack(st.o[c][2][r] * inv, st.o[c][3][r] * inv);
+                        wv.z = E::pack(st.o[c][4][r] * inv, st.o[c][5][r] * inv);
+                        wv.w = E::pack(st.o[c][6][r] * inv, st.o[c][7][r] * inv);
+                        *reinterpret_cast<uint4*>(out + o_idx * kD + 128 * c + 32 * quad + 8 * r) = wv;
+                    }
+                if (lse && quad == 0) lse[o_idx] = lse_nat;
+            } else {
+                const int64_t p_idx = RAGGED ? ((int64_t)(w + s) * cache.num_kv_heads + kvh) * 16 + r16
+                                             : (int64_t)(w + s) * num_q_heads + h;
+#pragma unroll
+                for (int c = 0; c < GE::kPasses; ++c) {
+                    float* po = part_o + p_idx * kD + 128 * c + 32 * quad;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        *reinterpret_cast<float4*>(po + 8 * r) = float4{st.o[c][0][r] * inv, st.o[c][1][r] * inv,
+                                                                        st.o[c][2][r] * inv, st.o[c][3][r] * inv};
+                        *reinterpret_cast<float4*>(po + 8 * r + 4) = float4{st.o[c][4][r] * inv, st.o[c][5][r] * inv,
+                                                                            st.o[c][6][r] * inv, st.o[c][7][r] * inv};
+                    }
+                }
+                if (quad == 0) part_lse[p_idx] = lse_nat;
+            }
+        }
+        if (wave == 0 && lane == 0 && blockIdx.y == 0) {
+            if (t_begin == 0) seg_first[s] = whole ? -1 : w;
+            if (t_end == nt) seg_last[s] = w;
+        }
+        g = before + t_end;
+        before += nt;
+        ++s;
+    }
+}
+
+template <int NW, typename E, typename M, typename GE>
+void launch_nw(const AttnArgs& a, hipStream_t stream)
+{
+    const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), 1);
+    const bool uniform = a.cache.page_size >= 16;
+    auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true, E, M, GE>
+                                       : paged_decode_mfma_kernel<NW, false, true, E, M, GE>)
+                            : (uniform ? paged_decode_mfma_kernel<NW, true, false, E, M, GE>
+                                       : paged_decode_mfma_kernel<NW, false, false, E, M, GE>);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                       a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.part_o,
+                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal, a.mods);
+}
+
+template <typename E, typename M, typename GE>
+void launch_em(const AttnArgs& a, hipStream_t stream)
+{
+    switch (decode_mfma_heads_per_wg(a.cache.num_kv_heads, GE::kD)) {
+        case 8:
+            if constexpr (GE::kD <= 128) launch_nw<8, E, M, GE>(a, stream);
+            break;
+        case 4: launch_nw<4, E, M, GE>(a, stream); break;
+        case 2: launch_nw<2, E, M, GE>(a, stream); break;
+        default: launch_nw<1, E, M, GE>(a, stream); break;
+    }
+}
+
+}  // namespace
+
+// Every kernel instantiation of one head_dim; defined in that head_dim's translation unit.
+template <int D>
+void launch_decode_mfma_dim(const AttnArgs& a, hipStream_t stream)
+{
+    typedef Mods<true, true, false> WindowScore;
+    typedef Geo<D> GE;
+    if (a.dtype == PA_DTYPE_BF16) {
+        if (a.has_mods) launch_em<ElemBf16, WindowScore, GE>(a, stream);
+        else launch_em<ElemBf16, NoMods, GE>(a, stream);
+    } else {
+        if (a.has_mods) launch_em<ElemF16, WindowScore, GE>(a, stream);
+        else launch_em<ElemF16, NoMods, GE>(a, stream);
+    }
+}
+
+}  // namespace pa

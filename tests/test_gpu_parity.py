@@ -120,6 +120,23 @@ def test_decode_group_sizes(pa, oracle, Hq, Hkv):
     parity.check_step(pa, oracle, w, f"decode Hq={Hq} Hkv={Hkv}")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (32, 8), (16, 1), (24, 8), (64, 4), (12, 4)])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 64), (torch.bfloat16, 256), (torch.float16, 64),
+                                     (torch.float16, 256)])
+@pytest.mark.parametrize("wgs", [0, 7])
+def test_decode_head_dims_on_the_matrix_cores(pa, oracle, Hq, Hkv, dtype, d, wgs):
+    """head_dim 64 (half of each value product unused) and 256 (two column passes, 16-key tiles): every
+    waves-per-workgroup variant, odd and maximal group sizes, default and forced cuts of the tile stream."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[300, 77, 1025, 16, 15, 0, 2049], num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d,
+                        page_size=16, dtype=dtype, seed=35, device=DEV)
+    binding.pa_set_option("decode_workgroups", wgs)
+    try:
+        parity.check_step(pa, oracle, w, f"decode d={d} Hq={Hq} Hkv={Hkv} {dtype} wgs={wgs}")
+    finally:
+        binding.pa_set_option("decode_workgroups", 0)
+
+
 @pytest.mark.parametrize("wgs", [1, 3, 7, 64, 256, 1000])
 def test_decode_split_schedules(pa, oracle, wgs):
     """Every cut of the batch's key-tile stream merges to the same answer (the LSE merge is exact): one
@@ -577,7 +594,8 @@ def build_mods(case, Hq, lens):
 
 
 @pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
-@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 128), (torch.float32, 64)])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 128), (torch.float32, 64),
+                                     (torch.bfloat16, 64), (torch.float16, 256)])
 def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
     lens = [700, 64, 2049, 33, 1, 0, 300]
     w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16, dtype=dtype,
