@@ -67,6 +67,8 @@ def parse():
     ap.add_argument("--dtype", choices=["default", "bf16", "fp16"], default="default",
                     help="16-bit element type of the pools (fp16 is the paper's own precision)")
     ap.add_argument("--page-size", type=int, default=0, help="override the workload's page size (power of two)")
+    ap.add_argument("--head-dim", type=int, default=0, choices=[0, 64, 128, 256],
+                    help="override the head_dim of the 16-bit workloads (default 128)")
     ap.add_argument("--window", type=int, default=0, help="sliding window in tokens (0 = off)")
     ap.add_argument("--alibi", action="store_true", help="add a linear position bias per head")
     ap.add_argument("--cold", action="store_true",
@@ -224,7 +226,7 @@ def main():
         return run_page_manager(torch, binding, args, P)
     if args.page_size:
         P = args.page_size
-    w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True)
+    w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True, head_dim=args.head_dim or None)
     if args.dtype == "fp16" and w.dtype == torch.bfloat16:
         # the same N(0,1) draws rounded to fp16 instead of bf16 (NaN poison survives the conversion)
         for name in ("k_cache", "v_cache", "q", "k_new", "v_new"):

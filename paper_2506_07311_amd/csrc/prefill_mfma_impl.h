@@ -1,0 +1,509 @@
+// Paged prefill (ragged packed queries, optional causal bound) for bf16 / fp16 pools with head_dim D = 128 or 64 on
+// gfx950.  Internal header: the kernel templates; one translation unit per head_dim instantiates them.  The text
+// below describes D = 128.  D = 64 is the same kernel with half the steps: LDS rows keep their 256-byte stride and
+// swizzle, only the positions of the 8 existing 16-byte pieces are read (the fetch fills the other 8 positions
+// with repeats), the score product takes 4 steps instead of 8 and the value product covers 2 column blocks, not 4.
+//
+// Prefill is a dense contraction (about 590 flop per byte at 2048 tokens), so it runs on the matrix cores
+// with v_mfma_f32_32x32x16_bf16 in the flash-attention arrangement: one workgroup of 4 waves owns 128
+// consecutive ROWS of one (sequence, KV head); wave w owns 32 of them.  A row is a (query, query head) pair:
+// the G query heads that share the KV head are packed next to each other (row = query * G + head; G a power of
+// two up to 16, else one head per workgroup), so K and V are streamed once per KV head whatever G is and a
+// call with few queries per sequence (decode rows, speculative tokens, short chunks) still fills the tile G
+// times better.  "Query" below means such a row.  The context is walked in tiles of 64 keys; the launch may
+// cut it into chunks (one workgroup per chunk, partials merged by the split-KV merge kernel) when the call has
+// too few rows to fill the machine.  A tile's K and V rows are fetched page by page through the block table (Algorithm 1:
+// page = block_table[s][j >> log2 P], slot = j & (P-1)) and written STRAIGHT INTO LDS by the load unit
+// (global_load_lds_dwordx4: 16 bytes per lane, a wave fills 4 consecutive 256-byte rows per instruction), one
+// tile ahead of the one being computed, into the other of two 32 KiB buffers -- no staging registers, no LDS
+// store instructions, one barrier per tile.  Rows are unpadded (256 B = all 64 LDS banks); the 16-byte piece L
+// of row r sits at piece L ^ swz(r), swz(r) = 4*(r%4) + (r/4)%4 (each lane simply fetches the piece that belongs
+// at its LDS position), which makes both kinds of operand read conflict-free:
+//   K rows are read as 16-byte MFMA operands (16 consecutive lanes = 16 consecutive rows, same logical piece:
+//     swz takes 16 distinct values),
+//   V rows are read TRANSPOSED with ds_read_b64_tr_b16, the LDS transpose load of gfx950 -- the contraction
+//     index of P.V is the key while memory is contiguous along head_dim (32 lanes read 64 bytes of each of 4
+//     consecutive rows: swz moves them to 4 different quarters of the banks).
+// Both products are computed transposed so that every per-query quantity is lane-local (lane%32 = query):
+//   S^T[key, q]  = K[key, :] . Q[q, :]^T        A = K from LDS, B = Q held in registers for the whole kernel
+//   O^T[col, q] += V^T[col, key] . P^T[key, q]  A = V^T from LDS, B = P straight from the S^T accumulators
+// The accumulator layout of S^T (lane holds keys 8a + 4h + b of its query) is, after packing to bf16, already
+// the B-operand layout of the second product for a permuted key order, and the transpose loads fetch V in that
+// same order.  Online softmax runs in the log2 domain; masking (length, causal, ragged rows) is by selection.
+//
+// Softmax weights enter the matrix cores as bf16.  With few keys the individual weights are large and their
+// 2^-9 rounding shows in the output, so query tiles whose context is at most max(kPreciseKeys, len / 8) keys carry
+// the weights as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
+#pragma once
+
+#include "prefill_tiles.h"
+
+namespace pa {
+
+namespace {
+
+using namespace prefill;
+
+__device__ __forceinline__ uint4 lds_frag(const char* p)
+{
+    return *reinterpret_cast<const uint4*>(p);
+}
+
+// V^T operand of the second product for 32 head_dim columns and one 16-key step, from row-major V.
+// ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block receives element i%4 of the 8 bytes
+// addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.  Lane x = q + 4*j of a block therefore points at
+// key j of the step, columns 4q..4q+3 of the block's 16 columns, and lane i ends up with column i of 4 keys.
+// The two loads fetch the keys of contraction slots 0-3 and 4-7 (8 rows apart; their swizzles differ).
+struct tr_pair {
+    s16x4 lo, hi;
+};
+__device__ __forceinline__ uint4 lds_frag_tr(const char* lo, const char* hi)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    tr_pair r;
+    r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lo));
+    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(hi));
+    return __builtin_bit_cast(uint4, r);
+}
+
+// Online-softmax update with the 32 keys of one half tile.  s holds raw scores on entry; the weights are
+// returned in p.  The running statistic is a REFERENCE exponent m_ref (log2 domain) that may trail the true
+// running max by up to kJump: weights are exp2(score - m_ref) <= 2^kJump, which fp32 sums and bf16 operands
+// carry without loss, and out = O / l does not depend on the reference.  The weights therefore do not wait for
+// the max of the half: they are computed speculatively with the reference as it stands, and only when some
+// query's max jumps more than kJump above its reference (always on its first keys, rarely later) is the
+// reference raised, O and l rescaled and the half's weights recomputed -- a wave-uniform slow path that keeps
+// the common path free of branches between the score and the value products.
+// What the mask / score hooks need per row (this lane's).  Unused without their hook.
+struct RowMods {
+    int32_t lo;         // window: first visible key of this row
+    int32_t lo_until;   // window: tiles that start before this key need the lower mask (wave-uniform)
+    int32_t pos;        // score: the row's absolute position
+    float slope2;       // score: bias slope * log2(e)
+    float cap_in;       // score: scale / softcap, 0 without a cap
+    float cap_out;      // score: softcap * log2(e)
+};
+
+// M: compile-time policy of the hooks.  With score hooks the scores are first rewritten in place as
+// log2(e) * (cap(scale * s) + slope * (key - pos)) and the rest runs with a unit scale.
+template <bool MASK, bool FIRST, typename M, int T>
+__device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T], float& m_ref, float& l, float sc,
+                                             int32_t key0, int32_t nk, const RowMods& rm)
+{
+    if (M::kScore) {
+        const float b0 = rm.slope2 * (float)(key0 - rm.pos);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float x;
+            if (rm.cap_in > 0.f) {   // c * tanh(y / c) with tanh(z) = 1 - 2 / (1 + e^(2z))
+                const float e2z = __builtin_amdgcn_exp2f(s[r] * rm.cap_in * (2.f * kLog2e));
+                x = rm.cap_out * (1.f - 2.f * __builtin_amdgcn_rcpf(1.f + e2z));
+            } else {
+                x = s[r] * sc;
+            }
+            s[r] = x + __builtin_fmaf(rm.slope2, (float)(8 * (r / 4) + (r % 4)), b0);
+        }
+        sc = 1.f;
+    }
+    const bool below = M::kWindow && key0 < rm.lo_until;      // wave-uniform up to the lane's 4-key offset
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (MASK && key0 + 8 * (r / 4) + (r % 4) >= nk) s[r] = -INFINITY;   // mask by selection
+        if (below && key0 + 8 * (r / 4) + (r % 4) < rm.lo) s[r] = -INFINITY;
+        tmax = fmaxf(tmax, s[r]);
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, -m_ref));
+        psum += p[r];
+    }
+    // keep the speculative weights ahead of the branch below (they are dead on its slow path, and the
+    // optimiser would otherwise sink them behind the test, back onto the critical path)
+    asm volatile("" ::"v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7]), "v"(p[8]),
+                 "v"(p[9]), "v"(p[10]), "v"(p[11]), "v"(p[12]), "v"(p[13]), "v"(p[14]), "v"(p[15]));
+    if (FIRST) {
+        // instruction order for the region that holds both score products and this half's softmax: the second
+        // half's 8 matrix instructions are issued with the vector work of the first half's softmax in between
+        constexpr int KS = 2 * T;                             // matrix instructions per score product
+        __builtin_amdgcn_sched_group_barrier(0x100, KS / 2, 0);
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < KS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 72 / KS, 0);
+        }
+    }
+    const float top = pair_max(tmax) * sc;                    // sc > 0: scaling commutes with the max
+    const bool jump = !(top - m_ref <= kJump);                // also true for the NaN / inf of a fresh reference
+    if (__any(jump)) {
+        const float m_new = fmaxf(m_ref, top);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new; // a query with no allowed key so far
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);
+#pragma unroll
+        for (int t = 0; t < T; ++t) o[t] *= alpha;
+        l *= alpha;
+        m_ref = m_new;
+        psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, -m_use));
+            psum += p[r];
+        }
+    }
+    l += psum;
+}
+
+// O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps).  vbuf = V part of the tile buffer,
+// vx[2t], vx[2t+1] = this lane's swizzled transpose-load offsets (slots 0-3 / 4-7) for the 32 columns t.  P^T as B operand of a step:
+// elements e = 0..7 <-> weights 8*step + e.
+template <bool PRECISE, typename E, int T>
+__device__ __forceinline__ void half_pv(f32x16 (&o)[T], const f32x16& s, const char* vbuf, int half,
+                                        const uint32_t (&vx)[2 * T])
+{
+    uint4 va[T], vb[T];
+    const char* v0 = vbuf + (32 * half) * kRow;
+#pragma unroll
+    for (int t = 0; t < T; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
+#pragma unroll
+    for (int t = 0; t < T; ++t) vb[t] = lds_frag_tr(v0 + 16 * kRow + vx[2 * t], v0 + 16 * kRow + vx[2 * t + 1]);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        const int r0 = 8 * st;
+        uint4 w, wl;
+        w.x = E::pack(s[r0 + 0], s[r0 + 1]);
+        w.y = E::pack(s[r0 + 2], s[r0 + 3]);
+        w.z = E::pack(s[r0 + 4], s[r0 + 5]);
+        w.w = E::pack(s[r0 + 6], s[r0 + 7]);
+        if (PRECISE) {   // second 16-bit term of the weights: p = hi + lo, lo = round(p - hi)
+            wl.x = E::pack(s[r0 + 0] - E::lo_of(w.x), s[r0 + 1] - E::hi_of(w.x));
+            wl.y = E::pack(s[r0 + 2] - E::lo_of(w.y), s[r0 + 3] - E::hi_of(w.y));
+            wl.z = E::pack(s[r0 + 4] - E::lo_of(w.z), s[r0 + 5] - E::hi_of(w.z));
+            wl.w = E::pack(s[r0 + 6] - E::lo_of(w.w), s[r0 + 7] - E::hi_of(w.w));
+        } else {
+            wl = w;
+        }
+        const uint4 (&cur)[T] = st ? vb : va;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            o[t] = E::mfma32(cur[t], w, o[t]);
+            if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
+        }
+    }
+}
+
+// S^T of half tile `half` (32 keys) against the wave's 32 queries: 8 chained matrix instructions, the K operand
+// reads kept four ahead.  kx[ks] = this lane's swizzled operand offset for head_dim step ks.
+template <typename E, int KS>
+__device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int half, const uint32_t (&kx)[KS],
+                                            const uint4 (&qf)[KS])
+{
+    constexpr int H = KS / 2;
+    s = (f32x16)(0.f);   // folded into the first matrix instruction's accumulator operand
+    const char* kh = kbuf + (32 * half) * kRow;
+    uint4 ka[H];
+#pragma unroll
+    for (int i = 0; i < H; ++i) ka[i] = lds_frag(kh + kx[i]);
+#pragma unroll
+    for (int i = 0; i < H; ++i) {
+        s = E::mfma32(ka[i], qf[i], s);
+        ka[i] = lds_frag(kh + kx[i + H]);
+    }
+#pragma unroll
+    for (int i = 0; i < H; ++i) s = E::mfma32(ka[i], qf[i + H], s);
+}
+
+// One 64-key tile for one wave, processed as two half tiles of 32 keys so that, within the wave, the softmax of
+// one half (vector ALU) runs under the matrix instructions of the other half:
+//     matrix cores:  S(h0)   S(h1)          PV(h0)          PV(h1)
+//     vector ALU:            softmax(h0)    softmax(h1)
+// buf = tile buffer (K rows, then V rows); key0 = first key of the tile + 4 * (lane/32); nk = keys this lane's
+// query may see (MASK only); sc = scale * log2(e) > 0.
+template <bool PRECISE, bool MASK, typename E, typename M, int T>
+__device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[2 * T], const uint32_t (&vx)[2 * T],
+                                            const uint4 (&qf)[2 * T], f32x16 (&o)[T], float& m, float& l, float sc,
+                                            int32_t key0, int32_t nk, const RowMods& rm)
+{
+    f32x16 s0, s1, p;
+    half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
+    half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
+    half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm);
+    half_pv<PRECISE, E, T>(o, p, buf + kTileBytes, 0, vx);
+    half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm);
+    half_pv<PRECISE, E, T>(o, p, buf + kTileBytes, 1, vx);
+}
+
+template <bool PRECISE, bool UNIFORM, typename E, typename M, int D>
+__device__ __forceinline__ void prefill_body(
+    char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
+    float scale, int32_t causal, const PrefillPlan& plan)
+{
+    constexpr int KS = D / 16, T = D / 32;               // steps of a score product, 32-column blocks of O
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int ql = lane & 31, hh = lane >> 5;
+    // Rows of a workgroup's 128-row tile are (query, head) pairs: the 2^log2_pack query heads packed into a tile
+    // share one KV head, row r of a sequence is query r >> log2_pack, packed head r & (pack - 1).
+    const int32_t lg = plan.log2_pack;
+    const int32_t heads = num_q_heads >> lg;                 // head groups along the grid
+    // Workgroups are dispatched in blockIdx.x order: the row-tile index is the slowest-varying part and runs
+    // backwards, so the whole grid is handed out heaviest (latest causal tiles) first; the context chunks of a
+    // tile follow each other.
+    const int32_t hb = heads * batch;
+    const int32_t slow = (int32_t)(blockIdx.x / hb);
+    const int32_t tile = num_tiles - 1 - slow / plan.nsplit;
+    const int32_t split = slow % plan.nsplit;
+    const int32_t rest = blockIdx.x % hb;
+    const int32_t s = rest / heads;
+    const int32_t hg = rest % heads;
+    const int32_t q_begin = cu_q_lens[s];
+    const int32_t q_len = cu_q_lens[s + 1] - q_begin;
+    const int32_t n_rows = q_len << lg;
+    const int32_t m0 = tile * kBM;
+    if (m0 >= n_rows) return;
+    if (plan.skip_small && q_len * (num_q_heads / cache.num_kv_heads) <= 16) return;
+    const int32_t len = seq_lens[s];
+    // workgroup-wide key range; it also selects which instantiation handles this tile
+    const int32_t q_last = (min(m0 + kBM, n_rows) - 1) >> lg;
+    int32_t nk_wg = len;
+    if (causal) nk_wg = min(len, len - q_len + q_last + 1);
+    nk_wg = max(nk_wg, 0);
+    // sliding window: |key - pos| < window.  The workgroup starts at the 64-aligned key before the window of its
+    // first row and, without a causal bound, ends with the window of its last row.
+    const int32_t window = (M::kWindow && plan.mods.window > 0) ? plan.mods.window : 0;
+    int32_t k_lo = 0;
+    if (window > 0) {
+        k_lo = max(len - q_len + (m0 >> lg) - window + 1, 0) & ~(kBN - 1);
+        if (!causal) nk_wg = max(min(nk_wg, len - q_len + q_last + window), 0);
+    }
+    // Few effective keys mean few, large weights whose 16-bit rounding shows: short contexts and windows, and any
+    // position bias (a steep slope concentrates the weight on a handful of keys however long the context is).
+    // "Few" is relative to the sequence: a row's rounding error falls as 1/sqrt(keys) while the scale its
+    // sequence's outputs are judged on falls with the sequence length, so the bound grows as len / 8 (the rows
+    // below it see at most 1/64 of a causal sequence's tile work).
+    const bool few_keys = nk_wg - k_lo <= max(kPreciseKeys, len >> 3) ||
+                          (M::kScore && plan.mods.alibi_slopes != nullptr);
+    if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
+    // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
+    // reads only the chunks that hold keys of a row)
+    // (without a causal bound a window also cuts the END of a row's range, which the merge does not know: those
+    // chunks must leave explicit empty partials, so the workgroup goes on with zero tiles)
+    if (plan.nsplit > 1 && split * plan.chunk >= nk_wg && !(window > 0 && !causal)) return;
+    const int32_t k_begin = max(split * plan.chunk, k_lo);
+    const int32_t k_end = min(nk_wg, split * plan.chunk + plan.chunk);
+
+    const int32_t G = num_q_heads / cache.num_kv_heads;
+    const int32_t* table = block_table + (int64_t)s * max_blocks;
+
+    // this lane's row: query, head, and key bound
+    const int32_t r_lane = m0 + 32 * wave + ql;
+    const bool q_valid = r_lane < n_rows;
+    const int32_t r_c = min(r_lane, n_rows - 1);
+    const int32_t qi_c = r_c >> lg;
+    const int32_t h = (hg << lg) + (r_c & ((1 << lg) - 1));
+    const int32_t kvh = (hg << lg) / G;
+    const int32_t pos = len - q_len + qi_c;                  // the row's absolute position
+    int32_t nk = len;                                        // keys 0 .. nk-1 are allowed
+    if (causal) nk = min(len, pos + 1);
+    else if (window > 0) nk = min(len, pos + window);
+    nk = max(nk, 0);
+    // per wave: the largest bound of its 32 rows decides which tiles it can skip, the smallest which
+    // tiles need no mask
+    const int32_t pos_first = len - q_len + (min(m0 + 32 * wave, n_rows - 1) >> lg);
+    const int32_t pos_last = len - q_len + (min(m0 + 32 * wave + 31, n_rows - 1) >> lg);
+    int32_t nk_wave = len, nk_wave_min = len;
+    if (causal) {
+        nk_wave = min(len, pos_last + 1);
+        nk_wave_min = min(len, pos_first + 1);
+    } else if (window > 0) {
+        nk_wave = min(len, pos_last + window);
+        nk_wave_min = min(len, pos_first + window);
+    }
+    nk_wave = max(nk_wave, 0);
+    nk_wave_min = max(nk_wave_min, 0);
+    RowMods rm;
+    rm.lo = 0;
+    rm.lo_until = 0;
+    rm.pos = pos;
+    rm.slope2 = 0.f;
+    rm.cap_in = 0.f;
+    rm.cap_out = 0.f;
+    int32_t lo_wave = 0;                                     // tiles that end at or before it hold nothing for the wave
+    if (window > 0) {
+        rm.lo = pos - window + 1;
+        rm.lo_until = pos_last - window + 1;
+        lo_wave = pos_first - window + 1;
+    }
+    if (M::kScore) {
+        if (plan.mods.alibi_slopes) rm.slope2 = plan.mods.alibi_slopes[h] * kLog2e;
+        if (plan.mods.softcap > 0.f) {
+            rm.cap_in = scale / plan.mods.softcap;
+            rm.cap_out = plan.mods.softcap * kLog2e;
+        }
+    }
+
+    const int64_t row = (int64_t)(q_begin + qi_c) * num_q_heads + h;
+    // Q as B operand: lane%32 = query, step ks covers head_dim elements 16*ks + 8*hh .. +7
+    uint4 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(q + row * D + 16 * ks + 8 * hh);
+
+    f32x16 o[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const float sc = scale * kLog2e;
+
+    // swizzled LDS offsets of this lane's operands (see the header): K piece (2*ks + hh) of row ql,
+    // V pieces of the 32 columns t for the lane's transpose-load row
+    uint32_t kx[KS], vx[2 * T];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kx[ks] = ql * kRow + 16 * ((2 * ks + hh) ^ swz(ql));
+    {
+        // transpose-load rows of this lane: key 4*hh + j (+8 for slots 4-7) of a 16-key step, columns 4*qq..+3 of
+        // the 16-column block dblk of the 32 columns t
+        const int j = (lane & 15) >> 2, qq = lane & 3, dblk = (lane >> 4) & 1;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int piece = 4 * t + 2 * dblk + (qq >> 1);
+            vx[2 * t] = (4 * hh + j) * kRow + 16 * (piece ^ swz(4 * hh + j)) + 8 * (qq & 1);
+            vx[2 * t + 1] = (4 * hh + j + 8) * kRow + 16 * (piece ^ swz(4 * hh + j + 8)) + 8 * (qq & 1);
+        }
+    }
+    // fetch role of this lane: position lane%16 of rows 16*i + frow holds logical piece (lane%16) ^ swz(frow)
+    const int frow = 4 * wave + (lane >> 4);
+    // (a row of head_dim 64 has 8 pieces: the other 8 positions of the LDS row receive repeats that nobody reads)
+    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + 16 * (((lane & 15) ^ swz(frow)) & (D / 8 - 1)));
+    const int32_t wrow = __builtin_amdgcn_readfirstlane(4 * wave * kRow);
+    const int32_t last_key = len - 1;
+
+    PageIds ids;
+    const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
+    if (n_tiles > 0) {
+        load_ids<UNIFORM>(ids, cache, table, k_begin, frow, last_key);
+        fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, k_begin, frow, last_key, lane_off);
+        if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, k_begin + kBN, frow, last_key);
+        __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
+    }
+    // Two tiles per trip so that each buffer is a distinct LDS object for the compiler: while the matrix cores
+    // read one, the load unit fills the other with the next tile; the page ids of the tile after that are requested
+    // at the same time.  The barrier at the end of a tile waits for this wave's loads first.
+    for (int32_t t = 0; t < n_tiles; t += 2) {
+        const int32_t t0 = k_begin + t * kBN;
+        if (t + 1 < n_tiles) {
+            fetch_tile<UNIFORM>(buf1 + wrow, ids, cache, t0 + kBN, frow, last_key, lane_off);
+            if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
+        }
+        if (t0 < nk_wave && t0 + kBN > lo_wave) {            // wave-uniform: else nothing for this wave here
+            if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
+                attend_tile<PRECISE, true, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
+            else
+                attend_tile<PRECISE, false, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
+        }
+        __syncthreads();
+        if (t + 1 >= n_tiles) break;
+        const int32_t t1 = t0 + kBN;
+        if (t + 2 < n_tiles) {
+            fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, t1 + kBN, frow, last_key, lane_off);
+            if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
+        }
+        if (t1 < nk_wave && t1 + kBN > lo_wave) {
+            if (t1 + kBN > nk_wave_min)
+                attend_tile<PRECISE, true, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
+            else
+                attend_tile<PRECISE, false, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
+        }
+        __syncthreads();
+    }
+
+    l += __shfl_xor(l, 32, 64);
+    if (!q_valid) return;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    // o[t][r]: column 32*t + 8*(r/4) + 4*hh + r%4 of this lane's query
+    if (plan.nsplit > 1) {
+        // partial of this chunk: normalised output in fp32 and the natural-log LSE over the chunk's keys
+        const int64_t pidx = row * plan.nsplit + split;
+        float* prow = plan.part_o + pidx * D;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                float4 w;
+                w.x = o[t][4 * a + 0] * inv;
+                w.y = o[t][4 * a + 1] * inv;
+                w.z = o[t][4 * a + 2] * inv;
+                w.w = o[t][4 * a + 3] * inv;
+                *reinterpret_cast<float4*>(prow + 32 * t + 8 * a + 4 * hh) = w;
+            }
+        if (hh == 0) plan.part_lse[pidx] = l > 0.f ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+        return;
+    }
+    uint16_t* orow = out + row * D;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            uint2 w;
+            w.x = E::pack(o[t][4 * a + 0] * inv, o[t][4 * a + 1] * inv);
+            w.y = E::pack(o[t][4 * a + 2] * inv, o[t][4 * a + 3] * inv);
+            *reinterpret_cast<uint2*>(orow + 32 * t + 8 * a + 4 * hh) = w;
+        }
+    if (lse && hh == 0) lse[row] = l > 0.f ? (m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+}
+
+// Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
+// workgroup runs exactly one of them, decided by its context length.
+template <bool UNIFORM, typename E, typename M, int D>
+__global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
+    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
+    float scale, int32_t causal, PrefillPlan plan)
+{
+    __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
+    prefill_body<false, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+                                 num_q_heads, max_blocks, scale, causal, plan);
+    prefill_body<true, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+                                num_q_heads, max_blocks, scale, causal, plan);
+}
+
+}  // namespace
+
+// Every kernel instantiation of one head_dim; defined in that head_dim's translation unit.
+template <int D>
+pa_status launch_prefill_mfma_dim(const AttnArgs& a, const PrefillPlan& plan, int64_t blocks, int64_t tiles,
+                                  hipStream_t stream)
+{
+    const dim3 grid((uint32_t)blocks, 1, 1);
+    // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
+    const bool uniform = a.cache.page_size >= 16;
+    typedef Mods<true, true, false> WindowScore;
+    auto kern = paged_prefill_mfma_kernel<true, ElemBf16, NoMods, D>;
+    if (a.dtype == PA_DTYPE_BF16) {
+        if (a.has_mods) kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, WindowScore, D>
+                                       : paged_prefill_mfma_kernel<false, ElemBf16, WindowScore, D>;
+        else if (!uniform) kern = paged_prefill_mfma_kernel<false, ElemBf16, NoMods, D>;
+    } else {
+        if (a.has_mods) kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, WindowScore, D>
+                                       : paged_prefill_mfma_kernel<false, ElemF16, WindowScore, D>;
+        else kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, NoMods, D>
+                            : paged_prefill_mfma_kernel<false, ElemF16, NoMods, D>;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                       a.cu_q_lens, a.block_table, a.seq_lens, a.batch, (int32_t)tiles, a.num_q_heads, a.max_blocks,
+                       a.scale, a.causal, plan);
+    return launch_status();
+}
+
+}  // namespace pa

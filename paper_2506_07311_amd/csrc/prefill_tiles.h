@@ -10,7 +10,6 @@ namespace prefill {
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef mfma_f32x16 f32x16;
 
-constexpr int kD = 128;
 constexpr int kBM = 128;              // rows per workgroup of the 32-rows-per-wave kernel
 constexpr int kBN = 64;               // keys per tile
 constexpr int kThreads = 256;
@@ -39,7 +38,7 @@ struct PrefillPlan {
     int32_t chunk;        // context tokens per workgroup (multiple of 64 and of the page size when nsplit > 1)
     int32_t nsplit;       // chunks along the grid; > 1: partials go to part_o / part_lse for the merge kernel
     int32_t skip_small;   // 1: sequences with q_len * G <= 16 are computed by the decode kernel, not here
-    float* part_o;        // [total_q, Hq, nsplit, 128]
+    float* part_o;        // [total_q, Hq, nsplit, head_dim]
     float* part_lse;      // [total_q, Hq, nsplit]
     ModArgs mods;         // mask / score hooks (used by the instantiations that have them)
 };

@@ -242,9 +242,11 @@ def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> List[int]:
 
 
 def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_size: Optional[int] = None,
-           shrink: int = 1, poison: bool = True) -> PagedWorkload:
+           shrink: int = 1, poison: bool = True, head_dim: Optional[int] = None) -> PagedWorkload:
     """The five benchmark workloads (1-based), then three jagged-batch workloads (6-8).  ``shrink`` divides context lengths
-    (and config 4's length range) for cases the CPU oracle must finish in seconds."""
+    (and config 4's length range) for cases the CPU oracle must finish in seconds; ``head_dim`` overrides the 128 of
+    the 16-bit workloads (2-8)."""
+    hd = head_dim or 128
     if n == 1:   # single-sequence fp32 decode, 8 of 64 pages used
         L = context or 128
         return make_workload("cfg1_fp32_single_decode", seq_lens=[L], num_q_heads=8, num_kv_heads=8,
@@ -253,29 +255,29 @@ def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_s
     if n == 2:   # batched GQA decode, bf16
         L = context or 2048
         return make_workload(f"cfg2_bf16_gqa_decode_L{L}", seq_lens=[L] * 8, num_q_heads=32, num_kv_heads=8,
-                             head_dim=128, page_size=page_size or 16, seed=2, device=device, poison=poison)
+                             head_dim=hd, page_size=page_size or 16, seed=2, device=device, poison=poison)
     if n == 3:   # causal prefill, bf16; every token is appended this step
         S = context or max(16, 2048 // shrink)
         return make_workload(f"cfg3_bf16_causal_prefill_S{S}", seq_lens=[S] * 4, q_lens=[S] * 4,
-                             num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=page_size or 16,
+                             num_q_heads=32, num_kv_heads=8, head_dim=hd, page_size=page_size or 16,
                              causal=True, seed=3, device=device, poison=poison)
     if n == 4:   # mixed-length decode with shared prefixes
         hi = max(128, 32768 // shrink)
         lens = log_uniform_lengths(64, 64, hi, seed=4)
         return make_workload(f"cfg4_bf16_mixed_decode_max{hi}", seq_lens=lens, num_q_heads=32, num_kv_heads=8,
-                             head_dim=128, page_size=page_size or 16, share_group=8,
+                             head_dim=hd, page_size=page_size or 16, share_group=8,
                              share_prefix_tokens=max(16, 1024 // shrink), seed=4, device=device, poison=poison)
     if n == 5:   # long-context split-KV decode
         L = context or max(64, 131072 // shrink)
         P = page_size or 16
         return make_workload(f"cfg5_bf16_long_decode_L{L}_P{P}", seq_lens=[L] * 16, num_q_heads=64,
-                             num_kv_heads=8, head_dim=128, page_size=P, seed=5, device=device, poison=poison)
+                             num_kv_heads=8, head_dim=hd, page_size=P, seed=5, device=device, poison=poison)
     # Jagged-batch workloads of the prefill entry point (Sec. III-B: ragged queries described by prefix sums).
     if n == 6:   # chat growth: one 1024-token chunk appended behind 31744 cached tokens (1k -> 32k incremental)
         L = context or max(128, 32768 // shrink)
         chunk = max(16, 1024 // shrink)
         return make_workload(f"cfg6_bf16_chunked_prefill_{chunk}_on_{L - chunk}", seq_lens=[L], q_lens=[chunk],
-                             num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=page_size or 16, causal=True,
+                             num_q_heads=32, num_kv_heads=8, head_dim=hd, page_size=page_size or 16, causal=True,
                              seed=6, device=device, poison=poison)
     if n in (7, 8):   # config 4's length mix; 7: four sequences prefill 512 tokens while sixty decode; 8: four
         hi = max(128, 32768 // shrink)            # speculative tokens per sequence
@@ -285,6 +287,6 @@ def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_s
         else:
             q_lens = [min(L, 4) for L in lens]
         return make_workload(f"cfg{n}_bf16_jagged_max{hi}", seq_lens=lens, q_lens=q_lens, num_q_heads=32,
-                             num_kv_heads=8, head_dim=128, page_size=page_size or 16, causal=True, seed=n,
+                             num_kv_heads=8, head_dim=hd, page_size=page_size or 16, causal=True, seed=n,
                              device=device, poison=poison)
     raise ValueError(f"no config {n}")
