@@ -55,6 +55,14 @@ WORKLOADS = {
 }
 
 
+def measured_traffic(args):
+    """The committed counter figures belong to a workload as it is defined; a run that overrides its shape, element
+    type or hooks has no measured traffic."""
+    if args.head_dim or args.page_size or args.window or args.alibi or args.dtype == "fp16":
+        return None
+    return MEASURED_TRAFFIC.get(args.workload)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -361,7 +369,7 @@ def main():
         small_bytes = sum(L for L, sm in zip(w.seq_lens_host, small) if sm) * 2 * w.num_kv_heads * w.head_dim * 2
         ach = small_bytes / (t_dec * 1e-6) / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args),
                               "kernel": "paged_decode_mfma_kernel", "algorithmic_bytes": small_bytes,
                               "note": "KV bytes of the sequences the decode kernel computes in this call"}
     elif is_prefill:
@@ -382,14 +390,14 @@ def main():
         ach = flops / (dom["avg_us"] * 1e-6) / 1e12
         result["roofline"] = {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                               "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
-                              "traffic": MEASURED_TRAFFIC.get(args.workload),
+                              "traffic": measured_traffic(args),
                               "kernel": "paged_prefill_mfma_kernel" if "paged_prefill_mfma_kernel" in kernels
                               else "paged_attention_generic_kernel", "useful_flops": flops}
     else:
         name = "paged_decode_mfma_kernel" if "paged_decode_mfma_kernel" in kernels else "paged_attention_generic_kernel"
         ach = kv_bytes / (kernels[name]["avg_us"] * 1e-6) / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                              "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args),
                               "kernel": name,
                               "algorithmic_bytes": kv_bytes}
 
