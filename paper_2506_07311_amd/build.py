@@ -14,7 +14,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpagedattn.so")
 SOURCES = ["api.hip", "kv_copy.hip", "attention_generic.hip", "merge.hip", "decode_mfma.hip", "decode_mfma_d64.hip",
-           "decode_mfma_d256.hip", "prefill_mfma.hip", "prefill_mfma_d64.hip", "page_pool.hip"]
+           "decode_mfma_d256.hip", "prefill_mfma.hip", "prefill_mfma_d64.hip", "prefill_mfma_d256.hip",
+           "page_pool.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "prefill_tiles.h"),
            os.path.join(CSRC, "decode_mfma_impl.h"), os.path.join(CSRC, "prefill_mfma_impl.h"),
            os.path.join(HERE, "..", "include", "pagedattn.h")]

@@ -9,11 +9,14 @@ using namespace prefill;
 template pa_status launch_prefill_mfma_dim<128>(const AttnArgs&, const PrefillPlan&, int64_t, int64_t, hipStream_t);
 extern template pa_status launch_prefill_mfma_dim<64>(const AttnArgs&, const PrefillPlan&, int64_t, int64_t,
                                                       hipStream_t);
+extern template pa_status launch_prefill_mfma_dim<256>(const AttnArgs&, const PrefillPlan&, int64_t, int64_t,
+                                                       hipStream_t);
 
 bool prefill_mfma_supported(const AttnArgs& a)
 {
     if (a.dtype != PA_DTYPE_BF16 && a.dtype != PA_DTYPE_F16) return false;
-    if (a.cache.head_dim != 128 && a.cache.head_dim != 64) return false;
+    const int32_t d = a.cache.head_dim;
+    if (d != 128 && d != 64 && !(d == 256 && a.cache.page_size >= 16)) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
     if (a.has_mods && a.mods.doc_ids) return false;   // document masks: portable kernel
     return true;
@@ -45,8 +48,9 @@ pa_status launch_prefill_mfma(const AttnArgs& a, hipStream_t stream)
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
     {
         ProfileScope prof("paged_prefill_mfma_kernel", stream);
-        const pa_status st = a.cache.head_dim == 64 ? launch_prefill_mfma_dim<64>(a, plan, blocks, tiles, stream)
-                                                    : launch_prefill_mfma_dim<128>(a, plan, blocks, tiles, stream);
+        const pa_status st = a.cache.head_dim == 64    ? launch_prefill_mfma_dim<64>(a, plan, blocks, tiles, stream)
+                             : a.cache.head_dim == 256 ? launch_prefill_mfma_dim<256>(a, plan, blocks, tiles, stream)
+                                                       : launch_prefill_mfma_dim<128>(a, plan, blocks, tiles, stream);
         if (st != PA_OK || plan.nsplit == 1) return st;
     }
     return launch_merge(a, stream);

@@ -1,8 +1,10 @@
 // Paged prefill (ragged packed queries, optional causal bound) for bf16 / fp16 pools with head_dim D = 128 or 64 on
-// gfx950.  Internal header: the kernel templates; one translation unit per head_dim instantiates them.  The text
-// below describes D = 128.  D = 64 is the same kernel with half the steps: LDS rows keep their 256-byte stride and
+// gfx950 (and D = 256 for page sizes of 16 and more).  Internal header: the kernel templates; one translation unit
+// per head_dim instantiates them.  The text below describes D = 128.  D = 64 is the same kernel with half the steps: LDS rows keep their 256-byte stride and
 // swizzle, only the positions of the 8 existing 16-byte pieces are read (the fetch fills the other 8 positions
-// with repeats), the score product takes 4 steps instead of 8 and the value product covers 2 column blocks, not 4.
+// with repeats), the score product takes 4 steps instead of 8 and the value product covers 2 column blocks, not 4.  D = 256 doubles the
+// steps and the column blocks: LDS rows are 512 bytes (two swizzled 256-byte halves), the two tile buffers fill 128 KiB
+// and the 128 accumulator registers of O leave room for one workgroup per compute unit only.
 //
 // Prefill is a dense contraction (about 590 flop per byte at 2048 tokens), so it runs on the matrix cores
 // with v_mfma_f32_32x32x16_bf16 in the flash-attention arrangement: one workgroup of 4 waves owns 128
@@ -43,6 +45,44 @@ namespace pa {
 namespace {
 
 using namespace prefill;
+
+// LDS row stride of a K or V row: 256 bytes up to head_dim 128, 512 bytes at head_dim 256.  The swizzle always
+// permutes the 16 pieces of a 256-byte half row among themselves (every row starts at bank 0 either way).
+template <int D>
+struct RowGeo {
+    static constexpr int kRowB = D > 128 ? 512 : 256;
+    static constexpr int kTileB = kBN * kRowB;        // K part of a tile buffer; the V part follows
+    static constexpr int kBufB = 2 * kTileB;
+};
+// byte offset inside its row of logical 16-byte piece L of LDS row r
+__device__ __forceinline__ int piece_pos(int L, int r) { return 16 * ((L & 16) | ((L & 15) ^ swz(r))); }
+
+// Tile fetch for 512-byte rows: one load-to-LDS instruction of a wave fills 2 consecutive rows (lane l: position
+// l%32 of row l/32); wave w issues, for i < 8, the K and V instructions of rows 8*i + 2*w, +1.  dst = buffer +
+// 2*w*512; row = 2*w + lane/32; lane_off[i & 1] = kv-head offset + this lane's logical piece, which depends on the
+// parity of i through the swizzle of row 8*i + row.
+template <bool UNIFORM>
+__device__ __forceinline__ void fetch_tile512(char* dst, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
+                                              int32_t last_key, const uint32_t (&lane_off)[2])
+{
+    constexpr int TB = RowGeo<256>::kTileB;
+    const int32_t pg[4] = {p.p0, p.p1, p.p2, p.p3};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int32_t key = t0 + 8 * i + row;
+        const int32_t slot = min(key, last_key) & (cache.page_size - 1);
+        int64_t off;
+        if (UNIFORM)
+            off = (int64_t)pg[i >> 1] * cache.page_stride * 2 +
+                  ((uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off[i & 1]);
+        else
+            off = ((int64_t)pg[i >> 1] * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off[i & 1];
+        char* d = dst + i * (8 * 512);
+        __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.k) + off), (lds_void*)d, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.v) + off), (lds_void*)(d + TB),
+                                         16, 0, 0);
+    }
+}
 
 __device__ __forceinline__ uint4 lds_frag(const char* p)
 {
@@ -167,12 +207,16 @@ template <bool PRECISE, typename E, int T>
 __device__ __forceinline__ void half_pv(f32x16 (&o)[T], const f32x16& s, const char* vbuf, int half,
                                         const uint32_t (&vx)[2 * T])
 {
-    uint4 va[T], vb[T];
-    const char* v0 = vbuf + (32 * half) * kRow;
+    constexpr int RB = T > 4 ? 512 : 256;
+    constexpr int TF = T > 4 ? 1 : T;                       // fragments read ahead of the first step
+    uint4 va[T], vb[TF];
+    const char* v0 = vbuf + (32 * half) * RB;
 #pragma unroll
     for (int t = 0; t < T; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
+    if (T <= 4) {
 #pragma unroll
-    for (int t = 0; t < T; ++t) vb[t] = lds_frag_tr(v0 + 16 * kRow + vx[2 * t], v0 + 16 * kRow + vx[2 * t + 1]);
+        for (int t = 0; t < TF; ++t) vb[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
+    }
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
         const int r0 = 8 * st;
@@ -189,11 +233,21 @@ __device__ __forceinline__ void half_pv(f32x16 (&o)[T], const f32x16& s, const c
         } else {
             wl = w;
         }
-        const uint4 (&cur)[T] = st ? vb : va;
+        if constexpr (T <= 4) {
+            const uint4 (&cur)[T] = st ? vb : va;
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            o[t] = E::mfma32(cur[t], w, o[t]);
-            if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
+            for (int t = 0; t < T; ++t) {
+                o[t] = E::mfma32(cur[t], w, o[t]);
+                if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
+            }
+        } else {
+            // wide rows: the second step's fragments take the place of the first step's as those are consumed
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                o[t] = E::mfma32(va[t], w, o[t]);
+                if (PRECISE) o[t] = E::mfma32(va[t], wl, o[t]);
+                if (st == 0) va[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
+            }
         }
     }
 }
@@ -204,19 +258,17 @@ template <typename E, int KS>
 __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int half, const uint32_t (&kx)[KS],
                                             const uint4 (&qf)[KS])
 {
-    constexpr int H = KS / 2;
+    constexpr int RB = KS > 8 ? 512 : 256;
     s = (f32x16)(0.f);   // folded into the first matrix instruction's accumulator operand
-    const char* kh = kbuf + (32 * half) * kRow;
-    uint4 ka[H];
+    const char* kh = kbuf + (32 * half) * RB;
+    uint4 ka[4];
 #pragma unroll
-    for (int i = 0; i < H; ++i) ka[i] = lds_frag(kh + kx[i]);
+    for (int i = 0; i < 4; ++i) ka[i] = lds_frag(kh + kx[i]);
 #pragma unroll
-    for (int i = 0; i < H; ++i) {
-        s = E::mfma32(ka[i], qf[i], s);
-        ka[i] = lds_frag(kh + kx[i + H]);
+    for (int i = 0; i < KS; ++i) {
+        s = E::mfma32(ka[i & 3], qf[i], s);
+        if (i + 4 < KS) ka[i & 3] = lds_frag(kh + kx[i + 4]);
     }
-#pragma unroll
-    for (int i = 0; i < H; ++i) s = E::mfma32(ka[i], qf[i + H], s);
 }
 
 // One 64-key tile for one wave, processed as two half tiles of 32 keys so that, within the wave, the softmax of
@@ -234,9 +286,10 @@ __device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx
     half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
     half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
     half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm);
-    half_pv<PRECISE, E, T>(o, p, buf + kTileBytes, 0, vx);
+    constexpr int TB = kBN * (T > 4 ? 512 : 256);
+    half_pv<PRECISE, E, T>(o, p, buf + TB, 0, vx);
     half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm);
-    half_pv<PRECISE, E, T>(o, p, buf + kTileBytes, 1, vx);
+    half_pv<PRECISE, E, T>(o, p, buf + TB, 1, vx);
 }
 
 template <bool PRECISE, bool UNIFORM, typename E, typename M, int D>
@@ -247,6 +300,7 @@ __device__ __forceinline__ void prefill_body(
     float scale, int32_t causal, const PrefillPlan& plan)
 {
     constexpr int KS = D / 16, T = D / 32;               // steps of a score product, 32-column blocks of O
+    constexpr int RB = RowGeo<D>::kRowB;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int ql = lane & 31, hh = lane >> 5;
@@ -368,7 +422,7 @@ __device__ __forceinline__ void prefill_body(
     // V pieces of the 32 columns t for the lane's transpose-load row
     uint32_t kx[KS], vx[2 * T];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kx[ks] = ql * kRow + 16 * ((2 * ks + hh) ^ swz(ql));
+    for (int ks = 0; ks < KS; ++ks) kx[ks] = ql * RB + piece_pos(2 * ks + hh, ql);
     {
         // transpose-load rows of this lane: key 4*hh + j (+8 for slots 4-7) of a 16-key step, columns 4*qq..+3 of
         // the 16-column block dblk of the 32 columns t
@@ -376,22 +430,32 @@ __device__ __forceinline__ void prefill_body(
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int piece = 4 * t + 2 * dblk + (qq >> 1);
-            vx[2 * t] = (4 * hh + j) * kRow + 16 * (piece ^ swz(4 * hh + j)) + 8 * (qq & 1);
-            vx[2 * t + 1] = (4 * hh + j + 8) * kRow + 16 * (piece ^ swz(4 * hh + j + 8)) + 8 * (qq & 1);
+            vx[2 * t] = (4 * hh + j) * RB + piece_pos(piece, 4 * hh + j) + 8 * (qq & 1);
+            vx[2 * t + 1] = (4 * hh + j + 8) * RB + piece_pos(piece, 4 * hh + j + 8) + 8 * (qq & 1);
         }
     }
-    // fetch role of this lane: position lane%16 of rows 16*i + frow holds logical piece (lane%16) ^ swz(frow)
-    const int frow = 4 * wave + (lane >> 4);
-    // (a row of head_dim 64 has 8 pieces: the other 8 positions of the LDS row receive repeats that nobody reads)
-    const uint32_t lane_off = (uint32_t)(kvh * cache.head_stride * 2 + 16 * (((lane & 15) ^ swz(frow)) & (D / 8 - 1)));
-    const int32_t wrow = __builtin_amdgcn_readfirstlane(4 * wave * kRow);
+    // fetch role of this lane.  256-byte rows: position lane%16 of rows 16*i + frow holds logical piece
+    // (lane%16) ^ swz(frow) (a row of head_dim 64 has 8 pieces: the other 8 positions receive repeats that nobody
+    // reads).  512-byte rows: position lane%32 of rows 8*i + frow; the swizzle of that row depends on the parity of i.
+    const int frow = D > 128 ? 2 * wave + (lane >> 5) : 4 * wave + (lane >> 4);
+    const uint32_t head_off = (uint32_t)(kvh * cache.head_stride * 2);
+    const uint32_t lane_off = head_off + 16 * (((lane & 15) ^ swz(frow)) & (D / 8 - 1));
+    uint32_t lane_off2[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+        lane_off2[par] = head_off + 16 * ((lane & 16) | ((lane & 15) ^ swz(8 * par + frow)));
+    const int32_t wrow = __builtin_amdgcn_readfirstlane(D > 128 ? 2 * wave * 512 : 4 * wave * 256);
     const int32_t last_key = len - 1;
+    auto fetch = [&](char* buf, const PageIds& pg, int32_t t0) {
+        if constexpr (D > 128) fetch_tile512<UNIFORM>(buf + wrow, pg, cache, t0, frow, last_key, lane_off2);
+        else fetch_tile<UNIFORM>(buf + wrow, pg, cache, t0, frow, last_key, lane_off);
+    };
 
     PageIds ids;
     const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
     if (n_tiles > 0) {
         load_ids<UNIFORM>(ids, cache, table, k_begin, frow, last_key);
-        fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, k_begin, frow, last_key, lane_off);
+        fetch(buf0, ids, k_begin);
         if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, k_begin + kBN, frow, last_key);
         __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
     }
@@ -401,7 +465,7 @@ __device__ __forceinline__ void prefill_body(
     for (int32_t t = 0; t < n_tiles; t += 2) {
         const int32_t t0 = k_begin + t * kBN;
         if (t + 1 < n_tiles) {
-            fetch_tile<UNIFORM>(buf1 + wrow, ids, cache, t0 + kBN, frow, last_key, lane_off);
+            fetch(buf1, ids, t0 + kBN);
             if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
         }
         if (t0 < nk_wave && t0 + kBN > lo_wave) {            // wave-uniform: else nothing for this wave here
@@ -414,7 +478,7 @@ __device__ __forceinline__ void prefill_body(
         if (t + 1 >= n_tiles) break;
         const int32_t t1 = t0 + kBN;
         if (t + 2 < n_tiles) {
-            fetch_tile<UNIFORM>(buf0 + wrow, ids, cache, t1 + kBN, frow, last_key, lane_off);
+            fetch(buf0, ids, t1 + kBN);
             if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
         }
         if (t1 < nk_wave && t1 + kBN > lo_wave) {
@@ -464,14 +528,14 @@ __device__ __forceinline__ void prefill_body(
 // Both instantiations live in one kernel as two separate code paths (each with its own tile loop); a
 // workgroup runs exactly one of them, decided by its context length.
 template <bool UNIFORM, typename E, typename M, int D>
-__global__ __launch_bounds__(kThreads, 2) void paged_prefill_mfma_kernel(
+__global__ __launch_bounds__(kThreads, D > 128 ? 1 : 2) void paged_prefill_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
     float scale, int32_t causal, PrefillPlan plan)
 {
-    __shared__ __attribute__((aligned(1024))) char buf0[kBufBytes];
-    __shared__ __attribute__((aligned(1024))) char buf1[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) char buf0[RowGeo<D>::kBufB];
+    __shared__ __attribute__((aligned(1024))) char buf1[RowGeo<D>::kBufB];
     prefill_body<false, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                  num_q_heads, max_blocks, scale, causal, plan);
     prefill_body<true, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
@@ -488,6 +552,7 @@ pa_status launch_prefill_mfma_dim(const AttnArgs& a, const PrefillPlan& plan, in
     const dim3 grid((uint32_t)blocks, 1, 1);
     // page sizes of 16 and more make the page of a 16-key group wave-uniform (scalar page translation)
     const bool uniform = a.cache.page_size >= 16;
+    if (D > 128 && !uniform) return PA_ERR_UNSUPPORTED;   // 512-byte rows: two rows per load must share a page
     typedef Mods<true, true, false> WindowScore;
     auto kern = paged_prefill_mfma_kernel<true, ElemBf16, NoMods, D>;
     if (a.dtype == PA_DTYPE_BF16) {

@@ -212,6 +212,22 @@ def test_prefill_head_dim_64_on_the_matrix_cores(pa, oracle, Hq, Hkv, dtype, P, 
         binding.pa_set_option("prefill_chunk_tokens", 0)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (32, 8), (16, 1), (24, 8)])
+@pytest.mark.parametrize("dtype,P", [(torch.bfloat16, 16), (torch.float16, 64), (torch.bfloat16, 128), (torch.bfloat16, 4)])
+@pytest.mark.parametrize("causal,chunk", [(True, 0), (False, 0), (True, 256)])
+def test_prefill_head_dim_256_on_the_matrix_cores(pa, oracle, Hq, Hkv, dtype, P, causal, chunk):
+    """head_dim 256: 512-byte LDS rows, 16 steps per score product, 8 column blocks of O, one workgroup per compute
+    unit (page sizes below 16 take the portable kernel)."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[300, 77, 513, 40, 0, 1300], q_lens=[300, 1, 130, 7, 0, 260], num_q_heads=Hq,
+                        num_kv_heads=Hkv, head_dim=256, page_size=P, dtype=dtype, causal=causal, seed=48, device=DEV)
+    binding.pa_set_option("prefill_chunk_tokens", chunk)
+    try:
+        parity.check_step(pa, oracle, w, f"prefill d=256 Hq={Hq} Hkv={Hkv} {dtype} P={P} causal={causal} chunk={chunk}")
+    finally:
+        binding.pa_set_option("prefill_chunk_tokens", 0)
+
+
 @pytest.mark.parametrize("chunk", [64, 256, 1024, 4096])
 @pytest.mark.parametrize("P", [16, 128, 4])
 def test_prefill_context_split_schedules(pa, oracle, chunk, P):
@@ -621,7 +637,7 @@ def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
 
 @pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
 @pytest.mark.parametrize("causal", [True, False])
-@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("d", [128, 64, 256])
 def test_prefill_with_mask_and_score_hooks(pa, oracle, case, causal, d):
     lens = [400, 64, 700, 33, 0]
     q_lens = [400, 10, 130, 1, 0]
