@@ -20,7 +20,6 @@ bool decode_mfma_supported(const AttnArgs& a)
     if (a.dtype != PA_DTYPE_BF16 && a.dtype != PA_DTYPE_F16) return false;
     const int32_t d = a.cache.head_dim;
     if (d != 64 && d != 128 && d != 256) return false;
-    if (a.has_mods && a.mods.doc_ids) return false;    // document masks: portable kernel
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
     if (G > 16) return false;
     if (a.cache.num_kv_heads > 65535 * 8) return false;

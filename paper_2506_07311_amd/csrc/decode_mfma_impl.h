@@ -59,6 +59,7 @@ template <typename GE>
 struct Tile {
     uint4 k[GE::kBlocks][GE::kKS];        // [16-key block][32-element step of head_dim]: lane%16 = key, lane/16 = 8-element piece
     uint4 v[GE::kPasses][4 * GE::kBlocks];   // 4 keys per block x 8 head_dim columns per lane and pass
+    int32_t doc[GE::kBlocks][4];             // document ids of the lane's 4 score keys per block (document masks only)
 };
 
 // Everything a wave needs to address its KV head's rows.
@@ -66,6 +67,7 @@ struct Addr {
     const char* kbase;          // pool base + kv head offset
     const char* vbase;
     const int32_t* table;       // block-table row of the sequence
+    const int32_t* doc;         // document-id row of the sequence (document masks only)
     int64_t page_bytes;
     int64_t token_bytes;
     int32_t log2_page;
@@ -77,10 +79,16 @@ struct Addr {
 
 // Issue the 16 loads of the tile that starts at key `t0`.  Keys at or beyond `c1` are clamped to the last
 // valid key, so every address is a live slot; their scores are masked by the caller.
-template <bool UNIFORM, typename GE>
+template <bool UNIFORM, typename M, typename GE>
 __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0, int32_t c1)
 {
     constexpr int kTileKeys = GE::kTileKeys;
+    if (M::kDoc) {   // ids of the keys whose scores this lane will hold (clamped like the rows themselves)
+#pragma unroll
+        for (int mt = 0; mt < GE::kBlocks; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t.doc[mt][i] = a.doc[min(t0 + 16 * mt + 4 * a.quad + i, c1 - 1)];
+    }
     if constexpr (UNIFORM) {
         if (t0 + kTileKeys <= c1) {   // full tile: 16-key blocks, each inside one page
 #pragma unroll
@@ -137,6 +145,7 @@ struct RowMods {
     float cap_in;       // score: scale / softcap, 0 without a cap
     float cap_out;      // score: softcap * log2(e)
     float scale;        // score: plain scale (the unmodified path folds log2(e) into it)
+    int32_t doc;        // document mask: the row's own document id
 };
 
 // lim = first key this lane's row may not see (the segment end, or less under a per-row causal bound);
@@ -182,14 +191,16 @@ __device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, c
             }
             if (partial && key >= lim) x = -INFINITY;   // mask by selection
             if (below && key < rm.lo) x = -INFINITY;
+            if (M::kDoc && t.doc[mt][i] != rm.doc) x = -INFINITY;
             s[mt][i] = x;
             tmax = fmaxf(tmax, x);
         }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    // decode: finite, every tile holds at least one valid key; a row under a causal bound may have seen none yet
+    // decode: finite, every tile holds at least one valid key; a row under a causal bound or a document mask may
+    // have seen none yet
     const float m_new = fmaxf(st.m, tmax);
-    const float m_use = (RAGGED && m_new == -INFINITY) ? 0.f : m_new;
+    const float m_use = ((RAGGED || M::kDoc) && m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
     float psum = 0.f;
 #pragma unroll
@@ -324,8 +335,7 @@ __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens
 // RAGGED: launched from the prefill entry point for the sequences with few queries (q_len * G <= 16): the 16
 // columns are (query, head) pairs, column = query * G + head, each with its own causal bound; q / out / lse rows
 // come from cu_q_lens; partials are 16 rows per KV head.
-// E: element traits (bf16 / fp16).  M: compile-time policy of the mask / score hooks (document masks are not
-// taken here).
+// E: element traits (bf16 / fp16).  M: compile-time policy of the mask / score hooks.
 template <int NW, bool UNIFORM, bool RAGGED, typename E, typename M, typename GE>
 __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
@@ -377,6 +387,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     before = __builtin_amdgcn_readfirstlane(before);
 
     Addr a;
+    a.doc = nullptr;
     a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
     a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
     a.page_bytes = cache.page_stride * 2;
@@ -419,6 +430,11 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         rm.cap_in = 0.f;
         rm.cap_out = 0.f;
         rm.scale = scale;
+        rm.doc = 0;
+        if (M::kDoc) {
+            a.doc = mods.doc_ids + (int64_t)s * mods.doc_stride;
+            rm.doc = a.doc[max(pos, 0)];
+        }
         if (M::kWindow && window > 0) {
             rm.lo = pos - window + 1;                      // |j - pos| < window, lower side
             rm.lo_until = len - window;                    // the last row's lower bound is the largest
@@ -455,13 +471,13 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 
         // two tiles in registers: while one is computed the other's loads are in flight
         Tile<GE> ta, tb;
-        load_tile<UNIFORM>(ta, a, c0, c1);
+        load_tile<UNIFORM, M>(ta, a, c0, c1);
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
-            if (t1 < c1) load_tile<UNIFORM>(tb, a, t1, c1);
+            if (t1 < c1) load_tile<UNIFORM, M>(tb, a, t1, c1);
             compute_tile<RAGGED, E, M, GE>(st, ta, qf, sc, t0, lim, mask_from, quad, rm);
             if (t1 >= c1) break;
-            if (t1 + kTileKeys < c1) load_tile<UNIFORM>(ta, a, t1 + kTileKeys, c1);
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M>(ta, a, t1 + kTileKeys, c1);
             compute_tile<RAGGED, E, M, GE>(st, tb, qf, sc, t1, lim, mask_from, quad, rm);
         }
 
@@ -471,9 +487,10 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         const bool whole = t_begin == 0 && t_end == nt;    // the sequence's stream lies inside this workgroup
         // D = 64: accumulator rows 8-15 (lanes of quads 2 and 3) repeat rows 0-7 and are not stored
         if (r16 < rows && (kD != 64 || quad < 2)) {
-            // l == 0: a row whose causal bound lies before this segment (RAGGED only)
-            const float inv = (!RAGGED || l > 0.f) ? 1.f / l : 0.f;
-            const float lse_nat = (!RAGGED || l > 0.f) ? (st.m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+            // l == 0: a row whose causal bound lies before this segment, or none of whose document's keys lie in it
+            constexpr bool kMayBeEmpty = RAGGED || M::kDoc;
+            const float inv = (!kMayBeEmpty || l > 0.f) ? 1.f / l : 0.f;
+            const float lse_nat = (!kMayBeEmpty || l > 0.f) ? (st.m + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
             if (whole) {
 #pragma unroll
                 for (int c = 0; c < GE::kPasses; ++c)
@@ -549,11 +566,14 @@ void launch_decode_mfma_dim(const AttnArgs& a, hipStream_t stream)
 {
     typedef Mods<true, true, false> WindowScore;
     typedef Geo<D> GE;
+    const bool docs = a.has_mods && a.mods.doc_ids;
     if (a.dtype == PA_DTYPE_BF16) {
-        if (a.has_mods) launch_em<ElemBf16, WindowScore, GE>(a, stream);
+        if (docs) launch_em<ElemBf16, AllMods, GE>(a, stream);
+        else if (a.has_mods) launch_em<ElemBf16, WindowScore, GE>(a, stream);
         else launch_em<ElemBf16, NoMods, GE>(a, stream);
     } else {
-        if (a.has_mods) launch_em<ElemF16, WindowScore, GE>(a, stream);
+        if (docs) launch_em<ElemF16, AllMods, GE>(a, stream);
+        else if (a.has_mods) launch_em<ElemF16, WindowScore, GE>(a, stream);
         else launch_em<ElemF16, NoMods, GE>(a, stream);
     }
 }

@@ -18,7 +18,6 @@ bool prefill_mfma_supported(const AttnArgs& a)
     const int32_t d = a.cache.head_dim;
     if (d != 128 && d != 64 && !(d == 256 && a.cache.page_size >= 16)) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
-    if (a.has_mods && a.mods.doc_ids) return false;   // document masks: portable kernel
     return true;
 }
 

@@ -122,14 +122,21 @@ struct RowMods {
     float slope2;       // score: bias slope * log2(e)
     float cap_in;       // score: scale / softcap, 0 without a cap
     float cap_out;      // score: softcap * log2(e)
+    int32_t doc;        // document mask: the row's own document id
 };
 
 // M: compile-time policy of the hooks.  With score hooks the scores are first rewritten in place as
 // log2(e) * (cap(scale * s) + slope * (key - pos)) and the rest runs with a unit scale.
 template <bool MASK, bool FIRST, typename M, int T>
 __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T], float& m_ref, float& l, float sc,
-                                             int32_t key0, int32_t nk, const RowMods& rm)
+                                             int32_t key0, int32_t nk, const RowMods& rm, const int32_t* docs)
 {
+    // document mask: ids of this lane's 16 keys (4 groups of 4 consecutive keys, 8 apart) from the tile's ids in LDS
+    int4 ids[4];
+    if (M::kDoc) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) ids[a] = *reinterpret_cast<const int4*>(docs + 8 * a);
+    }
     if (M::kScore) {
         const float b0 = rm.slope2 * (float)(key0 - rm.pos);
 #pragma unroll
@@ -151,6 +158,11 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
     for (int r = 0; r < 16; ++r) {
         if (MASK && key0 + 8 * (r / 4) + (r % 4) >= nk) s[r] = -INFINITY;   // mask by selection
         if (below && key0 + 8 * (r / 4) + (r % 4) < rm.lo) s[r] = -INFINITY;
+        if (M::kDoc) {
+            const int4 g = ids[r / 4];
+            const int32_t id = (r % 4) == 0 ? g.x : (r % 4) == 1 ? g.y : (r % 4) == 2 ? g.z : g.w;
+            if (id != rm.doc) s[r] = -INFINITY;
+        }
         tmax = fmaxf(tmax, s[r]);
     }
     float psum = 0.f;
@@ -280,21 +292,21 @@ __device__ __forceinline__ void half_scores(f32x16& s, const char* kbuf, int hal
 template <bool PRECISE, bool MASK, typename E, typename M, int T>
 __device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx)[2 * T], const uint32_t (&vx)[2 * T],
                                             const uint4 (&qf)[2 * T], f32x16 (&o)[T], float& m, float& l, float sc,
-                                            int32_t key0, int32_t nk, const RowMods& rm)
+                                            int32_t key0, int32_t nk, const RowMods& rm, const int32_t* docs)
 {
     f32x16 s0, s1, p;
     half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
     half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
-    half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm);
+    half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm, docs);
     constexpr int TB = kBN * (T > 4 ? 512 : 256);
     half_pv<PRECISE, E, T>(o, p, buf + TB, 0, vx);
-    half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm);
+    half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm, docs + 32);
     half_pv<PRECISE, E, T>(o, p, buf + TB, 1, vx);
 }
 
 template <bool PRECISE, bool UNIFORM, typename E, typename M, int D>
 __device__ __forceinline__ void prefill_body(
-    char* buf0, char* buf1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    char* buf0, char* buf1, int32_t* docs0, int32_t* docs1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
     float scale, int32_t causal, const PrefillPlan& plan)
@@ -343,8 +355,9 @@ __device__ __forceinline__ void prefill_body(
     // "Few" is relative to the sequence: a row's rounding error falls as 1/sqrt(keys) while the scale its
     // sequence's outputs are judged on falls with the sequence length, so the bound grows as len / 8 (the rows
     // below it see at most 1/64 of a causal sequence's tile work).
+    // (a document mask can leave a row a handful of keys out of any context)
     const bool few_keys = nk_wg - k_lo <= max(kPreciseKeys, len >> 3) ||
-                          (M::kScore && plan.mods.alibi_slopes != nullptr);
+                          (M::kScore && plan.mods.alibi_slopes != nullptr) || (M::kDoc && plan.mods.doc_ids != nullptr);
     if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
     // reads only the chunks that hold keys of a row)
@@ -390,6 +403,12 @@ __device__ __forceinline__ void prefill_body(
     rm.slope2 = 0.f;
     rm.cap_in = 0.f;
     rm.cap_out = 0.f;
+    rm.doc = 0;
+    const int32_t* doc_row = nullptr;
+    if (M::kDoc) {
+        doc_row = plan.mods.doc_ids + (int64_t)s * plan.mods.doc_stride;
+        rm.doc = doc_row[max(pos, 0)];
+    }
     int32_t lo_wave = 0;                                     // tiles that end at or before it hold nothing for the wave
     if (window > 0) {
         rm.lo = pos - window + 1;
@@ -451,11 +470,48 @@ __device__ __forceinline__ void prefill_body(
         else fetch_tile<UNIFORM>(buf + wrow, pg, cache, t0, frow, last_key, lane_off);
     };
 
+    // Document masks: wave 0 brings the 64 ids of the next tile (one per lane) and stores them next to the tile
+    // buffer before the barrier that publishes the tile, together with their minimum and maximum (slots 64, 65).
+    // A wave skips a tile whose id range misses the id range of its rows: always right, and it pays when documents
+    // are contiguous runs of positions, as in packed batches.  (The tile is still fetched: deciding that ahead of
+    // the fetch costs a dependent global load per tile, which was measured to cost more than the fetches it saves.)
+    const bool doc_lane = M::kDoc && wave == 0;
+    int32_t doc_next = 0;
+    int32_t row_doc_min = rm.doc, row_doc_max = rm.doc;
+    // minimum and maximum over the wave with data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside each row
+    // of 16 lanes, then lane 15 of a row into the next row, lane 31 into the upper half; lane 63 holds the result
+    auto wave_range = [&](int32_t v, int32_t& mn, int32_t& mx) {
+        mn = v;
+        mx = v;
+#define PA_RANGE_STEP(CTRL, ROWS)                                                                   \
+        mn = min(mn, __builtin_amdgcn_update_dpp(mn, mn, CTRL, ROWS, 0xF, false));                  \
+        mx = max(mx, __builtin_amdgcn_update_dpp(mx, mx, CTRL, ROWS, 0xF, false));
+        PA_RANGE_STEP(0x111, 0xF) PA_RANGE_STEP(0x112, 0xF) PA_RANGE_STEP(0x114, 0xF) PA_RANGE_STEP(0x118, 0xF)
+        PA_RANGE_STEP(0x142, 0xA) PA_RANGE_STEP(0x143, 0xC)
+#undef PA_RANGE_STEP
+        mn = __builtin_amdgcn_readlane(mn, 63);
+        mx = __builtin_amdgcn_readlane(mx, 63);
+    };
+    auto put_docs = [&](int32_t* dst, int32_t v) {           // wave 0: the tile's ids and their range
+        int32_t mn, mx;
+        wave_range(v, mn, mx);
+        dst[lane] = v;
+        if (lane < 2) dst[kBN + lane] = lane ? mx : mn;
+    };
+    auto docs_overlap = [&](const int32_t* d) -> bool {      // wave-uniform
+        if (!M::kDoc) return true;
+        const int32_t mn = __builtin_amdgcn_readfirstlane(d[kBN]);
+        const int32_t mx = __builtin_amdgcn_readfirstlane(d[kBN + 1]);
+        return mx >= row_doc_min && mn <= row_doc_max;
+    };
+    auto tile_ids = [&](int32_t t0) -> int32_t { return doc_row[min(t0 + lane, last_key)]; };
+    if (M::kDoc) wave_range(rm.doc, row_doc_min, row_doc_max);
     PageIds ids;
     const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
     if (n_tiles > 0) {
         load_ids<UNIFORM>(ids, cache, table, k_begin, frow, last_key);
         fetch(buf0, ids, k_begin);
+        if (doc_lane) put_docs(docs0, tile_ids(k_begin));
         if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, k_begin + kBN, frow, last_key);
         __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
     }
@@ -466,27 +522,31 @@ __device__ __forceinline__ void prefill_body(
         const int32_t t0 = k_begin + t * kBN;
         if (t + 1 < n_tiles) {
             fetch(buf1, ids, t0 + kBN);
+            if (doc_lane) doc_next = tile_ids(t0 + kBN);
             if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
         }
-        if (t0 < nk_wave && t0 + kBN > lo_wave) {            // wave-uniform: else nothing for this wave here
+        if (t0 < nk_wave && t0 + kBN > lo_wave && docs_overlap(docs0)) {   // wave-uniform: else nothing for this wave here
             if (t0 + kBN > nk_wave_min)                      // wave-uniform: some score of this tile is masked
-                attend_tile<PRECISE, true, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
+                attend_tile<PRECISE, true, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm, docs0 + 4 * hh);
             else
-                attend_tile<PRECISE, false, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm);
+                attend_tile<PRECISE, false, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm, docs0 + 4 * hh);
         }
+        if (doc_lane && t + 1 < n_tiles) put_docs(docs1, doc_next);
         __syncthreads();
         if (t + 1 >= n_tiles) break;
         const int32_t t1 = t0 + kBN;
         if (t + 2 < n_tiles) {
             fetch(buf0, ids, t1 + kBN);
+            if (doc_lane) doc_next = tile_ids(t1 + kBN);
             if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
         }
-        if (t1 < nk_wave && t1 + kBN > lo_wave) {
+        if (t1 < nk_wave && t1 + kBN > lo_wave && docs_overlap(docs1)) {
             if (t1 + kBN > nk_wave_min)
-                attend_tile<PRECISE, true, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
+                attend_tile<PRECISE, true, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm, docs1 + 4 * hh);
             else
-                attend_tile<PRECISE, false, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm);
+                attend_tile<PRECISE, false, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm, docs1 + 4 * hh);
         }
+        if (doc_lane && t + 2 < n_tiles) put_docs(docs0, doc_next);
         __syncthreads();
     }
 
@@ -536,9 +596,11 @@ __global__ __launch_bounds__(kThreads, D > 128 ? 1 : 2) void paged_prefill_mfma_
 {
     __shared__ __attribute__((aligned(1024))) char buf0[RowGeo<D>::kBufB];
     __shared__ __attribute__((aligned(1024))) char buf1[RowGeo<D>::kBufB];
-    prefill_body<false, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    __shared__ __attribute__((aligned(16))) int32_t docs0[kBN + 4];
+    __shared__ __attribute__((aligned(16))) int32_t docs1[kBN + 4];
+    prefill_body<false, UNIFORM, E, M, D>(buf0, buf1, docs0, docs1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                  num_q_heads, max_blocks, scale, causal, plan);
-    prefill_body<true, UNIFORM, E, M, D>(buf0, buf1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
+    prefill_body<true, UNIFORM, E, M, D>(buf0, buf1, docs0, docs1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
                                 num_q_heads, max_blocks, scale, causal, plan);
 }
 
@@ -555,7 +617,14 @@ pa_status launch_prefill_mfma_dim(const AttnArgs& a, const PrefillPlan& plan, in
     if (D > 128 && !uniform) return PA_ERR_UNSUPPORTED;   // 512-byte rows: two rows per load must share a page
     typedef Mods<true, true, false> WindowScore;
     auto kern = paged_prefill_mfma_kernel<true, ElemBf16, NoMods, D>;
-    if (a.dtype == PA_DTYPE_BF16) {
+    if (a.has_mods && a.mods.doc_ids) {
+        if (a.dtype == PA_DTYPE_BF16)
+            kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, AllMods, D>
+                           : paged_prefill_mfma_kernel<false, ElemBf16, AllMods, D>;
+        else
+            kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, AllMods, D>
+                           : paged_prefill_mfma_kernel<false, ElemF16, AllMods, D>;
+    } else if (a.dtype == PA_DTYPE_BF16) {
         if (a.has_mods) kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, WindowScore, D>
                                        : paged_prefill_mfma_kernel<false, ElemBf16, WindowScore, D>;
         else if (!uniform) kern = paged_prefill_mfma_kernel<false, ElemBf16, NoMods, D>;
