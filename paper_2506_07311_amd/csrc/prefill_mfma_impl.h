@@ -108,12 +108,13 @@ __device__ __forceinline__ uint4 lds_frag_tr(const char* lo, const char* hi)
 
 // Online-softmax update with the 32 keys of one half tile.  s holds raw scores on entry; the weights are
 // returned in p.  The running statistic is a REFERENCE exponent m_ref (log2 domain) that may trail the true
-// running max by up to kJump: weights are exp2(score - m_ref) <= 2^kJump, which fp32 sums and bf16 operands
-// carry without loss, and out = O / l does not depend on the reference.  The weights therefore do not wait for
-// the max of the half: they are computed speculatively with the reference as it stands, and only when some
-// query's max jumps more than kJump above its reference (always on its first keys, rarely later) is the
-// reference raised, O and l rescaled and the half's weights recomputed -- a wave-uniform slow path that keeps
-// the common path free of branches between the score and the value products.
+// running max: weights are exp2(score - m_ref), and as long as a lane's 16 weights sum to at most kWeightSumMax
+// every one of them is a number that fp32 sums and 16-bit operands carry without loss, and out = O / l does not
+// depend on the reference.  So the common path takes no maximum at all: the weights are computed with the
+// reference as it stands, and only when some lane's sum exceeds the bound (or is not a number: a fresh reference
+// is -inf) -- always on a query's first keys, rarely later -- is the true maximum taken, the reference raised, O
+// and l rescaled and the half's weights recomputed: a wave-uniform slow path that keeps the common path free of
+// branches between the score and the value products.
 // What the mask / score hooks need per row (this lane's).  Unused without their hook.
 struct RowMods {
     int32_t lo;         // window: first visible key of this row
@@ -153,7 +154,6 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
         sc = 1.f;
     }
     const bool below = M::kWindow && key0 < rm.lo_until;      // wave-uniform up to the lane's 4-key offset
-    float tmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         if (MASK && key0 + 8 * (r / 4) + (r % 4) >= nk) s[r] = -INFINITY;   // mask by selection
@@ -163,7 +163,6 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
             const int32_t id = (r % 4) == 0 ? g.x : (r % 4) == 1 ? g.y : (r % 4) == 2 ? g.z : g.w;
             if (id != rm.doc) s[r] = -INFINITY;
         }
-        tmax = fmaxf(tmax, s[r]);
     }
     float psum = 0.f;
 #pragma unroll
@@ -192,9 +191,12 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
             __builtin_amdgcn_sched_group_barrier(0x002, 72 / KS, 0);
         }
     }
-    const float top = pair_max(tmax) * sc;                    // sc > 0: scaling commutes with the max
-    const bool jump = !(top - m_ref <= kJump);                // also true for the NaN / inf of a fresh reference
+    const bool jump = !(psum <= kWeightSumMax);               // also true for the NaN / inf of a fresh reference
     if (__any(jump)) {
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
+        const float top = pair_max(tmax) * sc;                // sc > 0: scaling commutes with the max
         const float m_new = fmaxf(m_ref, top);
         const float m_use = m_new == -INFINITY ? 0.f : m_new; // a query with no allowed key so far
         const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);

@@ -99,10 +99,9 @@ __device__ __forceinline__ float pair_max(float x)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// Online softmax keeps a REFERENCE exponent (log2 domain) that may trail the true running max by up to kJump:
-// weights are exp2(score - reference) <= 2^kJump, which fp32 sums and 16-bit operands carry without loss, and
-// out = O / l does not depend on the reference.
-constexpr float kJump = 8.f;
+// Online softmax keeps a REFERENCE exponent (log2 domain) that may trail the true running max; the reference is
+// raised when the 16 weights a lane computes for a half tile sum to more than this (fp16 operands end at 65504).
+constexpr float kWeightSumMax = 16384.f;
 
 }  // namespace prefill
 }  // namespace pa
