@@ -292,7 +292,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         // host only skips a launch that cannot find work.
         const int32_t G = num_q_heads / cache->num_kv_heads;
         const bool uniform_q = (int64_t)batch * max_q_len == total_q;      // every sequence has max_q_len queries
-        const bool may_have_small = !g_opt.no_small_q_route && decode_mfma_supported(a) &&
+        const bool may_have_small = !g_opt.no_small_q_route && decode_mfma_supported(a) && G <= 16 &&
                                     !(uniform_q && (int64_t)max_q_len * G > 16);
         const bool may_have_large = (int64_t)max_q_len * G > 16 || !may_have_small;
         char* p = reinterpret_cast<char*>(workspace);

@@ -21,7 +21,7 @@ bool decode_mfma_supported(const AttnArgs& a)
     const int32_t d = a.cache.head_dim;
     if (d != 64 && d != 128 && d != 256) return false;
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
-    if (G > 16) return false;
+    if (G > 16 * 64) return false;                     // one grid slice per 16 heads of a group
     if (a.cache.num_kv_heads > 65535 * 8) return false;
     // per-lane byte offsets inside a 16-key block are kept in 32 bits
     if (a.cache.token_stride * 2 * 16 + a.cache.head_stride * 2 > 0x7fffffffLL) return false;

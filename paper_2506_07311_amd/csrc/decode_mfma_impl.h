@@ -1,5 +1,5 @@
-// Split-KV paged decode for bf16 / fp16 pools with head_dim D = 64, 128 or 256 on gfx950 (CDNA4), group size
-// G = Hq/Hkv <= 16.  Internal header: the kernel templates; one translation unit per head_dim instantiates them.
+// Split-KV paged decode for bf16 / fp16 pools with head_dim D = 64, 128 or 256 on gfx950 (CDNA4); 16 query heads
+// of a KV head per wave (larger groups take ceil(G/16) workgroups per tile range, which re-read K/V through L2).  Internal header: the kernel templates; one translation unit per head_dim instantiates them.
 // (The description below is written for D = 128; what changes with D is listed at Geo.)
 //
 // Decode is bound by streaming every resident K/V byte once from HBM, so the design is about memory:
@@ -408,7 +408,9 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         const int32_t t_begin = g - before;
         const int32_t t_end = min(nt, g_end - before);
         // this lane's column: query qi of the sequence's q_len, head h (valid if r16 < rows)
-        int32_t rows = G, qi = 0, q_row = s, q_len = 1;
+        // (group sizes above 16: blockIdx.z picks 16 of the group's heads; these workgroups stream the same K/V)
+        const int32_t h0 = RAGGED ? 0 : 16 * (int32_t)blockIdx.z;
+        int32_t rows = min(G - h0, 16), qi = 0, q_row = s, q_len = 1;
         if (RAGGED) {
             const int32_t q_begin = cu_q_lens[s];
             q_len = cu_q_lens[s + 1] - q_begin;
@@ -442,14 +444,14 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         }
         if (M::kScore) {
             if (mods.alibi_slopes && r16 < rows)
-                rm.slope2 = mods.alibi_slopes[kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16)] * kLog2e;
+                rm.slope2 = mods.alibi_slopes[kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : h0 + r16)] * kLog2e;
             if (mods.softcap > 0.f) {
                 rm.cap_in = scale / mods.softcap;
                 rm.cap_out = mods.softcap * kLog2e;
             }
         }
         const int32_t mask_from = RAGGED ? c1 - 16 : c1;   // q_len <= 16: no bound lies further below the end
-        const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : r16);
+        const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : h0 + min(r16, rows - 1));
         const int64_t o_idx = (int64_t)q_row * num_q_heads + h;
         a.table = block_table + (int64_t)s * max_blocks;
 
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
                 if (quad == 0) part_lse[p_idx] = lse_nat;
             }
         }
-        if (wave == 0 && lane == 0 && blockIdx.y == 0) {
+        if (wave == 0 && lane == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
             if (t_begin == 0) seg_first[s] = whole ? -1 : w;
             if (t_end == nt) seg_last[s] = w;
         }
@@ -534,7 +536,8 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 template <int NW, typename E, typename M, typename GE>
 void launch_nw(const AttnArgs& a, hipStream_t stream)
 {
-    const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), 1);
+    const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
+    const dim3 grid((uint32_t)a.num_wgs, (uint32_t)(a.cache.num_kv_heads / NW), a.cu_q_lens ? 1u : (uint32_t)((G + 15) / 16));
     const bool uniform = a.cache.page_size >= 16;
     auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true, E, M, GE>
                                        : paged_decode_mfma_kernel<NW, false, true, E, M, GE>)

@@ -113,7 +113,8 @@ def test_decode_ragged_lengths_and_page_sizes(pa, oracle, dtype, d, P):
     parity.check_step(pa, oracle, w, f"ragged decode P={P} d={d} {dtype}")
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (8, 8), (16, 8), (32, 8), (64, 8), (16, 1), (24, 8), (40, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (8, 8), (16, 8), (32, 8), (64, 8), (16, 1), (24, 8), (40, 2), (32, 1),
+                                    (71, 1), (96, 2)])
 def test_decode_group_sizes(pa, oracle, Hq, Hkv):
     w = W.make_workload("t", seq_lens=[300, 77, 1025], num_q_heads=Hq, num_kv_heads=Hkv, head_dim=128,
                         page_size=16, dtype=torch.bfloat16, seed=31, device=DEV)
