@@ -62,9 +62,10 @@ def test_append_nothing_and_gather_empty(pa):
     assert torch.equal(before, w.k_cache) and gk.numel() == 0
 
 
-def test_head_major_pool_through_strides(pa, oracle):
+@pytest.mark.parametrize("d", [128, 64, 256])
+def test_head_major_pool_through_strides(pa, oracle, d):
     """A [NP, Hkv, P, d] pool described by strides holds the same logical cache."""
-    w = W.make_workload("t", seq_lens=[50, 17], num_q_heads=8, num_kv_heads=4, head_dim=128, page_size=16,
+    w = W.make_workload("t", seq_lens=[50, 17], num_q_heads=8, num_kv_heads=4, head_dim=d, page_size=16,
                         dtype=torch.bfloat16, seed=22, device=DEV)
     _, _, o_ref, _ = parity.oracle_step(oracle, w)
     kh = w.k_cache.permute(0, 2, 1, 3).contiguous()
@@ -479,8 +480,9 @@ def test_extreme_and_negative_scales(pa, oracle, scale):
     parity.check_step(pa, oracle, w, f"decode scale={scale}", tol=tol)
 
 
-def test_prefill_head_major_pool(pa, oracle):
-    w = W.make_workload("t", seq_lens=[200, 77], q_lens=[200, 77], num_q_heads=8, num_kv_heads=4, head_dim=128,
+@pytest.mark.parametrize("d", [128, 64, 256])
+def test_prefill_head_major_pool(pa, oracle, d):
+    w = W.make_workload("t", seq_lens=[200, 77], q_lens=[200, 77], num_q_heads=8, num_kv_heads=4, head_dim=d,
                         page_size=16, dtype=torch.bfloat16, causal=True, seed=73, device=DEV)
     _, _, o_ref, _ = parity.oracle_step(oracle, w)
     kh = w.k_cache.permute(0, 2, 1, 3).contiguous()
@@ -634,6 +636,16 @@ def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
     w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16, dtype=dtype,
                         seed=70, device=DEV)
     parity.check_step(pa, oracle, w, f"decode hooks {case}", mods=build_mods(case, 8, lens))
+
+
+@pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
+def test_decode_hooks_with_a_group_larger_than_one_slice(pa, oracle, case):
+    """20 query heads per KV head: two grid slices of the decode kernel, the second with 4 live columns; the
+    per-head slopes and the document ids must follow the slice's head offset."""
+    lens = [700, 64, 1300, 33, 1]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=40, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=72, device=DEV)
+    parity.check_step(pa, oracle, w, f"decode hooks G=20 {case}", mods=build_mods(case, 40, lens))
 
 
 @pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
