@@ -305,15 +305,21 @@ def main():
         binding.pa_profile_enable(True)
         time_steps(torch, step, args.steps, 0)
         binding.pa_profile_enable(False)
+        # (prepared calls carry the stream they were prepared on: the captured step is prepared on the capture stream)
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
-            step()
+            captured = make_step(*pools[0])
+            captured()
             side.synchronize()
             with torch.cuda.graph(graph, stream=side):
-                step()
+                captured()
+        torch.cuda.synchronize()
+        out.zero_()
         torch.cuda.synchronize()
         sec = time_steps(torch, graph.replay, args.steps, 2)
+        if not bool(out.any().item()):
+            raise SystemExit("bench.py: the captured graph did not run the step (output untouched)")
     else:
         # The per-kernel events are recorded in the timed region itself; only when a step is so short that the
         # events' own cost shows (hundreds of microseconds or less) the step time comes from a second, plain pass
