@@ -1,10 +1,12 @@
 // Split-KV paged decode for bf16 / fp16 pools with head_dim D = 64, 128 or 256 on gfx950 (CDNA4); 16 query heads
-// of a KV head per wave (larger groups take ceil(G/16) workgroups per tile range, which re-read K/V through L2).  Internal header: the kernel templates; one translation unit per head_dim instantiates them.
+// of a KV head per wave (larger groups take ceil(G/16) workgroups per tile range, which re-read K/V through L2).
+// Internal header: the kernel templates; one translation unit per head_dim instantiates them.
 // (The description below is written for D = 128; what changes with D is listed at Geo.)
 //
 // Decode is bound by streaming every resident K/V byte once from HBM, so the design is about memory:
 //   * one wave owns one KV head of one (sequence, context chunk); the NW waves of a workgroup own NW
-//     adjacent KV heads, so that together they read whole contiguous token rows of a page;
+//     adjacent KV heads and meet at a barrier before every tile load, so that together, and at the same time,
+//     they read whole contiguous token rows of a page;
 //   * each wave walks its chunk in tiles of 32 keys; every K/V byte is fetched by one 16-byte load per
 //     lane straight into the registers the MFMA reads -- no LDS round trip -- and the next tile's 16
 //     loads (16 KB per wave) are in flight while the current tile is computed;
