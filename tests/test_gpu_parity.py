@@ -659,6 +659,33 @@ def test_prefill_with_mask_and_score_hooks(pa, oracle, case, causal, d):
     parity.check_step(pa, oracle, w, f"prefill hooks {case} causal={causal} d={d}", mods=build_mods(case, 8, lens))
 
 
+@pytest.mark.parametrize("chunk,wgs", [(0, 0), (128, 5), (512, 64)])
+@pytest.mark.parametrize("shuffled", [False, True])
+@pytest.mark.parametrize("d", [128, 256])
+def test_document_masks_with_context_splits_and_tile_skipping(pa, oracle, chunk, wgs, shuffled, d):
+    """Document masks on the matrix-core kernels over many tiles: contiguous documents (waves skip the tiles of other
+    documents) and ids in no order (nothing can be skipped, every tile is masked per key), with the context cut into
+    chunks and the few-query sequences' stream cut between workgroups."""
+    from paper_2506_07311_amd import binding
+    lens = [1300, 700, 2049, 64, 300]
+    q_lens = [1300, 3, 600, 1, 300]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16,
+                        dtype=torch.bfloat16, causal=True, seed=74, device=DEV)
+    ids = doc_ids(lens, 11)
+    if shuffled:
+        rng = np.random.default_rng(12)
+        ids = rng.integers(0, 3, size=ids.shape).astype(np.int32)
+    binding.pa_set_option("prefill_chunk_tokens", chunk)
+    binding.pa_set_option("decode_workgroups", wgs)
+    try:
+        # rows that see one or two keys reach |out| >= 4, where a bf16 output rounds by 1.6e-2
+        parity.check_step(pa, oracle, w, f"docs chunk={chunk} wgs={wgs} shuffled={shuffled} d={d}",
+                          mods={"doc_ids": ids}, tol=(2e-2, 2e-2))
+    finally:
+        binding.pa_set_option("prefill_chunk_tokens", 0)
+        binding.pa_set_option("decode_workgroups", 0)
+
+
 @pytest.mark.parametrize("window", [64, 500, 1025])
 @pytest.mark.parametrize("causal", [True, False])
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
