@@ -159,11 +159,18 @@ int32_t prefill_nsplit_bound(int32_t batch, int32_t num_q_heads, int32_t total_q
     return best;
 }
 
-// Workgroups along the tile stream for the MFMA decode kernel: one per compute unit (per KV-head group), but
-// never so many that a workgroup gets fewer than two 32-key tiles of the longest possible stream.
-int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups)
+// Workgroups along the tile stream for the MFMA decode kernel: one per compute unit and KV-head group, and more when
+// that leaves fewer than four waves per compute unit (a workgroup holds one wave per KV head: few KV heads, as on one
+// shard of a tensor-parallel model, mean small workgroups; `slices` = grid slices of 16 heads for groups above 16) --
+// but never so many that a workgroup gets fewer than two 32-key tiles of the longest possible stream.
+int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups, int32_t num_kv_heads, int32_t slices)
 {
-    int64_t target = g_opt.decode_workgroups > 0 ? g_opt.decode_workgroups : device_cus() / head_groups;
+    int64_t target = g_opt.decode_workgroups;
+    if (target <= 0) {
+        target = device_cus() / head_groups;
+        const int64_t by_waves = 4LL * device_cus() / ((int64_t)num_kv_heads * (slices < 1 ? 1 : slices));
+        if (by_waves > target) target = by_waves;
+    }
     if (target < 1) target = 1;
     const int64_t tiles = (int64_t)batch * ((max_seq_len + 31) / 32);
     int64_t n = tiles / 2;
@@ -266,7 +273,8 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         if (!g_opt.force_generic && decode_mfma_supported(a)) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
-            a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
+            a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads,
+                                        (num_q_heads / cache->num_kv_heads + 15) / 16);
             const size_t parts = (size_t)a.num_wgs + batch;
             char* p = reinterpret_cast<char*>(workspace);
             a.part_o = reinterpret_cast<float*>(p);
@@ -312,7 +320,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
             AttnArgs b = a;
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             b.stream_split = 1;
-            b.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups);
+            b.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads, 1);
             if (b.num_wgs > kSmallRouteMaxWGs) b.num_wgs = kSmallRouteMaxWGs;
             const size_t rows = ((size_t)b.num_wgs + batch) * cache->num_kv_heads * 16;
             b.part_o = reinterpret_cast<float*>(p);
