@@ -58,7 +58,7 @@ WORKLOADS = {
 def measured_traffic(args):
     """The committed counter figures belong to a workload as it is defined; a run that overrides its shape, element
     type or hooks has no measured traffic."""
-    if args.head_dim or args.page_size or args.window or args.alibi or args.dtype == "fp16":
+    if args.head_dim or args.page_size or args.window or args.alibi or args.dtype == "fp16" or args.heads:
         return None
     return MEASURED_TRAFFIC.get(args.workload)
 
@@ -77,6 +77,8 @@ def parse():
     ap.add_argument("--page-size", type=int, default=0, help="override the workload's page size (power of two)")
     ap.add_argument("--head-dim", type=int, default=0, choices=[0, 64, 128, 256],
                     help="override the head_dim of the 16-bit workloads (default 128)")
+    ap.add_argument("--heads", default="", help="HQ,HKV: override the 64 / 8 heads of the decode_b16_ctx131072 workloads "
+                                                "(e.g. 8,1: one shard of an 8-way tensor-parallel model)")
     ap.add_argument("--window", type=int, default=0, help="sliding window in tokens (0 = off)")
     ap.add_argument("--alibi", action="store_true", help="add a linear position bias per head")
     ap.add_argument("--cold", action="store_true",
@@ -234,7 +236,8 @@ def main():
         return run_page_manager(torch, binding, args, P)
     if args.page_size:
         P = args.page_size
-    w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True, head_dim=args.head_dim or None)
+    heads = tuple(int(x) for x in args.heads.split(",")) if args.heads else None
+    w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=True, head_dim=args.head_dim or None, heads=heads)
     if args.dtype == "fp16" and w.dtype == torch.bfloat16:
         # the same N(0,1) draws rounded to fp16 instead of bf16 (NaN poison survives the conversion)
         for name in ("k_cache", "v_cache", "q", "k_new", "v_new"):

@@ -242,10 +242,12 @@ def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> List[int]:
 
 
 def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_size: Optional[int] = None,
-           shrink: int = 1, poison: bool = True, head_dim: Optional[int] = None) -> PagedWorkload:
+           shrink: int = 1, poison: bool = True, head_dim: Optional[int] = None,
+           heads: Optional[tuple] = None) -> PagedWorkload:
     """The five benchmark workloads (1-based), then three jagged-batch workloads (6-8).  ``shrink`` divides context lengths
     (and config 4's length range) for cases the CPU oracle must finish in seconds; ``head_dim`` overrides the 128 of
-    the 16-bit workloads (2-8)."""
+    the 16-bit workloads (2-8); ``heads`` = (query heads, KV heads) overrides workload 5's 64 / 8 (the per-GPU shape
+    of a tensor-parallel shard has few KV heads)."""
     hd = head_dim or 128
     if n == 1:   # single-sequence fp32 decode, 8 of 64 pages used
         L = context or 128
@@ -270,8 +272,9 @@ def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_s
     if n == 5:   # long-context split-KV decode
         L = context or max(64, 131072 // shrink)
         P = page_size or 16
-        return make_workload(f"cfg5_bf16_long_decode_L{L}_P{P}", seq_lens=[L] * 16, num_q_heads=64,
-                             num_kv_heads=8, head_dim=hd, page_size=P, seed=5, device=device, poison=poison)
+        hq, hkv = heads or (64, 8)
+        return make_workload(f"cfg5_bf16_long_decode_L{L}_P{P}", seq_lens=[L] * 16, num_q_heads=hq,
+                             num_kv_heads=hkv, head_dim=hd, page_size=P, seed=5, device=device, poison=poison)
     # Jagged-batch workloads of the prefill entry point (Sec. III-B: ragged queries described by prefix sums).
     if n == 6:   # chat growth: one 1024-token chunk appended behind 31744 cached tokens (1k -> 32k incremental)
         L = context or max(128, 32768 // shrink)
