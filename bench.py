@@ -334,7 +334,8 @@ def main():
         if sec < 500e-6:
             sec = time_steps(torch, step, args.steps, 0, stats_key="step")
             kernel_timing = "events in a pass of their own (same steps); step time from a pass without them"
-    for name in ("paged_kv_append_kernel", "paged_decode_mfma_kernel", "paged_attention_generic_kernel",
+    for name in ("paged_kv_append_kernel", "paged_decode_mfma_kernel", "paged_decode_short_kernel",
+                 "paged_attention_generic_kernel",
                  "paged_attention_merge_kernel", "paged_prefill_mfma_kernel"):
         n, ms = binding.pa_profile_read(name)
         if n:
@@ -403,7 +404,8 @@ def main():
                               "kernel": "paged_prefill_mfma_kernel" if "paged_prefill_mfma_kernel" in kernels
                               else "paged_attention_generic_kernel", "useful_flops": flops}
     else:
-        name = "paged_decode_mfma_kernel" if "paged_decode_mfma_kernel" in kernels else "paged_attention_generic_kernel"
+        name = next(n for n in ("paged_decode_mfma_kernel", "paged_decode_short_kernel",
+                                "paged_attention_generic_kernel") if n in kernels)
         ach = kv_bytes / (kernels[name]["avg_us"] * 1e-6) / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args),

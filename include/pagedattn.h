@@ -205,6 +205,9 @@ const char* pa_status_string(pa_status status);
  *   "prefill_chunk_tokens" context tokens per workgroup of the MFMA prefill kernel (0 = heuristic: no split
  *                          unless the call has too few query rows to fill the machine); size the workspace
  *                          AFTER setting it
+ *   "decode_short"         the one-launch decode kernel for short contexts (a workgroup per sequence and KV head,
+ *                          no workspace, no merge launch): 0 = taken while the step is small enough for it to
+ *                          pay (the default), 1 = whenever it supports the call, -1 = never
  *   "no_small_q_route"     1 = the prefill entry point keeps sequences with few queries (q_len * G <= 16) on
  *                          the prefill kernel instead of handing them to the decode kernel
  *   "force_generic"        1 = always take the portable VALU kernels

@@ -18,6 +18,7 @@ struct Options {
     int64_t force_generic = 0;
     int64_t prefill_chunk_tokens = 0;
     int64_t no_small_q_route = 0;
+    int64_t decode_short = 0;      // 0 = heuristic, 1 = whenever the one-launch kernel supports the call, -1 = never
 } g_opt;
 
 // Compute units of the current device (the tile-stream decode launches one workgroup per CU by default).
@@ -180,6 +181,23 @@ int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups,
     return (int32_t)n;
 }
 
+// One launch instead of tile stream + merge: pays while a step is bound by launches and memory round trips.  A
+// workgroup of the one-launch kernel streams its (sequence, KV head) at about 55 GB/s, so its time is about
+// 4 us + 9 us per 512 KB, against a floor of 12-16 us for tile stream + merge: measured on 1..256 sequences of
+// 128..2048 tokens, it wins up to 1024 tokens (512 at head_dim 256: rows twice as long) as long as its grid is
+// at most two workgroups per compute unit; beyond that the tile stream's whole-row reads and equal split use the
+// memory system better.
+constexpr int64_t kShortMaxRowBytes = 1024 * 512;   // context tokens x bytes of a K row and a V row (>= 512)
+constexpr int64_t kShortMaxWGsPerCU = 2;
+
+bool short_decode_pays(const AttnArgs& a)
+{
+    if (g_opt.decode_workgroups > 0) return false;     // the caller shapes the tile stream: keep it
+    const int64_t row_bytes = 4LL * (a.cache.head_dim > 128 ? a.cache.head_dim : 128);
+    const int64_t wgs = (int64_t)a.batch * a.cache.num_kv_heads * ((a.num_q_heads / a.cache.num_kv_heads + 15) / 16);
+    return a.max_seq_len * row_bytes <= kShortMaxRowBytes && wgs <= kShortMaxWGsPerCU * device_cus();
+}
+
 size_t stream_workspace_bytes(int32_t batch, int32_t hq, int32_t d, int32_t wgs)
 {
     const size_t parts = (size_t)wgs + batch;
@@ -270,6 +288,9 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     if (decode) {
+        if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a) &&
+            (g_opt.decode_short > 0 || short_decode_pays(a)))
+            return launch_decode_short(a, s);
         if (!g_opt.force_generic && decode_mfma_supported(a)) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
@@ -511,6 +532,11 @@ pa_status pa_set_option(const char* name, int64_t value)
     if (!strcmp(name, "no_small_q_route")) {
         if (value != 0 && value != 1) return PA_ERR_INVALID_ARG;
         g_opt.no_small_q_route = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "decode_short")) {
+        if (value < -1 || value > 1) return PA_ERR_INVALID_ARG;
+        g_opt.decode_short = value;
         return PA_OK;
     }
     if (!strcmp(name, "force_generic")) {

@@ -143,6 +143,10 @@ pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream);
 bool decode_mfma_supported(const AttnArgs& a);
 int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads, int32_t head_dim);
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
+// The same tiles in one launch for short contexts: a workgroup per (sequence, KV head), its waves split the context
+// and merge through LDS; no workspace.
+bool decode_short_supported(const AttnArgs& a);
+pa_status launch_decode_short(const AttnArgs& a, hipStream_t stream);
 // MFMA prefill kernel: bf16, head_dim 128.
 bool prefill_mfma_supported(const AttnArgs& a);
 int32_t prefill_mfma_log2_pack(int32_t num_q_heads, int32_t num_kv_heads);

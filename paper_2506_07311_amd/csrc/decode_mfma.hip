@@ -6,6 +6,9 @@ namespace pa {
 template void launch_decode_mfma_dim<128>(const AttnArgs&, hipStream_t);
 extern template void launch_decode_mfma_dim<64>(const AttnArgs&, hipStream_t);
 extern template void launch_decode_mfma_dim<256>(const AttnArgs&, hipStream_t);
+template void launch_decode_short_dim<128>(const AttnArgs&, hipStream_t);
+extern template void launch_decode_short_dim<64>(const AttnArgs&, hipStream_t);
+extern template void launch_decode_short_dim<256>(const AttnArgs&, hipStream_t);
 
 int32_t decode_mfma_heads_per_wg(int32_t num_kv_heads, int32_t head_dim)
 {
@@ -28,6 +31,25 @@ bool decode_mfma_supported(const AttnArgs& a)
     // tile counts are kept in 32 bits (tiles hold 16 keys at head_dim 256, 32 otherwise)
     if ((int64_t)a.batch * ((a.max_seq_len + 15) / 16) > 0x7fffffffLL) return false;
     return true;
+}
+
+bool decode_short_supported(const AttnArgs& a)
+{
+    // one workgroup per (sequence, KV head, slice of 16 heads): the grid's y and z extents are 16-bit
+    const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
+    return decode_mfma_supported(a) && !a.cu_q_lens && a.cache.num_kv_heads <= 65535 && (G + 15) / 16 <= 65535;
+}
+
+pa_status launch_decode_short(const AttnArgs& a, hipStream_t stream)
+{
+    ProfileScope prof("paged_decode_short_kernel", stream);
+    switch (a.cache.head_dim) {
+        case 64: launch_decode_short_dim<64>(a, stream); break;
+        case 128: launch_decode_short_dim<128>(a, stream); break;
+        case 256: launch_decode_short_dim<256>(a, stream); break;
+        default: return PA_ERR_UNSUPPORTED;
+    }
+    return launch_status();
 }
 
 pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream)

@@ -4,5 +4,6 @@
 namespace pa {
 
 template void launch_decode_mfma_dim<64>(const AttnArgs&, hipStream_t);
+template void launch_decode_short_dim<64>(const AttnArgs&, hipStream_t);
 
 }  // namespace pa

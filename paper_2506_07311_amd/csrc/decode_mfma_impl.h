@@ -540,6 +540,178 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Short contexts in one launch.  When a step holds little data its time is launches and dependent memory round
+// trips, not bandwidth: the tile stream above needs a second launch to merge its partials.  Here one workgroup
+// owns one (sequence, KV head[, slice of 16 heads]); its NW waves split the sequence's tiles into NW contiguous
+// ranges, run the same tile loop, and merge their NW partials through LDS -- no workspace, no merge kernel.
+// LDS: NW x 16 rows x (D + 4) floats of unnormalised accumulators (rows padded by 16 bytes so that the 16 rows of
+// a quad land on distinct banks), NW x 16 maxima and NW x 16 sums: 66 KiB at head_dim 128 and 256.
+// ---------------------------------------------------------------------------------------------------
+template <int NW, bool UNIFORM, typename E, typename M, typename GE>
+__global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
+    CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t num_q_heads,
+    int32_t max_blocks, float scale, ModArgs mods)
+{
+    constexpr int kD = GE::kD;
+    constexpr int kTileKeys = GE::kTileKeys;
+    constexpr int kRow = kD + 4;
+    __shared__ __attribute__((aligned(16))) float sm_o[NW * 16 * kRow];
+    __shared__ float sm_m[NW * 16];
+    __shared__ float sm_l[NW * 16];
+
+    const int32_t window = M::kWindow ? mods.window : 0;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int32_t s = blockIdx.x;
+    const int32_t kvh = blockIdx.y;
+    const int32_t G = num_q_heads / cache.num_kv_heads;
+    const int32_t h0 = 16 * (int32_t)blockIdx.z;
+    const int32_t rows = min(G - h0, 16);
+    const int32_t r16 = lane & 15, quad = lane >> 4;
+    const float sc = scale * kLog2e;
+
+    const int32_t len = seq_lens[s];
+    const int32_t key0 = first_key_of<kTileKeys>(len, 1, window);
+    const int32_t nt = tiles_of<kTileKeys>(len - key0);
+    const int32_t t_begin = (int32_t)(((int64_t)wave * nt) / NW);
+    const int32_t t_end = (int32_t)(((int64_t)(wave + 1) * nt) / NW);
+    const int32_t c0 = key0 + t_begin * kTileKeys;
+    const int32_t c1 = min(len, key0 + t_end * kTileKeys);
+    const int32_t pos = len - 1;
+
+    State<GE> st;
+#pragma unroll
+    for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.o[c][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    st.m = -INFINITY;
+    st.l = 0.f;
+
+    if (t_begin < t_end) {                                   // wave-uniform: this wave holds tiles
+        Addr a;
+        a.doc = nullptr;
+        a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
+        a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
+        a.page_bytes = cache.page_stride * 2;
+        a.token_bytes = cache.token_stride * 2;
+        a.log2_page = cache.log2_page;
+        a.pmask = cache.page_size - 1;
+        a.r16 = r16;
+        a.quad = quad;
+        a.koff = (uint32_t)(r16 * a.token_bytes + quad * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + (r16 & GE::kPieceMask) * 16);
+        a.table = block_table + (int64_t)s * max_blocks;
+
+        RowMods rm;
+        rm.lo = 0;
+        rm.lo_until = 0;
+        rm.pos = pos;
+        rm.slope2 = 0.f;
+        rm.cap_in = 0.f;
+        rm.cap_out = 0.f;
+        rm.scale = scale;
+        rm.doc = 0;
+        if (M::kDoc) {
+            a.doc = mods.doc_ids + (int64_t)s * mods.doc_stride;
+            rm.doc = a.doc[pos];
+        }
+        if (M::kWindow && window > 0) {
+            rm.lo = pos - window + 1;
+            rm.lo_until = len - window;
+        }
+        if (M::kScore) {
+            if (mods.alibi_slopes && r16 < rows) rm.slope2 = mods.alibi_slopes[kvh * G + h0 + r16] * kLog2e;
+            if (mods.softcap > 0.f) {
+                rm.cap_in = scale / mods.softcap;
+                rm.cap_out = mods.softcap * kLog2e;
+            }
+        }
+        const int64_t q_idx = (int64_t)s * num_q_heads + kvh * G + h0 + min(r16, rows - 1);
+        uint4 qf[GE::kKS];
+#pragma unroll
+        for (int ks = 0; ks < GE::kKS; ++ks) {
+            qf[ks] = uint4{0, 0, 0, 0};
+            if (r16 < rows) qf[ks] = *reinterpret_cast<const uint4*>(q + q_idx * kD + 32 * ks + 8 * quad);
+        }
+        Tile<GE> ta, tb;
+        load_tile<UNIFORM, M>(ta, a, c0, c1);
+        for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
+            const int32_t t1 = t0 + kTileKeys;
+            if (t1 < c1) load_tile<UNIFORM, M>(tb, a, t1, c1);
+            compute_tile<false, E, M, GE>(st, ta, qf, sc, t0, c1, c1, quad, rm);
+            if (t1 >= c1) break;
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M>(ta, a, t1 + kTileKeys, c1);
+            compute_tile<false, E, M, GE>(st, tb, qf, sc, t1, c1, c1, quad, rm);
+        }
+    }
+
+    // publish the wave's partial: unnormalised accumulator, running maximum (log2 domain), sum
+    float l = st.l;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (kD != 64 || quad < 2) {                              // D = 64: quads 2 and 3 repeat quads 0 and 1
+        float* po = sm_o + (wave * 16 + r16) * kRow + 32 * quad;
+#pragma unroll
+        for (int c = 0; c < GE::kPasses; ++c)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                *reinterpret_cast<float4*>(po + 128 * c + 8 * r) =
+                    float4{st.o[c][0][r], st.o[c][1][r], st.o[c][2][r], st.o[c][3][r]};
+                *reinterpret_cast<float4*>(po + 128 * c + 8 * r + 4) =
+                    float4{st.o[c][4][r], st.o[c][5][r], st.o[c][6][r], st.o[c][7][r]};
+            }
+    }
+    if (quad == 0) {
+        sm_m[wave * 16 + r16] = st.m;
+        sm_l[wave * 16 + r16] = l;
+    }
+    __syncthreads();                                         // every wave arrives exactly once, with or without tiles
+
+    // merge: thread -> (row, 4 columns); weights 2^(m_p - M), a partial without any visible key weighs nothing
+    const int64_t out_row0 = (int64_t)s * num_q_heads + kvh * G + h0;
+    for (int it = threadIdx.x; it < 16 * (kD / 4); it += NW * 64) {
+        const int row = it / (kD / 4), c4 = it % (kD / 4);
+        if (row >= rows) continue;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < NW; ++p) mx = fmaxf(mx, sm_m[p * 16 + row]);
+        float sum = 0.f;
+        float4 acc = float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int p = 0; p < NW; ++p) {
+            const float mp = sm_m[p * 16 + row];
+            const float wgt = mp == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mp - mx);
+            const float4 v = *reinterpret_cast<const float4*>(sm_o + (p * 16 + row) * kRow + 4 * c4);
+            sum = __builtin_fmaf(wgt, sm_l[p * 16 + row], sum);
+            acc.x = __builtin_fmaf(wgt, v.x, acc.x);
+            acc.y = __builtin_fmaf(wgt, v.y, acc.y);
+            acc.z = __builtin_fmaf(wgt, v.z, acc.z);
+            acc.w = __builtin_fmaf(wgt, v.w, acc.w);
+        }
+        const float inv = sum > 0.f ? 1.f / sum : 0.f;       // sum == 0: an empty sequence (or no visible key)
+        uint2 wv;
+        wv.x = E::pack(acc.x * inv, acc.y * inv);
+        wv.y = E::pack(acc.z * inv, acc.w * inv);
+        *reinterpret_cast<uint2*>(out + (out_row0 + row) * kD + 4 * c4) = wv;
+        if (lse && c4 == 0) lse[out_row0 + row] = sum > 0.f ? (mx + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
+    }
+}
+
+template <int NW, typename E, typename M, typename GE>
+void launch_short_nw(const AttnArgs& a, hipStream_t stream)
+{
+    const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
+    const dim3 grid((uint32_t)a.batch, (uint32_t)a.cache.num_kv_heads, (uint32_t)((G + 15) / 16));
+    auto kern = a.cache.page_size >= 16 ? paged_decode_short_kernel<NW, true, E, M, GE>
+                                        : paged_decode_short_kernel<NW, false, E, M, GE>;
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
+                       a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.mods);
+}
+
 template <int NW, typename E, typename M, typename GE>
 void launch_nw(const AttnArgs& a, hipStream_t stream)
 {
@@ -571,6 +743,24 @@ void launch_em(const AttnArgs& a, hipStream_t stream)
 }  // namespace
 
 // Every kernel instantiation of one head_dim; defined in that head_dim's translation unit.
+template <int D>
+void launch_decode_short_dim(const AttnArgs& a, hipStream_t stream)
+{
+    typedef Mods<true, true, false> WindowScore;
+    typedef Geo<D> GE;
+    constexpr int NW = D > 128 ? 4 : 8;                 // head_dim 256: two tiles take about 250 registers
+    const bool docs = a.has_mods && a.mods.doc_ids;
+    if (a.dtype == PA_DTYPE_BF16) {
+        if (docs) launch_short_nw<NW, ElemBf16, AllMods, GE>(a, stream);
+        else if (a.has_mods) launch_short_nw<NW, ElemBf16, WindowScore, GE>(a, stream);
+        else launch_short_nw<NW, ElemBf16, NoMods, GE>(a, stream);
+    } else {
+        if (docs) launch_short_nw<NW, ElemF16, AllMods, GE>(a, stream);
+        else if (a.has_mods) launch_short_nw<NW, ElemF16, WindowScore, GE>(a, stream);
+        else launch_short_nw<NW, ElemF16, NoMods, GE>(a, stream);
+    }
+}
+
 template <int D>
 void launch_decode_mfma_dim(const AttnArgs& a, hipStream_t stream)
 {

@@ -23,6 +23,16 @@ def bits(a):
     return a.view(np.uint32) if a.dtype == np.float32 else a
 
 
+@pytest.fixture(params=["stream", "one_launch"])
+def decode_route(request, pa):
+    """The two decode kernels on the matrix cores, each forced in turn: the tile stream with its merge kernel, and the
+    one-launch kernel for short contexts (which the library would pick by itself only while the step is small)."""
+    from paper_2506_07311_amd import binding
+    binding.pa_set_option("decode_short", -1 if request.param == "stream" else 1)
+    yield request.param
+    binding.pa_set_option("decode_short", 0)
+
+
 # ----------------------------------------------------------------------------- append / gather (bit-exact)
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("P,Hkv,d", [(16, 8, 128), (1, 2, 64), (64, 8, 128), (4, 3, 32), (128, 1, 256)])
@@ -107,7 +117,7 @@ def test_config5_long_context_small(pa, oracle, P):
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64),
                                      (torch.float32, 128), (torch.bfloat16, 256)])
 @pytest.mark.parametrize("P", [1, 2, 8, 16, 32, 128])
-def test_decode_ragged_lengths_and_page_sizes(pa, oracle, dtype, d, P):
+def test_decode_ragged_lengths_and_page_sizes(pa, oracle, dtype, d, P, decode_route):
     lens = [0, 1, 2, 15, 16, 17, 31, 33, 255, 257, 700, 1500]
     w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=P, dtype=dtype,
                         seed=23 + P, device=DEV)
@@ -116,7 +126,7 @@ def test_decode_ragged_lengths_and_page_sizes(pa, oracle, dtype, d, P):
 
 @pytest.mark.parametrize("Hq,Hkv", [(1, 1), (8, 8), (16, 8), (32, 8), (64, 8), (16, 1), (24, 8), (40, 2), (32, 1),
                                     (71, 1), (96, 2)])
-def test_decode_group_sizes(pa, oracle, Hq, Hkv):
+def test_decode_group_sizes(pa, oracle, Hq, Hkv, decode_route):
     w = W.make_workload("t", seq_lens=[300, 77, 1025], num_q_heads=Hq, num_kv_heads=Hkv, head_dim=128,
                         page_size=16, dtype=torch.bfloat16, seed=31, device=DEV)
     parity.check_step(pa, oracle, w, f"decode Hq={Hq} Hkv={Hkv}")
@@ -137,6 +147,78 @@ def test_decode_head_dims_on_the_matrix_cores(pa, oracle, Hq, Hkv, dtype, d, wgs
         parity.check_step(pa, oracle, w, f"decode d={d} Hq={Hq} Hkv={Hkv} {dtype} wgs={wgs}")
     finally:
         binding.pa_set_option("decode_workgroups", 0)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (32, 8), (16, 1), (24, 8), (64, 4), (12, 4)])
+@pytest.mark.parametrize("dtype,d,P", [(torch.bfloat16, 64, 16), (torch.bfloat16, 256, 16), (torch.float16, 64, 4),
+                                       (torch.float16, 256, 64), (torch.bfloat16, 128, 1), (torch.float16, 128, 128)])
+def test_decode_in_one_launch(pa, oracle, Hq, Hkv, dtype, d, P):
+    """The one-launch decode kernel forced on every head_dim: contexts shorter than the waves of a workgroup (waves
+    without tiles), ragged tails, and contexts of many tiles per wave."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[300, 77, 1025, 16, 15, 2049, 1, 5000, 33], num_q_heads=Hq, num_kv_heads=Hkv,
+                        head_dim=d, page_size=P, dtype=dtype, seed=36, device=DEV)
+    binding.pa_set_option("decode_short", 1)
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    try:
+        parity.check_step(pa, oracle, w, f"one-launch decode d={d} Hq={Hq} Hkv={Hkv} {dtype} P={P}")
+        torch.cuda.synchronize()
+        assert binding.pa_profile_read("paged_decode_short_kernel")[0] == 1
+        assert binding.pa_profile_read("paged_attention_merge_kernel")[0] == 0
+    finally:
+        binding.pa_profile_enable(False)
+        binding.pa_profile_reset()
+        binding.pa_set_option("decode_short", 0)
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_decode_entry_with_an_empty_sequence(pa, decode_route, d):
+    """seq_lens[s] == 0 through the decode entry point itself: zeros and lse = -inf for that sequence; the other
+    sequences keep their values (bit for bit in the one-launch kernel, whose split of a sequence does not depend on
+    the others; the tile stream cuts elsewhere, so there only up to rounding)."""
+    w = W.make_workload("t", seq_lens=[300, 77, 5, 900], num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16,
+                        dtype=torch.bfloat16, seed=38, device=DEV)
+    out0, lse0 = parity.gpu_step(pa, w, append=True)
+    w.seq_lens[1] = 0
+    out1, lse1 = parity.gpu_step(pa, w, append=False)
+    keep = [0, 2, 3]
+    if decode_route == "one_launch":
+        assert torch.equal(out1[keep], out0[keep]) and torch.equal(lse1[keep], lse0[keep])
+    else:
+        parity.assert_close(parity.to_f64(out1[keep]), parity.to_f64(out0[keep]), torch.bfloat16, "other sequences")
+        assert torch.allclose(lse1[keep], lse0[keep], atol=1e-4, rtol=0)
+    assert (out1[1] == 0).all() and (lse1[1] == float("-inf")).all()
+
+
+def test_decode_route_follows_the_size_of_the_step(pa):
+    """Left to itself the library takes the one-launch kernel while every wave would walk a few tiles only, and the
+    tile stream (with its merge) beyond that or when the caller fixes the stream's workgroups."""
+    from paper_2506_07311_amd import binding
+
+    def kernels_of(L, batch=8, wgs=0):
+        w = W.make_workload("t", seq_lens=[L] * batch, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                            dtype=torch.bfloat16, seed=37, device=DEV, poison=False)
+        binding.pa_set_option("decode_workgroups", wgs)
+        binding.pa_profile_reset()
+        binding.pa_profile_enable(True)
+        try:
+            parity.gpu_step(pa, w, append=False)
+            torch.cuda.synchronize()
+            return (binding.pa_profile_read("paged_decode_short_kernel")[0],
+                    binding.pa_profile_read("paged_decode_mfma_kernel")[0],
+                    binding.pa_profile_read("paged_attention_merge_kernel")[0])
+        finally:
+            binding.pa_profile_enable(False)
+            binding.pa_profile_reset()
+            binding.pa_set_option("decode_workgroups", 0)
+
+    assert kernels_of(128) == (1, 0, 0)
+    assert kernels_of(1024) == (1, 0, 0)
+    assert kernels_of(1025) == (0, 1, 1)
+    assert kernels_of(1024, wgs=16) == (0, 1, 1)
+    assert kernels_of(512, batch=64) == (1, 0, 0)
+    assert kernels_of(512, batch=65) == (0, 1, 1)
 
 
 @pytest.mark.parametrize("wgs", [1, 3, 7, 64, 256, 1000])
@@ -631,7 +713,7 @@ def build_mods(case, Hq, lens):
 @pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 128), (torch.float32, 64),
                                      (torch.bfloat16, 64), (torch.float16, 256)])
-def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
+def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d, decode_route):
     lens = [700, 64, 2049, 33, 1, 0, 300]
     w = W.make_workload("t", seq_lens=lens, num_q_heads=8, num_kv_heads=2, head_dim=d, page_size=16, dtype=dtype,
                         seed=70, device=DEV)
@@ -639,7 +721,7 @@ def test_decode_with_mask_and_score_hooks(pa, oracle, case, dtype, d):
 
 
 @pytest.mark.parametrize("case", MOD_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
-def test_decode_hooks_with_a_group_larger_than_one_slice(pa, oracle, case):
+def test_decode_hooks_with_a_group_larger_than_one_slice(pa, oracle, case, decode_route):
     """20 query heads per KV head: two grid slices of the decode kernel, the second with 4 live columns; the
     per-head slopes and the document ids must follow the slice's head offset."""
     lens = [700, 64, 1300, 33, 1]
