@@ -84,6 +84,9 @@ def parse():
     ap.add_argument("--cold", action="store_true",
                     help="small decode workloads: rotate through copies of the pools (>= 512 MB in total) so that "
                          "every step misses the 256 MB last-level cache; default is warm (one pool)")
+    ap.add_argument("--step", choices=["fused", "pair"], default="fused",
+                    help="decode workloads: one paged_decode_step call per step (the append happens inside; default) "
+                         "or the pair paged_kv_append + paged_attention_decode")
     ap.add_argument("--launch", choices=["direct", "graph"], default="direct",
                     help="graph: capture one step (append + attention + merge) in a HIP graph and replay it; for the "
                          "small workloads, whose step is shorter than the host's launch overhead")
@@ -268,7 +271,12 @@ def main():
             pools.append((w.k_cache.clone(), w.v_cache.clone()))
     # One step = append + attention (+ merge).  The arguments of the two calls are marshalled once per pool copy
     # (binding.prepare_*): the small workloads' steps are shorter on the GPU than converting the arguments again.
+    fused = args.step == "fused" and not is_prefill and w.k_new.shape[0] == w.batch
+
     def make_step(kc, vc):
+        if fused:   # one new token per sequence at its last position, then decode: one call
+            return pa.prepare_decode_step(kc, vc, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+                                          w.scale, out=out, workspace=ws, **mods)
         app = pa.prepare_kv_append(kc, vc, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
         if is_prefill and mods:
             return lambda: (app(), pa.paged_attention_prefill_mod(kc, vc, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
@@ -334,7 +342,8 @@ def main():
         if sec < 500e-6:
             sec = time_steps(torch, step, args.steps, 0, stats_key="step")
             kernel_timing = "events in a pass of their own (same steps); step time from a pass without them"
-    for name in ("paged_kv_append_kernel", "paged_decode_mfma_kernel", "paged_decode_short_kernel",
+    for name in ("paged_kv_append_kernel", "paged_kv_append_last_kernel", "paged_decode_mfma_kernel",
+                 "paged_decode_short_kernel",
                  "paged_attention_generic_kernel",
                  "paged_attention_merge_kernel", "paged_prefill_mfma_kernel"):
         n, ms = binding.pa_profile_read(name)
@@ -354,7 +363,9 @@ def main():
         "dtype": {torch.bfloat16: "bf16", torch.float16: "f16", torch.float32: "f32"}[w.dtype], "data": "synthetic",
         "config": {"workload": args.workload, "batch": w.batch, "context": w.max_seq_len,
                    "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
-                   "page_size": w.page_size, "pool_pages": w.num_pages, "step": "append + attention (+ merge)",
+                   "page_size": w.page_size, "pool_pages": w.num_pages,
+                   "step": "paged_decode_step: append + attention (+ merge) in one call" if fused
+                   else "append + attention (+ merge)",
                    "launch": args.launch, "cache": f"cold ({len(pools)} pool copies)" if args.cold else "warm",
                    **({"window": args.window} if args.window else {}),
                    **({"alibi": True} if args.alibi else {})},

@@ -181,6 +181,23 @@ pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void*
                                       size_t workspace_bytes, void* stream);
 
 /*
+ * One decode step as one call: Algorithm 1, Assign, for one new token per sequence, then decode over the context
+ * that now ends with it.  Equivalent to
+ *     paged_kv_append(cache, k_new, v_new, seq_ids = 0 .. batch-1, positions = seq_lens - 1, T = batch, ...)
+ *     paged_attention_decode_mod(cache, q, out, lse, ..., mods, ...)
+ * and bit-identical to that pair in the pools and in out / lse.  k_new, v_new : [batch, Hkv, d] contiguous, cache
+ * dtype, 16-byte aligned; token s lands at position seq_lens[s] - 1 (seq_lens counts it already); a sequence with
+ * seq_lens[s] == 0 receives no token and gives out = 0, lse = -inf.  mods may be NULL.  The point of the call is
+ * the launch count: a step over short contexts (the range the paper measures, Sec. IV) is bound by launches and
+ * memory round trips, and here the append runs inside the one-launch decode kernel whenever that kernel takes the
+ * call; otherwise the library enqueues the append and then the decode kernels, as the pair of calls would.
+ */
+pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
+                            void* out, float* lse, const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                            int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                            const pa_attn_mods* mods, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Debug utility: checks on the device the preconditions about device-side CONTENTS that the other entry points
  * assume and do not check.  counts (host, int64[3]) receives
  *   [0] block-table entries among the first ceil(seq_lens[s] / page_size) of a row that lie outside [0, num_pages)

@@ -28,9 +28,11 @@ from .binding import (  # noqa: F401
     paged_attention_prefill,
     paged_attention_prefill_mod,
     paged_attention_workspace_bytes,
+    paged_decode_step,
     paged_kv_append,
     paged_kv_gather,
     prepare_decode,
+    prepare_decode_step,
     prepare_kv_append,
     prepare_prefill,
 )

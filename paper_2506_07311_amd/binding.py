@@ -21,7 +21,8 @@ PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
-    "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "pa_debug_check",
+    "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "paged_decode_step",
+    "pa_debug_check",
     "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
     "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
@@ -284,6 +285,43 @@ def paged_attention_decode_mod(k_cache, v_cache, q, block_table, seq_lens, max_s
                                         ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     _check(st, "paged_attention_decode_mod")
     return out
+
+
+def prepare_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
+                        window: int = 0, softcap: float = 0.0, alibi_slopes=None, doc_ids=None, out=None, lse=None,
+                        workspace=None, head_major=False, stream=None) -> PreparedCall:
+    """paged_decode_step (append of one new token per sequence + decode, one call) with its arguments marshalled once;
+    the call returns ``out``."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    B, Hq, hd = q.shape
+    if hd != d.head_dim or seq_lens.shape[0] != B or block_table.shape[0] != B:
+        raise PagedAttnError("q must be [B, Hq, d] with B matching seq_lens and block_table")
+    _dense(k_new, "k_new", k_cache.dtype), _dense(v_new, "v_new", k_cache.dtype)
+    if tuple(k_new.shape) != (B, d.num_kv_heads, hd) or tuple(v_new.shape) != (B, d.num_kv_heads, hd):
+        raise PagedAttnError("k_new / v_new must be [B, Hkv, d]")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens")
+    out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    if workspace is None:
+        workspace = _workspace(None, paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len), q.device)
+    m = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    args = (ctypes.byref(d), _p(k_new), _p(v_new), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
+            ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
+            ctypes.c_float(scale), ctypes.byref(m), _p(workspace),
+            ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    return PreparedCall(lib.paged_decode_step, args,
+                        (d, m, k_cache, v_cache, k_new, v_new, q, out, lse, block_table, seq_lens, workspace,
+                         alibi_slopes, doc_ids), "paged_decode_step", out)
+
+
+def paged_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, max_seq_len: int, scale: float,
+                      **kw):
+    """Appends token s of ``k_new`` / ``v_new`` ([B, Hkv, d]) at position seq_lens[s] - 1 and decodes, in one call.
+    Returns ``out``; keyword arguments as for prepare_decode_step."""
+    return prepare_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, max_seq_len, scale, **kw)()
 
 
 def paged_attention_prefill_mod(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,

@@ -231,7 +231,8 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
                         const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len, const int32_t* block_table,
                         const int32_t* seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks,
                         int32_t max_seq_len, float scale, int32_t causal, const pa_attn_mods* mods, void* workspace,
-                        size_t workspace_bytes, void* stream, bool decode)
+                        size_t workspace_bytes, void* stream, bool decode, const void* k_new = nullptr,
+                        const void* v_new = nullptr)
 {
     pa_status st = check_cache(cache);
     if (st != PA_OK) return st;
@@ -285,12 +286,19 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.skip_small = 0;
     a.mods = m;
     a.has_mods = m.window > 0 || m.softcap > 0.f || m.alibi_slopes || m.doc_ids;
+    a.k_new = k_new;
+    a.v_new = v_new;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
     if (decode) {
         if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a) &&
             (g_opt.decode_short > 0 || short_decode_pays(a)))
-            return launch_decode_short(a, s);
+            return launch_decode_short(a, s);              // with k_new / v_new: the append happens in this launch
+        if (a.k_new) {                                     // a step on the other kernels: append, then attend
+            st = launch_kv_append_last(cache, k_new, v_new, seq_lens, block_table, batch, max_blocks, s);
+            if (st != PA_OK) return st;
+            a.k_new = a.v_new = nullptr;
+        }
         if (!g_opt.force_generic && decode_mfma_supported(a)) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
@@ -475,6 +483,17 @@ pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* 
 {
     return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
                          max_seq_len, scale, 0, mods, workspace, workspace_bytes, stream, true);
+}
+
+pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
+                            void* out, float* lse, const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                            int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                            const pa_attn_mods* mods, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (batch > 0 && (!k_new || !v_new)) return PA_ERR_INVALID_ARG;
+    if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return PA_ERR_UNSUPPORTED;
+    return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
+                         max_seq_len, scale, 0, mods, workspace, workspace_bytes, stream, true, k_new, v_new);
 }
 
 pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,

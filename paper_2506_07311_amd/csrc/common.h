@@ -77,6 +77,9 @@ inline pa_status launch_status()
 pa_status launch_kv_append(const pa_kv_cache_desc* c, const void* k_new, const void* v_new, const int32_t* seq_ids,
                            const int32_t* positions, int32_t T, const int32_t* block_table, int32_t max_blocks,
                            hipStream_t stream);
+pa_status launch_kv_append_last(const pa_kv_cache_desc* c, const void* k_new, const void* v_new,
+                                const int32_t* seq_lens, const int32_t* block_table, int32_t batch, int32_t max_blocks,
+                                hipStream_t stream);
 pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, const int32_t* block_table,
                            const int32_t* seq_lens, const int32_t* cu_seq_lens, int32_t batch, int32_t max_blocks,
                            int32_t max_seq_len, hipStream_t stream);
@@ -135,6 +138,10 @@ struct AttnArgs {
     int32_t skip_small;      // prefill kernel: leave sequences with q_len * G <= 16 to the decode kernel
     ModArgs mods;
     bool has_mods;
+    // decode step with the append of one new token per sequence folded in (position seq_lens[s] - 1): [batch, Hkv, d]
+    // rows of the cache dtype, or null
+    const void* k_new;
+    const void* v_new;
 };
 
 // Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.

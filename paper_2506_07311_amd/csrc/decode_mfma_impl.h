@@ -77,11 +77,16 @@ struct Addr {
     uint32_t koff;              // UNIFORM: lane-invariant byte offset of the lane's K piece inside a 16-key block
     uint32_t voff[4];           // UNIFORM: same for the lane's 4 V rows of a 16-key block
     int32_t r16, quad;
+    // FUSED (the step's new token is appended by the same kernel): the K / V rows of key new_pos are read from
+    // the new token's rows (k_new / v_new of this sequence and KV head) instead of the pool
+    const char* knew;
+    const char* vnew;
+    int32_t new_pos;
 };
 
 // Issue the 16 loads of the tile that starts at key `t0`.  Keys at or beyond `c1` are clamped to the last
 // valid key, so every address is a live slot; their scores are masked by the caller.
-template <bool UNIFORM, typename M, typename GE>
+template <bool UNIFORM, typename M, typename GE, bool FUSED = false>
 __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0, int32_t c1)
 {
     constexpr int kTileKeys = GE::kTileKeys;
@@ -100,6 +105,19 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
                 const int64_t blk = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
                 const char* kp = a.kbase + blk;
                 const char* vp = a.vbase + blk;
+                if constexpr (FUSED) {
+                    const char* kl = kb + a.r16 == a.new_pos ? a.knew + a.quad * 16 : kp + a.koff;
+#pragma unroll
+                    for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kl + 64 * ks);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const char* vl = kb + 4 * a.quad + i == a.new_pos ? a.vnew + (a.r16 & GE::kPieceMask) * 16
+                                                                          : vp + a.voff[i];
+#pragma unroll
+                        for (int c = 0; c < GE::kPasses; ++c) t.v[c][4 * mt + i] = load16(vl + 256 * c);
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + a.koff + 64 * ks);
 #pragma unroll
@@ -117,6 +135,7 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
         const int32_t key = min(t0 + 16 * mt + a.r16, last);
         const int64_t page = a.table[key >> a.log2_page];
         const char* kp = a.kbase + page * a.page_bytes + (int64_t)(key & a.pmask) * a.token_bytes + a.quad * 16;
+        if (FUSED && key == a.new_pos) kp = a.knew + a.quad * 16;
 #pragma unroll
         for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + 64 * ks);
 #pragma unroll
@@ -125,6 +144,7 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
             const int64_t vpage = a.table[vkey >> a.log2_page];
             const char* vp = a.vbase + vpage * a.page_bytes + (int64_t)(vkey & a.pmask) * a.token_bytes +
                              (a.r16 & GE::kPieceMask) * 16;
+            if (FUSED && vkey == a.new_pos) vp = a.vnew + (a.r16 & GE::kPieceMask) * 16;
 #pragma unroll
             for (int c = 0; c < GE::kPasses; ++c) t.v[c][4 * mt + i] = load16(vp + 256 * c);
         }
@@ -390,6 +410,9 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 
     Addr a;
     a.doc = nullptr;
+    a.knew = nullptr;
+    a.vnew = nullptr;
+    a.new_pos = -1;
     a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
     a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
     a.page_bytes = cache.page_stride * 2;
@@ -548,11 +571,16 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 // LDS: NW x 16 rows x (D + 4) floats of unnormalised accumulators (rows padded by 16 bytes so that the 16 rows of
 // a quad land on distinct banks), NW x 16 maxima and NW x 16 sums: 66 KiB at head_dim 128 and 256.
 // ---------------------------------------------------------------------------------------------------
-template <int NW, bool UNIFORM, typename E, typename M, typename GE>
+// FUSED: the kernel also performs the step's append (Algorithm 1, Assign) of one new token per sequence at position
+// len - 1: the wave that owns the sequence's last tile (always the last wave) stores the token's K / V rows of
+// this KV head into their slot, and reads those rows from k_new / v_new instead of the pool, so nothing waits for
+// the store.  (Workgroups of other head slices of the same KV head read the new rows the same way and store nothing.)
+template <int NW, bool UNIFORM, bool FUSED, typename E, typename M, typename GE>
 __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t num_q_heads,
-    int32_t max_blocks, float scale, ModArgs mods)
+    int32_t max_blocks, float scale, ModArgs mods, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new)
 {
     constexpr int kD = GE::kD;
     constexpr int kTileKeys = GE::kTileKeys;
@@ -605,6 +633,26 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
         for (int i = 0; i < 4; ++i)
             a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + (r16 & GE::kPieceMask) * 16);
         a.table = block_table + (int64_t)s * max_blocks;
+        a.knew = nullptr;
+        a.vnew = nullptr;
+        a.new_pos = -1;
+        if constexpr (FUSED) {
+            const int64_t new_row = ((int64_t)s * cache.num_kv_heads + kvh) * kD * 2;
+            a.knew = reinterpret_cast<const char*>(k_new) + new_row;
+            a.vnew = reinterpret_cast<const char*>(v_new) + new_row;
+            a.new_pos = pos;
+            if (wave == NW - 1 && blockIdx.z == 0) {
+                constexpr int kPieces = kD / 8;              // 16-byte pieces of a row; K then V: at most 64 lanes
+                if (lane < 2 * kPieces) {
+                    const bool is_v = lane >= kPieces;
+                    const int piece = lane - (is_v ? kPieces : 0);
+                    const int64_t page = a.table[pos >> a.log2_page];
+                    const int64_t slot = page * a.page_bytes + (int64_t)(pos & a.pmask) * a.token_bytes + piece * 16;
+                    char* dst = const_cast<char*>(is_v ? a.vbase : a.kbase) + slot;
+                    *reinterpret_cast<uint4*>(dst) = load16((is_v ? a.vnew : a.knew) + piece * 16);
+                }
+            }
+        }
 
         RowMods rm;
         rm.lo = 0;
@@ -638,13 +686,13 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
             if (r16 < rows) qf[ks] = *reinterpret_cast<const uint4*>(q + q_idx * kD + 32 * ks + 8 * quad);
         }
         Tile<GE> ta, tb;
-        load_tile<UNIFORM, M>(ta, a, c0, c1);
+        load_tile<UNIFORM, M, GE, FUSED>(ta, a, c0, c1);
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
-            if (t1 < c1) load_tile<UNIFORM, M>(tb, a, t1, c1);
+            if (t1 < c1) load_tile<UNIFORM, M, GE, FUSED>(tb, a, t1, c1);
             compute_tile<false, E, M, GE>(st, ta, qf, sc, t0, c1, c1, quad, rm);
             if (t1 >= c1) break;
-            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M>(ta, a, t1 + kTileKeys, c1);
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M, GE, FUSED>(ta, a, t1 + kTileKeys, c1);
             compute_tile<false, E, M, GE>(st, tb, qf, sc, t1, c1, c1, quad, rm);
         }
     }
@@ -706,10 +754,14 @@ void launch_short_nw(const AttnArgs& a, hipStream_t stream)
 {
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
     const dim3 grid((uint32_t)a.batch, (uint32_t)a.cache.num_kv_heads, (uint32_t)((G + 15) / 16));
-    auto kern = a.cache.page_size >= 16 ? paged_decode_short_kernel<NW, true, E, M, GE>
-                                        : paged_decode_short_kernel<NW, false, E, M, GE>;
+    const bool uniform = a.cache.page_size >= 16;
+    auto kern = a.k_new ? (uniform ? paged_decode_short_kernel<NW, true, true, E, M, GE>
+                                   : paged_decode_short_kernel<NW, false, true, E, M, GE>)
+                        : (uniform ? paged_decode_short_kernel<NW, true, false, E, M, GE>
+                                   : paged_decode_short_kernel<NW, false, false, E, M, GE>);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
-                       a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.mods);
+                       a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.mods,
+                       (const uint16_t*)a.k_new, (const uint16_t*)a.v_new);
 }
 
 template <int NW, typename E, typename M, typename GE>

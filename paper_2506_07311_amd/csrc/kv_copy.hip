@@ -37,6 +37,32 @@ __global__ __launch_bounds__(kThreads) void paged_kv_append_kernel(
         v_cache[dst] = v_new[idx];
 }
 
+// The append of a decode step: one new token per sequence, token s at position seq_lens[s] - 1 (Algorithm 1, Assign,
+// with seq_ids = 0 .. batch-1 and positions = seq_lens - 1 implied); a sequence of length 0 receives nothing.
+__global__ __launch_bounds__(kThreads) void paged_kv_append_last_kernel(
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, const uint4* __restrict__ k_new,
+    const uint4* __restrict__ v_new, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ block_table,
+    int64_t total_vec, int32_t vec_per_head, int32_t num_kv_heads, int32_t max_blocks, int32_t log2_page,
+    int64_t page_stride_v, int64_t token_stride_v, int64_t head_stride_v)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total_vec) return;
+    const int32_t vec = (int32_t)(idx % vec_per_head);
+    const int64_t th = idx / vec_per_head;
+    const int32_t h = (int32_t)(th % num_kv_heads);
+    const int64_t s = th / num_kv_heads;
+    const int32_t t = seq_lens[s] - 1;
+    if (t < 0) return;
+    const int32_t b = t >> log2_page;
+    const int32_t o = t & ((1 << log2_page) - 1);
+    const int64_t page = block_table[s * max_blocks + b];
+    const int64_t dst = page * page_stride_v + (int64_t)o * token_stride_v + (int64_t)h * head_stride_v + vec;
+    if (blockIdx.y == 0)
+        k_cache[dst] = k_new[idx];
+    else
+        v_cache[dst] = v_new[idx];
+}
+
 __global__ __launch_bounds__(kThreads) void paged_kv_gather_kernel(
     const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, uint4* __restrict__ out_k,
     uint4* __restrict__ out_v, const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
@@ -132,6 +158,26 @@ pa_status launch_kv_append(const pa_kv_cache_desc* c, const void* k_new, const v
     hipLaunchKernelGGL(paged_kv_append_kernel, dim3((uint32_t)blocks, 2, 1), dim3(kThreads), 0, stream,
                        (uint4*)c->k_cache, (uint4*)c->v_cache, (const uint4*)k_new, (const uint4*)v_new, seq_ids,
                        positions, block_table, total_vec, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
+                       c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
+    return launch_status();
+}
+
+pa_status launch_kv_append_last(const pa_kv_cache_desc* c, const void* k_new, const void* v_new,
+                                const int32_t* seq_lens, const int32_t* block_table, int32_t batch, int32_t max_blocks,
+                                hipStream_t stream)
+{
+    const CacheView v = make_view(c);
+    const int eb = elem_bytes(c->dtype);
+    const int32_t epv = 16 / eb;
+    const int32_t vec_per_head = c->head_dim / epv;
+    const int64_t total_vec = (int64_t)batch * c->num_kv_heads * vec_per_head;
+    const int64_t blocks = (total_vec + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
+    if (blocks == 0) return PA_OK;
+    ProfileScope prof("paged_kv_append_last_kernel", stream);
+    hipLaunchKernelGGL(paged_kv_append_last_kernel, dim3((uint32_t)blocks, 2, 1), dim3(kThreads), 0, stream,
+                       (uint4*)c->k_cache, (uint4*)c->v_cache, (const uint4*)k_new, (const uint4*)v_new, seq_lens,
+                       block_table, total_vec, vec_per_head, c->num_kv_heads, max_blocks, v.log2_page,
                        c->page_stride / epv, c->token_stride / epv, c->head_stride / epv);
     return launch_status();
 }

@@ -191,6 +191,95 @@ def test_decode_entry_with_an_empty_sequence(pa, decode_route, d):
     assert (out1[1] == 0).all() and (lse1[1] == float("-inf")).all()
 
 
+STEP_SHAPES = [
+    # lens, Hq, Hkv, d, P, dtype
+    ([300, 77, 1025, 16, 15, 33, 1, 64, 32], 32, 8, 128, 16, torch.bfloat16),
+    ([300, 77, 1, 513, 32], 8, 8, 64, 16, torch.float16),
+    ([300, 77, 1, 513, 16], 24, 8, 256, 64, torch.bfloat16),
+    ([300, 77, 1, 513, 17], 40, 2, 128, 4, torch.bfloat16),      # 20 heads per KV head: two grid slices; P < 16
+    ([5000, 77, 2049], 32, 8, 128, 16, torch.bfloat16),           # left to itself this takes the tile stream
+    ([300, 77, 31], 8, 8, 64, 16, torch.float32),                 # portable kernel
+]
+
+
+@pytest.mark.parametrize("shape", STEP_SHAPES, ids=lambda c: f"Hq{c[1]}-Hkv{c[2]}-d{c[3]}-P{c[4]}-n{len(c[0])}")
+@pytest.mark.parametrize("route", [0, 1, -1])
+@pytest.mark.parametrize("case", [None, dict(window=100), dict(docs=True, alibi=True, softcap=3.0)],
+                         ids=["plain", "window", "hooks"])
+def test_decode_step_is_the_append_followed_by_decode(pa, oracle, shape, route, case):
+    """paged_decode_step against the pair of calls it stands for: pools and outputs bit-identical, whichever kernels
+    the step runs on (route 0: the library's choice; 1: append inside the one-launch kernel; -1: append kernel, then
+    tile stream and merge), and the pair itself is checked against the oracle."""
+    from paper_2506_07311_amd import binding
+    lens, Hq, Hkv, d, P, dtype = shape
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=P, dtype=dtype,
+                        seed=39, device=DEV)
+    assert w.k_new.shape[0] == len(lens)                      # one new token per sequence, in sequence order
+    mods = build_mods(case, Hq, lens) if case else None
+    k0, v0 = w.k_cache.clone(), w.v_cache.clone()
+    binding.pa_set_option("decode_short", route)
+    try:
+        res = parity.check_step(pa, oracle, w, f"pair {shape} {case}", mods=mods)
+        out_pair, lse_pair = parity.gpu_step(pa, w, append=False, mods=mods)
+        k_pair, v_pair = w.k_cache.clone(), w.v_cache.clone()
+        w.k_cache.copy_(k0)
+        w.v_cache.copy_(v0)
+        kw = {}
+        if mods:
+            kw = dict(window=mods.get("window", 0), softcap=mods.get("softcap", 0.0))
+            if mods.get("alibi_slopes") is not None:
+                kw["alibi_slopes"] = torch.tensor(np.asarray(mods["alibi_slopes"]), dtype=torch.float32, device=DEV)
+            if mods.get("doc_ids") is not None:
+                kw["doc_ids"] = torch.tensor(np.asarray(mods["doc_ids"]), dtype=torch.int32, device=DEV)
+        lse = torch.full((w.batch, Hq), float("nan"), dtype=torch.float32, device=DEV)
+        binding.pa_profile_reset()
+        binding.pa_profile_enable(True)
+        out = pa.paged_decode_step(w.k_cache, w.v_cache, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens,
+                                   w.max_seq_len, w.scale, lse=lse, **kw)
+        torch.cuda.synchronize()
+        launches = sum(binding.pa_profile_read(n)[0] for n in ("paged_", ))
+        binding.pa_profile_enable(False)
+        view = torch.int32 if dtype == torch.float32 else torch.int16
+        assert torch.equal(w.k_cache.view(view), k_pair.view(view)) and torch.equal(w.v_cache.view(view), v_pair.view(view))
+        assert torch.equal(out.view(view), out_pair.view(view)), "out differs from the pair of calls"
+        assert torch.equal(lse, lse_pair)
+        if route == 1 and dtype != torch.float32:
+            assert launches == 1, "the step on the one-launch kernel is a single launch"
+    finally:
+        binding.pa_profile_enable(False)
+        binding.pa_profile_reset()
+        binding.pa_set_option("decode_short", 0)
+
+
+def test_decode_step_with_an_empty_sequence(pa):
+    """A sequence of length 0 receives no token and gives zeros; the pools keep every byte outside the other
+    sequences' slots."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[300, 77, 5, 900], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=40, device=DEV)
+    w.seq_lens[1] = 0
+    k0, v0 = w.k_cache.clone(), w.v_cache.clone()
+    results = []
+    for route in (1, -1):
+        w.k_cache.copy_(k0)
+        w.v_cache.copy_(v0)
+        binding.pa_set_option("decode_short", route)
+        try:
+            lse = torch.full((4, 8), float("nan"), dtype=torch.float32, device=DEV)
+            out = pa.paged_decode_step(w.k_cache, w.v_cache, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens,
+                                       w.max_seq_len, w.scale, lse=lse)
+            torch.cuda.synchronize()
+        finally:
+            binding.pa_set_option("decode_short", 0)
+        assert (out[1] == 0).all() and (lse[1] == float("-inf")).all()
+        results.append((w.k_cache.clone().view(torch.int16), w.v_cache.clone().view(torch.int16), out.clone(), lse))
+    assert torch.equal(results[0][0], results[1][0]) and torch.equal(results[0][1], results[1][1])
+    # the slot the untouched sequence would have used (its former last position) still holds its poison
+    changed = (results[0][0] != k0.view(torch.int16)).flatten(1).any(dim=1).sum().item()
+    assert changed <= 3, "only the three live sequences' pages may change"
+    parity.assert_close(parity.to_f64(results[0][2]), parity.to_f64(results[1][2]), torch.bfloat16, "routes agree")
+
+
 def test_decode_route_follows_the_size_of_the_step(pa):
     """Left to itself the library takes the one-launch kernel while every wave would walk a few tiles only, and the
     tile stream (with its merge) beyond that or when the caller fixes the stream's workgroups."""
