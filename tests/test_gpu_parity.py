@@ -588,11 +588,14 @@ def test_config5_full_size_sampled_sequences(pa, oracle, P):
 
 
 # ----------------------------------------------------------------------------- HIP graph replay
-def test_decode_step_replays_in_a_hip_graph(pa, oracle):
-    """One step (append + decode + merge) captured in a HIP graph: every replay, with eager work and
-    synchronisations in between and fresh inputs written in place, must reproduce the eager result bitwise
-    (the library records no memset node and allocates nothing, so the capture holds only its kernels)."""
-    w = W.make_workload("t", seq_lens=[700, 64, 2048, 33], num_q_heads=32, num_kv_heads=8, head_dim=128,
+@pytest.mark.parametrize("how", ["pair_of_calls", "step_call_one_launch", "step_call_tile_stream"])
+def test_decode_step_replays_in_a_hip_graph(pa, oracle, how):
+    """One step (append + decode + merge; or the single paged_decode_step call, as one launch or as append kernel +
+    tile stream + merge) captured in a HIP graph: every replay, with eager work and synchronisations in between
+    and fresh inputs written in place, must reproduce the eager result bitwise (the library records no memset
+    node and allocates nothing, so the capture holds only its kernels)."""
+    lens = [700, 64, 1000, 33] if how == "step_call_one_launch" else [700, 64, 2048, 33]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=32, num_kv_heads=8, head_dim=128,
                         page_size=16, dtype=torch.bfloat16, seed=61, device=DEV)
     ws = torch.empty(pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.batch, w.max_seq_len),
                      dtype=torch.uint8, device=DEV)
@@ -600,9 +603,13 @@ def test_decode_step_replays_in_a_hip_graph(pa, oracle):
     lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device=DEV)
 
     def step():
-        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
-        pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
-                                  out=out, lse=lse, workspace=ws)
+        if how == "pair_of_calls":
+            pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
+            pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
+                                      out=out, lse=lse, workspace=ws)
+        else:
+            pa.paged_decode_step(w.k_cache, w.v_cache, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens,
+                                 w.max_seq_len, w.scale, out=out, lse=lse, workspace=ws)
 
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
