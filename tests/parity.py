@@ -51,8 +51,9 @@ def oracle_step(oracle, w: W.PagedWorkload, append=True, mods=None):
     return k, v, out, lse
 
 
-def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, mods=None):
-    """Append then attention through the C-ABI binding, in place on the workload's pools."""
+def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, mods=None, step_call=False):
+    """Append then attention through the C-ABI binding, in place on the workload's pools.  ``step_call``: a decode
+    step goes through the single paged_decode_step call instead of paged_kv_append + paged_attention_decode."""
     kw = {}
     if mods:
         dev = w.q.device
@@ -61,10 +62,11 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, m
             kw["alibi_slopes"] = torch.tensor(np.asarray(mods["alibi_slopes"]), dtype=torch.float32, device=dev)
         if mods.get("doc_ids") is not None:
             kw["doc_ids"] = torch.tensor(np.asarray(mods["doc_ids"]), dtype=torch.int32, device=dev)
-    if append and w.seq_ids.numel():
-        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
     if prefill is None:
         prefill = w.causal or w.max_q_len > 1 or w.total_q != w.batch
+    step_call = step_call and append and not prefill and w.k_new.shape[0] == w.batch
+    if append and w.seq_ids.numel() and not step_call:
+        pa.paged_kv_append(w.k_cache, w.v_cache, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
     lse = torch.full((w.total_q, w.num_q_heads), float("nan"), dtype=torch.float32, device=w.q.device) \
         if with_lse else None
     # the workspace's contents are unspecified on entry: poison it (all-ones bytes: NaN as float, -1 as int), so a
@@ -72,7 +74,10 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, m
     ws = torch.full((pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.total_q,
                                                         w.max_seq_len),), 0xFF, dtype=torch.uint8, device=w.q.device)
     kw["workspace"] = ws
-    if prefill and mods:
+    if step_call:
+        out = pa.paged_decode_step(w.k_cache, w.v_cache, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens,
+                                   w.max_seq_len, w.scale, lse=lse, **kw)
+    elif prefill and mods:
         out = pa.paged_attention_prefill_mod(w.k_cache, w.v_cache, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
                                              w.seq_lens, w.max_seq_len, w.scale, w.causal, lse=lse, **kw)
     elif prefill:
@@ -94,7 +99,7 @@ def _bits(a):
 
 
 def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None, tol=None, mods=None,
-               per_seq=False):
+               per_seq=False, step_call=False):
     """Full parity of one step: pools bit-exact after the append, attention within tolerance.
     With ``seqs`` the oracle sees only those sequences (their pages copied out BEFORE the GPU path runs);
     the GPU path always runs the whole workload.  With ``per_seq`` the two measures are taken over each
@@ -104,7 +109,7 @@ def check_step(pa, oracle, w: W.PagedWorkload, what="", prefill=None, seqs=None,
     ref_w = w if seqs is None else W.restrict(w, seqs, device="cpu")
     assert mods is None or seqs is None
     k_ref, v_ref, o_ref, lse_ref = oracle_step(oracle, ref_w, mods=mods)
-    out, lse = gpu_step(pa, w, prefill=prefill, mods=mods)
+    out, lse = gpu_step(pa, w, prefill=prefill, mods=mods, step_call=step_call)
     after = w if seqs is None else W.restrict(w, seqs, device="cpu")
     assert np.array_equal(_bits(W.to_numpy(after.k_cache)), _bits(k_ref)), f"{what}: K pool differs after append"
     assert np.array_equal(_bits(W.to_numpy(after.v_cache)), _bits(v_ref)), f"{what}: V pool differs after append"

@@ -92,8 +92,11 @@ def test_config1_fp32_single_sequence_decode(pa, oracle):
 
 
 @pytest.mark.parametrize("L", [128, 256, 512, 1024, 2048])
-def test_config2_bf16_gqa_decode(pa, oracle, L):
-    parity.check_step(pa, oracle, W.config(2, device=DEV, context=L), f"config 2 L={L}")
+@pytest.mark.parametrize("step_call", [False, True], ids=["pair_of_calls", "step_call"])
+def test_config2_bf16_gqa_decode(pa, oracle, L, step_call):
+    """As the benchmark runs it: the library's own choice of kernels, through the pair of calls and through the single
+    step call."""
+    parity.check_step(pa, oracle, W.config(2, device=DEV, context=L), f"config 2 L={L}", step_call=step_call)
 
 
 @pytest.mark.parametrize("S", [256, 333])
@@ -573,16 +576,18 @@ def test_config3_full_size_causal_prefill(pa, oracle):
 
 
 def test_config4_full_size_mixed_decode(pa, oracle):
-    """All 64 ragged sequences (lengths 64..32768, shared 1024-token prefixes), the launch bench.py times."""
-    parity.check_step(pa, oracle, W.config(4, device=DEV), "config 4 full", seqs=list(range(64)))
+    """All 64 ragged sequences (lengths 64..32768, shared 1024-token prefixes), the launch bench.py times (one
+    paged_decode_step call per step)."""
+    parity.check_step(pa, oracle, W.config(4, device=DEV), "config 4 full", seqs=list(range(64)), step_call=True)
 
 
 @pytest.mark.parametrize("P", [16, 64])
 def test_config5_full_size_sampled_sequences(pa, oracle, P):
-    """Batch 16 x 131072 context in the launch configuration bench.py times; three whole sequences
+    """Batch 16 x 131072 context in the launch configuration bench.py times (P = 16: one paged_decode_step call
+    per step, as the benchmark's default; P = 64: the pair of calls, its --step pair); three whole sequences
     (all 64 heads) are recomputed by the oracle, and every output of the batch must be finite."""
     w = W.config(5, device=DEV, page_size=P)
-    parity.check_step(pa, oracle, w, f"config 5 full P={P}", seqs=[0, 7, 15])
+    parity.check_step(pa, oracle, w, f"config 5 full P={P}", seqs=[0, 7, 15], step_call=(P == 16))
     del w
     torch.cuda.empty_cache()
 
