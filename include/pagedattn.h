@@ -189,8 +189,9 @@ pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void*
  * dtype, 16-byte aligned; token s lands at position seq_lens[s] - 1 (seq_lens counts it already); a sequence with
  * seq_lens[s] == 0 receives no token and gives out = 0, lse = -inf.  mods may be NULL.  The point of the call is
  * the launch count: a step over short contexts (the range the paper measures, Sec. IV) is bound by launches and
- * memory round trips, and here the append runs inside the one-launch decode kernel whenever that kernel takes the
- * call; otherwise the library enqueues the append and then the decode kernels, as the pair of calls would.
+ * memory round trips, and here the append runs inside the decode kernel itself when the one-launch kernel for
+ * short contexts or the portable kernel takes the call; on the tile-stream kernel (long contexts) the library
+ * enqueues the append and then the decode kernels, as the pair of calls would.
  */
 pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
                             void* out, float* lse, const int32_t* block_table, const int32_t* seq_lens, int32_t batch,

@@ -294,12 +294,13 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a) &&
             (g_opt.decode_short > 0 || short_decode_pays(a)))
             return launch_decode_short(a, s);              // with k_new / v_new: the append happens in this launch
-        if (a.k_new) {                                     // a step on the other kernels: append, then attend
+        const bool stream_route = !g_opt.force_generic && decode_mfma_supported(a);
+        if (a.k_new && stream_route) {                     // a step on the tile stream: append, then attend
             st = launch_kv_append_last(cache, k_new, v_new, seq_lens, block_table, batch, max_blocks, s);
             if (st != PA_OK) return st;
             a.k_new = a.v_new = nullptr;
-        }
-        if (!g_opt.force_generic && decode_mfma_supported(a)) {
+        }                                                  // (the portable kernel below appends by itself)
+        if (stream_route) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
             a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads,

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks, float scale,
     int32_t causal, float* __restrict__ part_o, float* __restrict__ part_lse, int32_t chunk, int32_t nsplit,
-    ModArgs mods)
+    ModArgs mods, const void* __restrict__ k_new, const void* __restrict__ v_new)
 {
     using V = Vec<T>;
     constexpr int N = V::N;
@@ -175,6 +175,27 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
     const char* kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * EB;
     const char* vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * EB;
 
+    // Decode step with the append folded in (k_new != null; row == sequence): the new token sits at the last
+    // position.  Its K / V rows are read from k_new / v_new wherever the loops below meet that key, and the workgroup
+    // of the KV head's first query head whose chunk holds the key stores them into their slot (Algorithm 1, Assign).
+    const int32_t new_pos = k_new ? ri.pos : -1;
+    const char* knew_row = nullptr;
+    const char* vnew_row = nullptr;
+    if (k_new) {
+        const int64_t new_off = ((int64_t)s * cache.num_kv_heads + kvh) * d * EB;
+        knew_row = reinterpret_cast<const char*>(k_new) + new_off;
+        vnew_row = reinterpret_cast<const char*>(v_new) + new_off;
+        if (h % G == 0 && new_pos >= c0 && new_pos < c1 && tid < 2 * vpr) {
+            const bool is_v = tid >= vpr;
+            const int32_t piece = tid - (is_v ? vpr : 0);
+            const int64_t page = table[new_pos >> cache.log2_page];
+            const int64_t slot = (page * cache.page_stride + (int64_t)(new_pos & pmask) * cache.token_stride) * EB;
+            char* dst = const_cast<char*>(is_v ? vbase : kbase) + slot + piece * 16;
+            *reinterpret_cast<uint4*>(dst) =
+                *reinterpret_cast<const uint4*>((is_v ? vnew_row : knew_row) + piece * 16);
+        }
+    }
+
     score_t m = -INFINITY;
     float l = 0.f;
     float acc[N];
@@ -189,6 +210,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
             const int32_t j = t0 + jj;
             const int64_t page = table[j >> cache.log2_page];
             const char* kr = kbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
+            if (j == new_pos) kr = knew_row;
             typename V::dot_t dot = 0;
             for (int32_t c = 0; c < vpr; ++c) {
                 float kv[N];
@@ -226,6 +248,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
                 const int32_t j = t0 + jj;
                 const int64_t page = table[j >> cache.log2_page];
                 const char* vr = vbase + (page * cache.page_stride + (int64_t)(j & pmask) * cache.token_stride) * EB;
+                if (j == new_pos) vr = vnew_row;
                 float vv[N];
                 V::load(vr + vc * 16, vv);
                 const float p = (float)sc[jj];
@@ -269,7 +292,8 @@ pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream)
     // hook combinations instantiated here: none; window and / or score; all (document masks)
     const int hooks = !a.has_mods ? 0 : a.mods.doc_ids ? 2 : 1;
     void (*kern)(CacheView, const void*, void*, float*, const int32_t*, const int32_t*, const int32_t*, int32_t,
-                 int32_t, int32_t, float, int32_t, float*, float*, int32_t, int32_t, ModArgs) = nullptr;
+                 int32_t, int32_t, float, int32_t, float*, float*, int32_t, int32_t, ModArgs, const void*,
+                 const void*) = nullptr;
     typedef Mods<true, true, false> WindowScore;
     if (a.dtype == PA_DTYPE_F32)
         kern = hooks == 0   ? paged_attention_generic_kernel<float, NoMods>
@@ -285,7 +309,8 @@ pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream)
                             : paged_attention_generic_kernel<f16_tag, AllMods>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(kThreads), 0, stream, a.cache, a.q, a.out, a.lse,
                        a.cu_q_lens, a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.causal,
-                       a.part_o, a.part_lse, a.plan.chunk, a.plan.nsplit, a.mods);
+                       a.part_o, a.part_lse, a.plan.chunk, a.plan.nsplit, a.mods, a.cu_q_lens ? nullptr : a.k_new,
+                       a.cu_q_lens ? nullptr : a.v_new);
     return launch_status();
 }
 

@@ -201,7 +201,9 @@ STEP_SHAPES = [
     ([300, 77, 1, 513, 16], 24, 8, 256, 64, torch.bfloat16),
     ([300, 77, 1, 513, 17], 40, 2, 128, 4, torch.bfloat16),      # 20 heads per KV head: two grid slices; P < 16
     ([5000, 77, 2049], 32, 8, 128, 16, torch.bfloat16),           # left to itself this takes the tile stream
-    ([300, 77, 31], 8, 8, 64, 16, torch.float32),                 # portable kernel
+    ([300, 77, 31], 8, 8, 64, 16, torch.float32),                 # portable kernel: append inside it, one launch
+    ([5000, 77, 1], 8, 2, 64, 16, torch.float32),                 # portable kernel with a context split and a merge
+    ([300, 77, 1025, 2], 12, 4, 96, 8, torch.bfloat16),           # head_dim 96: portable kernel, 16-bit rows
 ]
 
 
@@ -246,7 +248,9 @@ def test_decode_step_is_the_append_followed_by_decode(pa, oracle, shape, route, 
         assert torch.equal(w.k_cache.view(view), k_pair.view(view)) and torch.equal(w.v_cache.view(view), v_pair.view(view))
         assert torch.equal(out.view(view), out_pair.view(view)), "out differs from the pair of calls"
         assert torch.equal(lse, lse_pair)
-        if route == 1 and dtype != torch.float32:
+        if d not in (64, 128, 256) or dtype == torch.float32:
+            assert launches <= 2, "portable kernel: the append runs inside it; at most a merge follows"
+        elif route == 1:
             assert launches == 1, "the step on the one-launch kernel is a single launch"
     finally:
         binding.pa_profile_enable(False)
