@@ -189,9 +189,9 @@ pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void*
  * dtype, 16-byte aligned; token s lands at position seq_lens[s] - 1 (seq_lens counts it already); a sequence with
  * seq_lens[s] == 0 receives no token and gives out = 0, lse = -inf.  mods may be NULL.  The point of the call is
  * the launch count: a step over short contexts (the range the paper measures, Sec. IV) is bound by launches and
- * memory round trips, and here the append runs inside the decode kernel itself when the one-launch kernel for
- * short contexts or the portable kernel takes the call; on the tile-stream kernel (long contexts) the library
- * enqueues the append and then the decode kernels, as the pair of calls would.
+ * memory round trips, and here the append runs inside the decode kernel itself: the wave (or workgroup) that
+ * meets a sequence's last key stores the new rows into their slot and reads them from k_new / v_new, on every
+ * decode kernel of the library.
  */
 pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
                             void* out, float* lse, const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
@@ -226,6 +226,8 @@ const char* pa_status_string(pa_status status);
  *   "decode_short"         the one-launch decode kernel for short contexts (a workgroup per sequence and KV head,
  *                          no workspace, no merge launch): 0 = taken while the step is small enough for it to
  *                          pay (the default), 1 = whenever it supports the call, -1 = never
+ *   "step_append_kernel"   1 = paged_decode_step on the tile-stream kernel appends with a kernel launch of its own
+ *                          instead of inside the decode kernel (for comparison)
  *   "no_small_q_route"     1 = the prefill entry point keeps sequences with few queries (q_len * G <= 16) on
  *                          the prefill kernel instead of handing them to the decode kernel
  *   "force_generic"        1 = always take the portable VALU kernels

@@ -18,6 +18,8 @@ struct Options {
     int64_t force_generic = 0;
     int64_t prefill_chunk_tokens = 0;
     int64_t no_small_q_route = 0;
+    int64_t step_append_kernel = 0;   // 1 = paged_decode_step on the tile stream appends with a kernel of its own
+                                      // (0: every decode kernel performs the step's append itself)
     int64_t decode_short = 0;      // 0 = heuristic, 1 = whenever the one-launch kernel supports the call, -1 = never
 } g_opt;
 
@@ -295,11 +297,11 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
             (g_opt.decode_short > 0 || short_decode_pays(a)))
             return launch_decode_short(a, s);              // with k_new / v_new: the append happens in this launch
         const bool stream_route = !g_opt.force_generic && decode_mfma_supported(a);
-        if (a.k_new && stream_route) {                     // a step on the tile stream: append, then attend
+        if (a.k_new && stream_route && g_opt.step_append_kernel) {   // append as a launch of its own, then attend
             st = launch_kv_append_last(cache, k_new, v_new, seq_lens, block_table, batch, max_blocks, s);
             if (st != PA_OK) return st;
             a.k_new = a.v_new = nullptr;
-        }                                                  // (the portable kernel below appends by itself)
+        }                                                  // (otherwise every decode kernel appends by itself)
         if (stream_route) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             a.stream_split = 1;
@@ -552,6 +554,11 @@ pa_status pa_set_option(const char* name, int64_t value)
     if (!strcmp(name, "no_small_q_route")) {
         if (value != 0 && value != 1) return PA_ERR_INVALID_ARG;
         g_opt.no_small_q_route = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "step_append_kernel")) {
+        if (value != 0 && value != 1) return PA_ERR_INVALID_ARG;
+        g_opt.step_append_kernel = value;
         return PA_OK;
     }
     if (!strcmp(name, "decode_short")) {

@@ -358,19 +358,21 @@ __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ seq_lens
 // columns are (query, head) pairs, column = query * G + head, each with its own causal bound; q / out / lse rows
 // come from cu_q_lens; partials are 16 rows per KV head.
 // E: element traits (bf16 / fp16).  M: compile-time policy of the mask / score hooks.
-template <int NW, bool UNIFORM, bool RAGGED, typename E, typename M, typename GE>
+// FUSED (plain decode only): the step's append is folded in as in the one-launch kernel below -- the wave whose
+// segment holds a sequence's last tile stores the new token's rows of its KV head and reads them from k_new / v_new.
+template <int NW, bool UNIFORM, bool RAGGED, typename E, typename M, typename GE, bool FUSED = false>
 __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t batch,
     int32_t num_q_heads, int32_t max_blocks, float scale, float* __restrict__ part_o, float* __restrict__ part_lse,
     int32_t* __restrict__ seg_first, int32_t* __restrict__ seg_last, const int32_t* __restrict__ cu_q_lens,
-    int32_t causal, ModArgs mods)
+    int32_t causal, ModArgs mods, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
 {
     constexpr int kD = GE::kD;
     constexpr int kTileKeys = GE::kTileKeys;
     const int32_t window = M::kWindow ? mods.window : 0;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: a scalar
     const int32_t w = blockIdx.x;
     const int32_t kvh = blockIdx.y * NW + wave;
     const int32_t G = num_q_heads / cache.num_kv_heads;
@@ -479,6 +481,24 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : h0 + min(r16, rows - 1));
         const int64_t o_idx = (int64_t)q_row * num_q_heads + h;
         a.table = block_table + (int64_t)s * max_blocks;
+        if constexpr (FUSED) {
+            a.new_pos = -1;
+            if (t_end == nt) {                               // this segment ends the sequence: it holds the new token
+                const int64_t new_row = ((int64_t)s * cache.num_kv_heads + kvh) * kD * 2;
+                a.knew = reinterpret_cast<const char*>(k_new) + new_row;
+                a.vnew = reinterpret_cast<const char*>(v_new) + new_row;
+                a.new_pos = len - 1;
+                constexpr int kPieces = kD / 8;
+                if (blockIdx.z == 0 && lane < 2 * kPieces) {
+                    const bool is_v = lane >= kPieces;
+                    const int piece = lane - (is_v ? kPieces : 0);
+                    const int64_t page = a.table[a.new_pos >> a.log2_page];
+                    const int64_t slot = page * a.page_bytes + (int64_t)(a.new_pos & a.pmask) * a.token_bytes + piece * 16;
+                    char* dst = const_cast<char*>(is_v ? a.vbase : a.kbase) + slot;
+                    *reinterpret_cast<uint4*>(dst) = load16((is_v ? a.vnew : a.knew) + piece * 16);
+                }
+            }
+        }
 
         // Q as the B operand of S^T = K Q^T: lane%16 = head, contraction slot 8*quad + e of step ks <-> element
         // 32*ks + 8*quad + e of head_dim -- the same element order the K loads use.
@@ -498,18 +518,18 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 
         // two tiles in registers: while one is computed the other's loads are in flight
         Tile<GE> ta, tb;
-        load_tile<UNIFORM, M>(ta, a, c0, c1);
+        load_tile<UNIFORM, M, GE, FUSED>(ta, a, c0, c1);
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
             // The waves of a workgroup (adjacent KV heads) meet before every tile load, so that together they request whole
             // token rows of the same pages at the same time: DRAM sees long contiguous runs instead of the 256-byte
             // head slices of waves that have drifted apart (measured: 76.2 % -> 78.6 % of HBM peak at head_dim 128).
             if (NW > 1) __builtin_amdgcn_s_barrier();
-            if (t1 < c1) load_tile<UNIFORM, M>(tb, a, t1, c1);
+            if (t1 < c1) load_tile<UNIFORM, M, GE, FUSED>(tb, a, t1, c1);
             compute_tile<RAGGED, E, M, GE>(st, ta, qf, sc, t0, lim, mask_from, quad, rm);
             if (t1 >= c1) break;
             if (NW > 1) __builtin_amdgcn_s_barrier();
-            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M>(ta, a, t1 + kTileKeys, c1);
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M, GE, FUSED>(ta, a, t1 + kTileKeys, c1);
             compute_tile<RAGGED, E, M, GE>(st, tb, qf, sc, t1, lim, mask_from, quad, rm);
         }
 
@@ -591,7 +611,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
 
     const int32_t window = M::kWindow ? mods.window : 0;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: a scalar
     const int32_t s = blockIdx.x;
     const int32_t kvh = blockIdx.y;
     const int32_t G = num_q_heads / cache.num_kv_heads;
@@ -772,11 +792,14 @@ void launch_nw(const AttnArgs& a, hipStream_t stream)
     const bool uniform = a.cache.page_size >= 16;
     auto kern = a.cu_q_lens ? (uniform ? paged_decode_mfma_kernel<NW, true, true, E, M, GE>
                                        : paged_decode_mfma_kernel<NW, false, true, E, M, GE>)
+                : a.k_new   ? (uniform ? paged_decode_mfma_kernel<NW, true, false, E, M, GE, true>
+                                       : paged_decode_mfma_kernel<NW, false, false, E, M, GE, true>)
                             : (uniform ? paged_decode_mfma_kernel<NW, true, false, E, M, GE>
                                        : paged_decode_mfma_kernel<NW, false, false, E, M, GE>);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                        a.block_table, a.seq_lens, a.batch, a.num_q_heads, a.max_blocks, a.scale, a.part_o,
-                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal, a.mods);
+                       a.part_lse, a.seg_first, a.seg_last, a.cu_q_lens, a.causal, a.mods,
+                       (const uint16_t*)(a.cu_q_lens ? nullptr : a.k_new), (const uint16_t*)(a.cu_q_lens ? nullptr : a.v_new));
 }
 
 template <typename E, typename M, typename GE>

@@ -248,14 +248,47 @@ def test_decode_step_is_the_append_followed_by_decode(pa, oracle, shape, route, 
         assert torch.equal(w.k_cache.view(view), k_pair.view(view)) and torch.equal(w.v_cache.view(view), v_pair.view(view))
         assert torch.equal(out.view(view), out_pair.view(view)), "out differs from the pair of calls"
         assert torch.equal(lse, lse_pair)
-        if d not in (64, 128, 256) or dtype == torch.float32:
-            assert launches <= 2, "portable kernel: the append runs inside it; at most a merge follows"
-        elif route == 1:
+        # the append runs inside the decode kernel on every route: at most a merge follows
+        assert launches <= 2
+        if route == 1 and d in (64, 128, 256) and dtype != torch.float32:
             assert launches == 1, "the step on the one-launch kernel is a single launch"
     finally:
         binding.pa_profile_enable(False)
         binding.pa_profile_reset()
         binding.pa_set_option("decode_short", 0)
+
+
+@pytest.mark.parametrize("own_kernel", [0, 1])
+def test_decode_step_on_the_tile_stream_with_and_without_an_append_kernel(pa, own_kernel):
+    """The tile stream performs the step's append inside the decode kernel (the wave that holds a sequence's last
+    tile) or, with option step_append_kernel, in a kernel of its own: same pools, same outputs, bit for bit, as
+    the pair of calls; 20 heads per KV head (two grid slices) and ragged tails included."""
+    from paper_2506_07311_amd import binding
+    for lens, Hq, Hkv, d, P in [([5000, 77, 2049, 1, 4096], 32, 8, 128, 16), ([3000, 31, 1500], 40, 2, 128, 4),
+                                ([2500, 640], 16, 4, 256, 64), ([2500, 640, 7], 8, 8, 64, 16)]:
+        w = W.make_workload("t", seq_lens=lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=P,
+                            dtype=torch.bfloat16, seed=41, device=DEV)
+        k0, v0 = w.k_cache.clone(), w.v_cache.clone()
+        out_pair, lse_pair = parity.gpu_step(pa, w)
+        k_pair, v_pair = w.k_cache.clone(), w.v_cache.clone()
+        w.k_cache.copy_(k0)
+        w.v_cache.copy_(v0)
+        binding.pa_set_option("step_append_kernel", own_kernel)
+        binding.pa_set_option("decode_short", -1)
+        binding.pa_profile_reset()
+        binding.pa_profile_enable(True)
+        try:
+            out, lse = parity.gpu_step(pa, w, step_call=True)
+            n_append = binding.pa_profile_read("paged_kv_append_last_kernel")[0]
+        finally:
+            binding.pa_profile_enable(False)
+            binding.pa_profile_reset()
+            binding.pa_set_option("step_append_kernel", 0)
+            binding.pa_set_option("decode_short", 0)
+        assert n_append == own_kernel
+        assert torch.equal(w.k_cache.view(torch.int16), k_pair.view(torch.int16))
+        assert torch.equal(w.v_cache.view(torch.int16), v_pair.view(torch.int16))
+        assert torch.equal(out.view(torch.int16), out_pair.view(torch.int16)) and torch.equal(lse, lse_pair)
 
 
 def test_decode_step_with_an_empty_sequence(pa):
