@@ -452,9 +452,10 @@ def main():
             pstep()
         torch.cuda.synchronize()
         binding.pa_profile_reset()
-        binding.pa_profile_enable(True)
-        psec = time_steps(torch, pstep, max(3, args.steps // 2), 0)
+        binding.pa_profile_enable(True)             # kernel durations: a pass with the per-kernel events ...
+        time_steps(torch, pstep, max(3, args.steps // 2), 0)
         binding.pa_profile_enable(False)
+        psec = time_steps(torch, pstep, max(3, args.steps // 2), 0)   # ... step time: the same steps without them
         S = wp.max_seq_len
         flops = 4 * wp.batch * wp.num_q_heads * wp.head_dim * S * (S + 1) // 2
         pk = None
