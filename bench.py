@@ -87,6 +87,8 @@ def parse():
     ap.add_argument("--step", choices=["fused", "pair"], default="fused",
                     help="decode workloads: one paged_decode_step call per step (the append happens inside; default) "
                          "or the pair paged_kv_append + paged_attention_decode")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library option set through pa_set_option before the run (repeatable), e.g. decode_short=-1")
     ap.add_argument("--launch", choices=["direct", "graph"], default="direct",
                     help="graph: capture one step (append + attention + merge) in a HIP graph and replay it; for the "
                          "small workloads, whose step is shorter than the host's launch overhead")
@@ -233,6 +235,9 @@ def main():
     from paper_2506_07311_amd import binding, workloads as W
 
     pa.load_library()
+    for item in args.option:
+        name, _, value = item.partition("=")
+        binding.pa_set_option(name, int(value))
     dev = "cuda:0"
     cfg, P, ctx = WORKLOADS[args.workload]
     if args.workload == "page_manager_serving":
@@ -366,6 +371,7 @@ def main():
                    "page_size": w.page_size, "pool_pages": w.num_pages,
                    "step": "paged_decode_step: append + attention (+ merge) in one call" if fused
                    else "append + attention (+ merge)",
+                   **({"options": args.option} if args.option else {}),
                    "launch": args.launch, "cache": f"cold ({len(pools)} pool copies)" if args.cold else "warm",
                    **({"window": args.window} if args.window else {}),
                    **({"alibi": True} if args.alibi else {})},
