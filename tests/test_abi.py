@@ -115,7 +115,21 @@ def test_host_validation_rejects_before_launch(lib):
     d16 = _desc(dtype=2)
     assert lib.paged_attention_decode(ctypes.byref(d16), p, p, null, p, p, i32(0), i32(32), i32(4), i32(64), f, ws,
                                       big, null) == 0
+    # step call: missing or misaligned new rows, the decode checks behind them, batch == 0 no-op
+    step = lambda kn, vn, batch=2, hq=32, wsb=big, mods=null: lib.paged_decode_step(
+        ctypes.byref(d), kn, vn, p, p, null, p, p, i32(batch), i32(hq), i32(4), i32(64), f, mods, ws, wsb, null)
+    assert step(null, p) == 1 and step(p, null) == 1
+    assert step(ctypes.c_void_p(0x4008), p) == 2
+    assert step(p, p, hq=12) == 1
+    assert step(p, p, wsb=ctypes.c_size_t(16)) == 3
+    assert step(null, null, batch=0) == 0
+    m = binding._Mods(-1, 0.0, None, None, 0)
+    assert step(p, p, mods=ctypes.byref(m)) == 1
     # options
+    for knob, bad in ((b"decode_short", 2), (b"decode_short", -2), (b"step_append_kernel", 2), (b"no_small_q_route", 3)):
+        assert lib.pa_set_option(knob, ctypes.c_int64(bad)) == 1
+    assert lib.pa_set_option(b"decode_short", ctypes.c_int64(-1)) == 0
+    assert lib.pa_set_option(b"decode_short", ctypes.c_int64(0)) == 0
     assert lib.pa_set_option(b"no_such_knob", ctypes.c_int64(1)) == 1
     assert lib.pa_set_option(b"decode_chunk_tokens", ctypes.c_int64(0)) == 0
 
