@@ -82,11 +82,15 @@ struct Addr {
     const char* knew;
     const char* vnew;
     int32_t new_pos;
+    // PRE (a wave that knows its whole key range up front): lane i holds block-table entry ids_base + i, so a
+    // tile's page id is a lane read instead of a dependent load in front of the tile's row loads
+    int32_t ids;
+    int32_t ids_base;
 };
 
 // Issue the 16 loads of the tile that starts at key `t0`.  Keys at or beyond `c1` are clamped to the last
 // valid key, so every address is a live slot; their scores are masked by the caller.
-template <bool UNIFORM, typename M, typename GE, bool FUSED = false>
+template <bool UNIFORM, typename M, typename GE, bool FUSED = false, bool PRE = false>
 __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0, int32_t c1)
 {
     constexpr int kTileKeys = GE::kTileKeys;
@@ -101,7 +105,12 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
 #pragma unroll
             for (int mt = 0; mt < GE::kBlocks; ++mt) {
                 const int32_t kb = t0 + 16 * mt;
-                const int64_t page = __builtin_amdgcn_readfirstlane(a.table[kb >> a.log2_page]);
+                int64_t page;
+                const int32_t rel = (kb >> a.log2_page) - a.ids_base;    // wave-uniform
+                if (PRE && rel < 64)
+                    page = __builtin_amdgcn_readlane(a.ids, rel);
+                else
+                    page = __builtin_amdgcn_readfirstlane(a.table[kb >> a.log2_page]);
                 const int64_t blk = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
                 const char* kp = a.kbase + blk;
                 const char* vp = a.vbase + blk;
@@ -415,6 +424,8 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
     a.knew = nullptr;
     a.vnew = nullptr;
     a.new_pos = -1;
+    a.ids = 0;
+    a.ids_base = 0;
     a.kbase = reinterpret_cast<const char*>(cache.k) + (int64_t)kvh * cache.head_stride * 2;
     a.vbase = reinterpret_cast<const char*>(cache.v) + (int64_t)kvh * cache.head_stride * 2;
     a.page_bytes = cache.page_stride * 2;
@@ -653,6 +664,10 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
         for (int i = 0; i < 4; ++i)
             a.voff[i] = (uint32_t)((4 * quad + i) * a.token_bytes + (r16 & GE::kPieceMask) * 16);
         a.table = block_table + (int64_t)s * max_blocks;
+        // the block-table entries of this wave's key range, one per lane (ranges of more than 64 pages fall back
+        // to loads for the part beyond)
+        a.ids_base = c0 >> a.log2_page;
+        a.ids = a.table[min(a.ids_base + lane, (c1 - 1) >> a.log2_page)];
         a.knew = nullptr;
         a.vnew = nullptr;
         a.new_pos = -1;
@@ -706,13 +721,13 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
             if (r16 < rows) qf[ks] = *reinterpret_cast<const uint4*>(q + q_idx * kD + 32 * ks + 8 * quad);
         }
         Tile<GE> ta, tb;
-        load_tile<UNIFORM, M, GE, FUSED>(ta, a, c0, c1);
+        load_tile<UNIFORM, M, GE, FUSED, true>(ta, a, c0, c1);
         for (int32_t t0 = c0; t0 < c1; t0 += 2 * kTileKeys) {
             const int32_t t1 = t0 + kTileKeys;
-            if (t1 < c1) load_tile<UNIFORM, M, GE, FUSED>(tb, a, t1, c1);
+            if (t1 < c1) load_tile<UNIFORM, M, GE, FUSED, true>(tb, a, t1, c1);
             compute_tile<false, E, M, GE>(st, ta, qf, sc, t0, c1, c1, quad, rm);
             if (t1 >= c1) break;
-            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M, GE, FUSED>(ta, a, t1 + kTileKeys, c1);
+            if (t1 + kTileKeys < c1) load_tile<UNIFORM, M, GE, FUSED, true>(ta, a, t1 + kTileKeys, c1);
             compute_tile<false, E, M, GE>(st, tb, qf, sc, t1, c1, c1, quad, rm);
         }
     }
