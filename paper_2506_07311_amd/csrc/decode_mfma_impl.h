@@ -22,6 +22,10 @@
 // ones whose probabilities the S^T accumulator layout already left in the matching lanes.
 // Softmax statistics are lane-local per head (lane%16 = head in both accumulators); the only cross-lane
 // traffic is a 4-way max per tile and one 4-way sum at the end.
+// Two kernels share the tile code: paged_decode_mfma_kernel (the batch's context as one stream of tiles cut evenly
+// over the workgroups, partials merged by a second launch) and paged_decode_short_kernel (short contexts: one
+// workgroup per sequence and KV head, its waves split the context and merge through LDS, one launch).  Both exist
+// in a variant that also performs the decode step's append of one new token per sequence (FUSED).
 #pragma once
 
 #include "common.h"
