@@ -383,6 +383,7 @@ def main():
     }
     if args.launch != "graph":
         result["kernel_timing"] = kernel_timing
+        result["us_per_step_with_kernel_events"] = round(sec_events * 1e6, 2)
     if "step" in STEP_STATS:
         result["step_us_stats"] = STEP_STATS["step"]
     G = w.num_q_heads // w.num_kv_heads
