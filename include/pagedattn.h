@@ -46,7 +46,7 @@ typedef enum {
 typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1, PA_DTYPE_F16 = 2 } pa_dtype;
 
 /*
- * The two global pools (Sec. III-B: "two global buffers store K and V pages").
+ * K and V live in two global pools of pages (Sec. III-B, Paged KV-Manager).
  * Algorithm 1 addresses them by the flat slot p = page * P + o; the literal
  * layout is therefore token-major [num_pages, page_size, num_kv_heads, head_dim]
  * with page_stride = P*Hkv*d, token_stride = Hkv*d, head_stride = d.  Strides
@@ -98,7 +98,11 @@ pa_status paged_kv_gather(const pa_kv_cache_desc* cache, void* out_k, void* out_
  * Upper bound (pure host function) of the split-KV workspace the two attention
  * entry points need for these sizes: fp32 partial outputs and (max, sum)
  * statistics per (query, head, context chunk).  Pass total_q = batch for
- * decode.  Always a multiple of 256; never 0.
+ * decode (the bound then covers the decode entry points only; a prefill call
+ * with total_q <= batch that is not plain decode keeps its few-query sequences
+ * on the prefill kernel when the workspace has no room for their partials).
+ * Always a multiple of 256; never 0.  Depends on the calling thread's
+ * pa_set_option knobs and on the current device's compute-unit count.
  */
 size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim,
                                        int32_t total_q, int32_t max_seq_len);
@@ -215,8 +219,8 @@ pa_status pa_debug_check(const pa_kv_cache_desc* cache, const int32_t* block_tab
 const char* pa_status_string(pa_status status);
 
 /*
- * Tuning knobs (host state, process-wide, not thread-safe against concurrent
- * launches).  name is one of
+ * Tuning knobs, kept per host thread: they shape the calls (and the workspace
+ * bound) of the thread that set them and nothing else.  name is one of
  *   "decode_chunk_tokens"  context tokens per split-KV workgroup of the portable kernel (0 = heuristic)
  *   "decode_workgroups"    workgroups the MFMA decode kernel spreads the batch's key tiles over
  *                          (0 = one per compute unit)
@@ -272,7 +276,11 @@ pa_status pa_profile_read(const char* kernel_prefix, int32_t* launches, double* 
  * a pool (the ring's reuse is ordered by events on that stream); a page that
  * was released may be handed out again at once, which is safe for the same
  * reason.  Entries of unmapped blocks are -1.  pa_pool_destroy waits for the
- * device to go idle when a device table is attached.
+ * device to go idle when a device table is attached.  A call changes the host
+ * bookkeeping first and enqueues the row copy last: if that copy fails
+ * (PA_ERR_HIP) the bookkeeping stands, the device row is stale for the
+ * changed entries, and the next call that changes the same sequence's row
+ * delivers them together with its own.
  * ---------------------------------------------------------------------------
  */
 typedef struct pa_pool pa_pool;

@@ -21,7 +21,8 @@ struct Options {
     int64_t step_append_kernel = 0;   // 1 = paged_decode_step on the tile stream appends with a kernel of its own
                                       // (0: every decode kernel performs the step's append itself)
     int64_t decode_short = 0;      // 0 = heuristic, 1 = whenever the one-launch kernel supports the call, -1 = never
-} g_opt;
+};
+thread_local Options g_opt;       // per host thread: a thread's knobs shape only the calls it makes itself
 
 // Compute units of the current device (the tile-stream decode launches one workgroup per CU by default).
 int32_t device_cus()
@@ -61,6 +62,8 @@ inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
 
 bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 
+}  // namespace
+
 pa_status check_cache(const pa_kv_cache_desc* c)
 {
     if (!c || !c->k_cache || !c->v_cache) return PA_ERR_INVALID_ARG;
@@ -74,6 +77,8 @@ pa_status check_cache(const pa_kv_cache_desc* c)
     if (((uintptr_t)c->k_cache | (uintptr_t)c->v_cache) & 15) return PA_ERR_UNSUPPORTED;
     return PA_OK;
 }
+
+namespace {
 
 int32_t nsplit_bound(int32_t max_seq_len)
 {
@@ -208,15 +213,46 @@ size_t stream_workspace_bytes(int32_t batch, int32_t hq, int32_t d, int32_t wgs)
 }
 
 // Workgroups of the decode kernel when it runs the few-query sequences of a prefill call; its partials there take
-// 16 rows per KV head, so the count is kept at one per compute unit of the largest part.
+// 16 rows per KV head, so the count is held to kSmallRouteMaxWGs and to kSmallRouteMaxHeadWGs / Hkv (a workgroup
+// holds up to eight KV heads: about one workgroup per compute unit either way).
 constexpr int32_t kSmallRouteMaxWGs = 256;
+constexpr int32_t kSmallRouteMaxHeadWGs = 2048;
 
-size_t small_route_workspace_bytes(int32_t batch, int32_t hq, int32_t d)
+int32_t small_route_wgs_cap(int32_t num_kv_heads)
 {
-    // at most hq KV heads (group size 1), 16 rows each
-    const size_t rows = ((size_t)kSmallRouteMaxWGs + batch) * hq * 16;
+    const int32_t by_heads = kSmallRouteMaxHeadWGs / num_kv_heads;
+    return by_heads < 1 ? 1 : by_heads < kSmallRouteMaxWGs ? by_heads : kSmallRouteMaxWGs;
+}
+
+size_t small_route_bytes(int32_t wgs, int32_t batch, int32_t num_kv_heads, int32_t d)
+{
+    const size_t rows = ((size_t)wgs + batch) * num_kv_heads * 16;
     return align256(rows * d * sizeof(float)) + align256(rows * sizeof(float)) +
            2 * align256((size_t)batch * sizeof(int32_t));
+}
+
+// Bound of small_route_bytes over every KV-head count that divides hq: wgs * Hkv <= kSmallRouteMaxHeadWGs, Hkv <= hq.
+size_t small_route_workspace_bytes(int32_t batch, int32_t hq, int32_t d)
+{
+    const size_t rows = ((size_t)kSmallRouteMaxHeadWGs + (size_t)batch * hq) * 16;
+    return align256(rows * d * sizeof(float)) + align256(rows * sizeof(float)) +
+           2 * align256((size_t)batch * sizeof(int32_t));
+}
+
+// Largest tile-stream grid plan_stream_wgs can choose for a call with hq query heads: head_groups >= 1 and
+// Hkv * slices >= hq / 16.
+int32_t stream_wgs_bound(int32_t batch, int32_t hq, int32_t max_seq_len)
+{
+    int64_t n = g_opt.decode_workgroups;
+    if (n <= 0) {
+        n = device_cus();
+        const int64_t by_waves = 64LL * device_cus() / hq;
+        if (by_waves > n) n = by_waves;
+    }
+    const int64_t tiles = (int64_t)batch * ((max_seq_len + 15) / 16);
+    if (n > tiles / 2) n = tiles / 2;
+    if (n > kMaxDecodeWGs) n = kMaxDecodeWGs;
+    return n < 1 ? 1 : (int32_t)n;
 }
 
 size_t part_o_bytes(int64_t rows, int32_t hq, int32_t d, int32_t nsplit)
@@ -229,11 +265,19 @@ size_t part_lse_bytes(int64_t rows, int32_t hq, int32_t nsplit)
     return align256((size_t)rows * hq * nsplit * sizeof(float));
 }
 
+// The workspace of a call.  The public entry points promise the bound paged_attention_workspace_bytes() and are
+// checked against it (bound = true); bound = false checks against what the call's plan really uses.
+struct Workspace {
+    void* ptr;
+    size_t bytes;
+    bool bound;
+};
+
 pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
                         const int32_t* cu_q_lens, int32_t total_q, int32_t max_q_len, const int32_t* block_table,
                         const int32_t* seq_lens, int32_t batch, int32_t num_q_heads, int32_t max_blocks,
-                        int32_t max_seq_len, float scale, int32_t causal, const pa_attn_mods* mods, void* workspace,
-                        size_t workspace_bytes, void* stream, bool decode, const void* k_new = nullptr,
+                        int32_t max_seq_len, float scale, int32_t causal, const pa_attn_mods* mods,
+                        const Workspace& ws, void* stream, bool decode, const void* k_new = nullptr,
                         const void* v_new = nullptr)
 {
     pa_status st = check_cache(cache);
@@ -255,9 +299,14 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         m.doc_ids = mods->doc_ids;
         m.doc_stride = mods->doc_ids ? mods->doc_stride : 0;
     }
-    const size_t need = paged_attention_workspace_bytes(batch, num_q_heads, cache->head_dim, total_q, max_seq_len);
-    if (!workspace || workspace_bytes < need) return PA_ERR_WORKSPACE_TOO_SMALL;
-    if ((uintptr_t)workspace & 255) return PA_ERR_INVALID_ARG;
+    if (ws.bound) {
+        const size_t need = paged_attention_workspace_bytes(batch, num_q_heads, cache->head_dim, total_q, max_seq_len);
+        if (!ws.ptr || ws.bytes < need) return PA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    if ((uintptr_t)ws.ptr & 255) return PA_ERR_INVALID_ARG;
+    // a prefill call whose every sequence brings exactly one query is a decode call (its causal bound is the length
+    // mask: the query sits at the last position)
+    if (!decode && max_q_len == 1 && total_q == batch) decode = true;
 
     AttnArgs a;
     a.cache = make_view(cache);
@@ -278,10 +327,8 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.causal = causal ? 1 : 0;
     a.plan.chunk = max_seq_len > 0 ? max_seq_len : 1;
     a.plan.nsplit = 1;
-    if (decode) a.plan = plan_decode(batch, max_seq_len, cache->page_size);
-    a.part_o = reinterpret_cast<float*>(workspace);
-    a.part_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) +
-                                          part_o_bytes(total_q, num_q_heads, cache->head_dim, a.plan.nsplit));
+    a.part_o = nullptr;
+    a.part_lse = nullptr;
     a.stream_split = 0;
     a.num_wgs = 0;
     a.seg_first = a.seg_last = nullptr;
@@ -291,35 +338,47 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.k_new = k_new;
     a.v_new = v_new;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    char* const base = reinterpret_cast<char*>(ws.ptr);
+    const int32_t d = cache->head_dim;
+
+    // tile-stream partials of the decode kernel at `p`: outputs, LSEs, first / last workgroup per sequence
+    auto place_stream = [&](AttnArgs& b, char* p, size_t rows) {
+        b.part_o = reinterpret_cast<float*>(p);
+        p += align256(rows * d * sizeof(float));
+        b.part_lse = reinterpret_cast<float*>(p);
+        p += align256(rows * sizeof(float));
+        b.seg_first = reinterpret_cast<int32_t*>(p);
+        p += align256((size_t)batch * sizeof(int32_t));
+        b.seg_last = reinterpret_cast<int32_t*>(p);
+    };
 
     if (decode) {
         if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a) &&
             (g_opt.decode_short > 0 || short_decode_pays(a)))
             return launch_decode_short(a, s);              // with k_new / v_new: the append happens in this launch
         const bool stream_route = !g_opt.force_generic && decode_mfma_supported(a);
-        if (a.k_new && stream_route && g_opt.step_append_kernel) {   // append as a launch of its own, then attend
-            st = launch_kv_append_last(cache, k_new, v_new, seq_lens, block_table, batch, max_blocks, s);
-            if (st != PA_OK) return st;
-            a.k_new = a.v_new = nullptr;
-        }                                                  // (otherwise every decode kernel appends by itself)
         if (stream_route) {
-            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, d);
             a.stream_split = 1;
             a.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads,
                                         (num_q_heads / cache->num_kv_heads + 15) / 16);
-            const size_t parts = (size_t)a.num_wgs + batch;
-            char* p = reinterpret_cast<char*>(workspace);
-            a.part_o = reinterpret_cast<float*>(p);
-            p += align256(parts * num_q_heads * cache->head_dim * sizeof(float));
-            a.part_lse = reinterpret_cast<float*>(p);
-            p += align256(parts * num_q_heads * sizeof(float));
-            a.seg_first = reinterpret_cast<int32_t*>(p);
-            p += align256((size_t)batch * sizeof(int32_t));
-            a.seg_last = reinterpret_cast<int32_t*>(p);
+            if (ws.bytes < stream_workspace_bytes(batch, num_q_heads, d, a.num_wgs)) return PA_ERR_WORKSPACE_TOO_SMALL;
+            place_stream(a, base, ((size_t)a.num_wgs + batch) * num_q_heads);
+            if (a.k_new && g_opt.step_append_kernel) {     // append as a launch of its own, then attend
+                st = launch_kv_append_last(cache, k_new, v_new, seq_lens, block_table, batch, max_blocks, s);
+                if (st != PA_OK) return st;
+                a.k_new = a.v_new = nullptr;
+            }                                              // (otherwise the decode kernel appends by itself)
             st = launch_decode_mfma(a, s);
             if (st != PA_OK) return st;
             return launch_merge(a, s);
         }
+        a.plan = plan_decode(batch, max_seq_len, cache->page_size);
+        const size_t po = part_o_bytes(batch, num_q_heads, d, a.plan.nsplit);
+        if (a.plan.nsplit > 1 && ws.bytes < po + part_lse_bytes(batch, num_q_heads, a.plan.nsplit))
+            return PA_ERR_WORKSPACE_TOO_SMALL;
+        a.part_o = reinterpret_cast<float*>(base);
+        a.part_lse = reinterpret_cast<float*>(base + po);
         st = launch_attention_generic(a, s);
         if (st != PA_OK) return st;
         if (a.plan.nsplit > 1) st = launch_merge(a, s);
@@ -332,36 +391,40 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
         // host only skips a launch that cannot find work.
         const int32_t G = num_q_heads / cache->num_kv_heads;
         const bool uniform_q = (int64_t)batch * max_q_len == total_q;      // every sequence has max_q_len queries
-        const bool may_have_small = !g_opt.no_small_q_route && decode_mfma_supported(a) && G <= 16 &&
-                                    !(uniform_q && (int64_t)max_q_len * G > 16);
+        bool may_have_small = !g_opt.no_small_q_route && decode_mfma_supported(a) && G <= 16 &&
+                              !(uniform_q && (int64_t)max_q_len * G > 16);
+        const SplitPlan pp = plan_prefill(batch, num_q_heads, prefill_mfma_log2_pack(num_q_heads, cache->num_kv_heads),
+                                          total_q, max_seq_len, cache->page_size);
+        const size_t split_bytes =
+            pp.nsplit > 1 ? part_o_bytes(total_q, num_q_heads, d, pp.nsplit) + part_lse_bytes(total_q, num_q_heads, pp.nsplit)
+                          : 0;
+        int32_t small_wgs = 0;
+        if (may_have_small) {
+            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, d);
+            small_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads, 1);
+            const int32_t cap = small_route_wgs_cap(cache->num_kv_heads);
+            if (small_wgs > cap) small_wgs = cap;
+            // The route is an optimisation: a workspace without room for its partials (a call with total_q == batch
+            // is promised the decode bound only) keeps those sequences on the prefill kernel.
+            if (ws.bytes < split_bytes + small_route_bytes(small_wgs, batch, cache->num_kv_heads, d))
+                may_have_small = false;
+        }
         const bool may_have_large = (int64_t)max_q_len * G > 16 || !may_have_small;
-        char* p = reinterpret_cast<char*>(workspace);
+        if (ws.bytes < split_bytes) return PA_ERR_WORKSPACE_TOO_SMALL;
         if (may_have_large) {
             AttnArgs b = a;
             b.skip_small = may_have_small ? 1 : 0;
-            b.plan = plan_prefill(batch, num_q_heads, prefill_mfma_log2_pack(num_q_heads, cache->num_kv_heads),
-                                  total_q, max_seq_len, cache->page_size);
-            b.part_o = reinterpret_cast<float*>(p);
-            b.part_lse = reinterpret_cast<float*>(p + part_o_bytes(total_q, num_q_heads, cache->head_dim, b.plan.nsplit));
+            b.plan = pp;
+            b.part_o = reinterpret_cast<float*>(base);
+            b.part_lse = reinterpret_cast<float*>(base + part_o_bytes(total_q, num_q_heads, d, pp.nsplit));
             st = launch_prefill_mfma(b, s);
             if (st != PA_OK) return st;
         }
         if (may_have_small) {
-            const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
-            if (np > 1) p += part_o_bytes(total_q, num_q_heads, cache->head_dim, np) + part_lse_bytes(total_q, num_q_heads, np);
             AttnArgs b = a;
-            const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, cache->head_dim);
             b.stream_split = 1;
-            b.num_wgs = plan_stream_wgs(batch, max_seq_len, head_groups, cache->num_kv_heads, 1);
-            if (b.num_wgs > kSmallRouteMaxWGs) b.num_wgs = kSmallRouteMaxWGs;
-            const size_t rows = ((size_t)b.num_wgs + batch) * cache->num_kv_heads * 16;
-            b.part_o = reinterpret_cast<float*>(p);
-            p += align256(rows * cache->head_dim * sizeof(float));
-            b.part_lse = reinterpret_cast<float*>(p);
-            p += align256(rows * sizeof(float));
-            b.seg_first = reinterpret_cast<int32_t*>(p);
-            p += align256((size_t)batch * sizeof(int32_t));
-            b.seg_last = reinterpret_cast<int32_t*>(p);
+            b.num_wgs = small_wgs;
+            place_stream(b, base + split_bytes, ((size_t)small_wgs + batch) * cache->num_kv_heads * 16);
             st = launch_decode_mfma(b, s);
             if (st != PA_OK) return st;
             st = launch_merge(b, s);
@@ -455,19 +518,19 @@ size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32
                                        int32_t max_seq_len)
 {
     if (batch <= 0 || num_q_heads <= 0 || head_dim <= 0 || total_q <= 0) return 256;
-    // prefill entry point: partials of the context split, when the sizes make it split
+    if (total_q <= batch) {
+        // decode: partials of the portable kernel's chunks, or of the tile stream's workgroups
+        const int32_t ns = nsplit_bound(max_seq_len);
+        const size_t chunked = part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
+        const size_t stream = stream_workspace_bytes(batch, num_q_heads, head_dim,
+                                                     stream_wgs_bound(batch, num_q_heads, max_seq_len));
+        return chunked > stream ? chunked : stream;
+    }
+    // prefill: partials of the context split, when the sizes make it split, and of the few-query route
     const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
-    size_t need = np > 1 ? part_o_bytes(total_q, num_q_heads, head_dim, np) + part_lse_bytes(total_q, num_q_heads, np)
-                         : 0;
-    need += small_route_workspace_bytes(batch, num_q_heads, head_dim);
-    if (total_q > batch) return need;
-    // decode entry point
-    const int32_t ns = nsplit_bound(max_seq_len);
-    const size_t chunked = part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
-    const size_t stream = stream_workspace_bytes(batch, num_q_heads, head_dim, kMaxDecodeWGs);
-    if (chunked > need) need = chunked;
-    if (stream > need) need = stream;
-    return need;
+    const size_t split = np > 1 ? part_o_bytes(total_q, num_q_heads, head_dim, np) + part_lse_bytes(total_q, num_q_heads, np)
+                                : 0;
+    return split + small_route_workspace_bytes(batch, num_q_heads, head_dim);
 }
 
 pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -476,7 +539,7 @@ pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, v
                                  void* workspace, size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
-                         max_seq_len, scale, 0, nullptr, workspace, workspace_bytes, stream, true);
+                         max_seq_len, scale, 0, nullptr, Workspace{workspace, workspace_bytes, true}, stream, true);
 }
 
 pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -485,7 +548,7 @@ pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* 
                                      const pa_attn_mods* mods, void* workspace, size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
-                         max_seq_len, scale, 0, mods, workspace, workspace_bytes, stream, true);
+                         max_seq_len, scale, 0, mods, Workspace{workspace, workspace_bytes, true}, stream, true);
 }
 
 pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
@@ -496,7 +559,7 @@ pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, co
     if (batch > 0 && (!k_new || !v_new)) return PA_ERR_INVALID_ARG;
     if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return PA_ERR_UNSUPPORTED;
     return run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads, max_blocks,
-                         max_seq_len, scale, 0, mods, workspace, workspace_bytes, stream, true, k_new, v_new);
+                         max_seq_len, scale, 0, mods, Workspace{workspace, workspace_bytes, true}, stream, true, k_new, v_new);
 }
 
 pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -507,7 +570,7 @@ pa_status paged_attention_prefill_mod(const pa_kv_cache_desc* cache, const void*
                                       size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, cu_q_lens, total_q, max_q_len, block_table, seq_lens, batch, num_q_heads,
-                         max_blocks, max_seq_len, scale, causal, mods, workspace, workspace_bytes, stream, false);
+                         max_blocks, max_seq_len, scale, causal, mods, Workspace{workspace, workspace_bytes, true}, stream, false);
 }
 
 pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
@@ -517,7 +580,7 @@ pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, 
                                   int32_t causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     return run_attention(cache, q, out, lse, cu_q_lens, total_q, max_q_len, block_table, seq_lens, batch, num_q_heads,
-                         max_blocks, max_seq_len, scale, causal, nullptr, workspace, workspace_bytes, stream, false);
+                         max_blocks, max_seq_len, scale, causal, nullptr, Workspace{workspace, workspace_bytes, true}, stream, false);
 }
 
 const char* pa_status_string(pa_status status)

@@ -1,5 +1,6 @@
 // Portable paged attention kernel (VALU, fp32 accumulation) for every shape the MFMA kernels do not
-// cover: fp32 pools, head_dim other than 128, group sizes above 16, document masks.  One workgroup
+// cover: fp32 pools, head_dims other than 64 / 128 / 256, non-positive scales in prefill, head_dim 256 prefill
+// with pages of fewer than 16 tokens; it also serves as an independent GPU cross-check.  One workgroup
 // computes one (query row, query head, context chunk) by flash-style tiles of 1024 keys:
 //   scores  s_j = scale * <q, K[j]>            one key per thread, 16-byte loads along head_dim
 //   mask    keys >= n_keys are never touched   (length mask / causal bound, Sec. III-B)

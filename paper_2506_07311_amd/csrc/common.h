@@ -65,6 +65,10 @@ struct ProfileScope {
     ~ProfileScope() { profile_end(s); }
 };
 
+// Host-checkable properties of a pool descriptor (pointers, dtype, sizes, strides, alignment), shared by every
+// entry point that takes one.
+pa_status check_cache(const pa_kv_cache_desc* c);
+
 inline pa_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? PA_OK : PA_ERR_HIP;

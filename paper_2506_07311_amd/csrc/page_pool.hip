@@ -23,6 +23,9 @@ struct pa_pool {
     int32_t* device_table = nullptr;
     int32_t* host_table = nullptr;          // [max_seqs, max_blocks] host mirror
     std::vector<int32_t> num_blocks;        // per sequence
+    // per sequence: entries [stale_lo, stale_hi) of the device row whose copy failed (PA_ERR_HIP); the next call that
+    // changes the sequence's row copies them again from the mirror together with its own
+    std::vector<int32_t> stale_lo, stale_hi;
     std::atomic<int32_t>* next = nullptr;   // free-stack links
     std::atomic<int32_t>* refs = nullptr;   // per page
     std::atomic<int32_t> fresh{0};          // bump pointer: pages [fresh, num_pages) were never handed out
@@ -92,10 +95,32 @@ void unref_page(pa_pool* p, int32_t page)
     if (p->refs[page].fetch_sub(1, std::memory_order_acq_rel) == 1) push_page(p, page);
 }
 
-// Copy entries [b0, b1) of the sequence's row to the device table.
+pa_status copy_row(pa_pool* p, int32_t seq, int32_t b0, int32_t b1, void* stream);
+
+// Copy entries [b0, b1) of the sequence's row to the device table, together with entries an earlier call failed to
+// deliver.  On PA_ERR_HIP the host mirror is ahead of the device row for the recorded range until a later call for
+// the same sequence succeeds.
 pa_status sync_row(pa_pool* p, int32_t seq, int32_t b0, int32_t b1, void* stream)
 {
-    if (!p->device_table || b1 <= b0) return PA_OK;
+    if (!p->device_table) return PA_OK;
+    if (p->stale_hi[seq] > p->stale_lo[seq]) {
+        const bool own = b1 > b0;                            // the union of this call's entries and the stale ones
+        b0 = own && b0 < p->stale_lo[seq] ? b0 : p->stale_lo[seq];
+        b1 = own && b1 > p->stale_hi[seq] ? b1 : p->stale_hi[seq];
+    }
+    if (b1 <= b0) return PA_OK;
+    const pa_status st = copy_row(p, seq, b0, b1, stream);
+    if (st == PA_OK) {
+        p->stale_lo[seq] = p->stale_hi[seq] = 0;
+    } else {
+        p->stale_lo[seq] = b0;
+        p->stale_hi[seq] = b1;
+    }
+    return st;
+}
+
+pa_status copy_row(pa_pool* p, int32_t seq, int32_t b0, int32_t b1, void* stream)
+{
     const size_t off = (size_t)seq * p->max_blocks + b0;
     const int32_t n = b1 - b0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -147,6 +172,8 @@ pa_status pa_pool_create(pa_pool** out, int32_t num_pages, int32_t page_size, in
     p->host_table = new int32_t[entries];
     for (size_t i = 0; i < entries; ++i) p->host_table[i] = -1;
     p->num_blocks.assign(max_seqs, 0);
+    p->stale_lo.assign(max_seqs, 0);
+    p->stale_hi.assign(max_seqs, 0);
     p->next = new std::atomic<int32_t>[num_pages];
     p->refs = new std::atomic<int32_t>[num_pages];
     for (int32_t i = 0; i < num_pages; ++i) {
@@ -259,7 +286,9 @@ pa_status pa_pool_share_prefix(pa_pool* p, int32_t dst, int32_t src, int32_t pre
 
 pa_status pa_pool_make_writable(pa_pool* p, const pa_kv_cache_desc* cache, int32_t seq, int32_t position, void* stream)
 {
-    if (!seq_ok(p, seq) || position < 0 || !cache || !cache->k_cache || !cache->v_cache) return PA_ERR_INVALID_ARG;
+    if (!seq_ok(p, seq) || position < 0) return PA_ERR_INVALID_ARG;
+    const pa_status desc = pa::check_cache(cache);           // dtype, strides, 16-byte alignment of the pools
+    if (desc != PA_OK) return desc;
     if (cache->page_size != p->page_size || cache->num_pages < p->num_pages) return PA_ERR_INVALID_ARG;
     const int32_t b = position >> p->log2_page;
     if (b >= p->num_blocks[seq]) return PA_ERR_INVALID_ARG;

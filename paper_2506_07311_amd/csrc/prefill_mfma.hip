@@ -18,6 +18,10 @@ bool prefill_mfma_supported(const AttnArgs& a)
     const int32_t d = a.cache.head_dim;
     if (d != 128 && d != 64 && !(d == 256 && a.cache.page_size >= 16)) return false;
     if (!(a.scale > 0.f)) return false;   // the kernel takes the max before scaling
+    // the tile fetch keeps a row's byte offset inside its page (slot, KV head, piece) in 32 bits
+    const int64_t in_page = (int64_t)(a.cache.page_size - 1) * a.cache.token_stride * 2 +
+                            (int64_t)(a.cache.num_kv_heads - 1) * a.cache.head_stride * 2 + 512;
+    if (in_page > 0xffffffffLL) return false;
     return true;
 }
 

@@ -34,8 +34,9 @@
 // same order.  Online softmax runs in the log2 domain; masking (length, causal, ragged rows) is by selection.
 //
 // Softmax weights enter the matrix cores as bf16.  With few keys the individual weights are large and their
-// 2^-9 rounding shows in the output, so query tiles whose context is at most max(kPreciseKeys, len / 8) keys carry
-// the weights as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
+// 2^-9 rounding shows in the output, so query tiles that see few keys -- at most kPreciseKeys, or fewer than
+// kPreciseShare of the harmonic mean of the key counts of all the call's rows (precise_key_bound) -- carry the
+// weights as two bf16 terms (p = hi + lo); over long contexts the rounding averages out.
 #pragma once
 
 #include "prefill_tiles.h"
@@ -104,6 +105,48 @@ __device__ __forceinline__ uint4 lds_frag_tr(const char* lo, const char* hi)
     r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lo));
     r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(hi));
     return __builtin_bit_cast(uint4, r);
+}
+
+// Which rows need two-term weights.  A row that sees n keys carries a weight-rounding error of about
+// 2^-9 * sqrt(sum p^2) ~ 1 / sqrt(n) in absolute terms, and the outputs of a call are judged against the RMS of the
+// whole output tensor, which behaves as 1 / sqrt(H) with H the harmonic mean of n over all rows of the call.  A row
+// whose n is well below H is therefore large compared with the scale it is measured on, whatever its own length:
+// a short sequence batched beside long ones, or the first rows of a long causal prompt.  Every workgroup derives H
+// from the lengths (one lane per sequence; sum over the rows of a causal sequence of 1/n = ln((hi+1/2)/(lo-1/2))
+// for n = lo..hi, capped at the window) -- a few dozen instructions next to loads it needs anyway -- and tiles whose first row
+// sees fewer than kPreciseShare * H keys take the two-term path.  Wave-uniform result.
+constexpr float kPreciseShare = 0.9f;
+
+__device__ __forceinline__ int32_t precise_key_bound(const int32_t* __restrict__ cu_q_lens,
+                                                     const int32_t* __restrict__ seq_lens, int32_t batch,
+                                                     int32_t causal, int32_t window, int lane)
+{
+    float rows = 0.f, inv = 0.f;
+    for (int32_t i = lane; i < batch; i += 64) {
+        const int32_t q_len = cu_q_lens[i + 1] - cu_q_lens[i];
+        const int32_t len = seq_lens[i];
+        if (q_len <= 0 || len <= 0) continue;
+        const int32_t hi = len;                                       // keys of the last row
+        const int32_t lo = causal ? max(len - q_len + 1, 1) : len;    // keys of the first row that sees any
+        const int32_t cap = window > 0 ? (causal ? window : 2 * window - 1) : 0x7fffffff;
+        const int32_t n_rows = causal ? hi - lo + 1 : q_len;
+        rows += (float)n_rows;
+        if (!causal) {
+            inv += (float)q_len / (float)min(len, cap);
+            continue;
+        }
+        const int32_t b = min(hi, cap);
+        if (b >= lo) inv += __builtin_amdgcn_logf(((float)b + 0.5f) / ((float)lo - 0.5f)) * kLn2;
+        const int32_t above = hi - max(lo, cap + 1) + 1;              // rows that see the whole window
+        if (above > 0) inv += (float)above / (float)cap;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        rows += __shfl_xor(rows, o, 64);
+        inv += __shfl_xor(inv, o, 64);
+    }
+    const float h = inv > 0.f ? rows / inv : 0.f;
+    return max(kPreciseKeys, (int32_t)fminf(kPreciseShare * h, 1.0e9f));
 }
 
 // Online-softmax update with the 32 keys of one half tile.  s holds raw scores on entry; the weights are
@@ -311,7 +354,7 @@ __device__ __forceinline__ void prefill_body(
     char* buf0, char* buf1, int32_t* docs0, int32_t* docs1, const CacheView& cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, int32_t batch, int32_t num_tiles, int32_t num_q_heads, int32_t max_blocks,
-    float scale, int32_t causal, const PrefillPlan& plan)
+    float scale, int32_t causal, const PrefillPlan& plan, int32_t precise_keys)
 {
     constexpr int KS = D / 16, T = D / 32;               // steps of a score product, 32-column blocks of O
     constexpr int RB = RowGeo<D>::kRowB;
@@ -352,13 +395,14 @@ __device__ __forceinline__ void prefill_body(
         k_lo = max(len - q_len + (m0 >> lg) - window + 1, 0) & ~(kBN - 1);
         if (!causal) nk_wg = max(min(nk_wg, len - q_len + q_last + window), 0);
     }
-    // Few effective keys mean few, large weights whose 16-bit rounding shows: short contexts and windows, and any
+    // Few effective keys mean few, large weights whose 16-bit rounding shows: rows that see far fewer keys than the
+    // call's rows do on (harmonic) average (precise_keys, see precise_key_bound), short contexts and windows, and any
     // position bias (a steep slope concentrates the weight on a handful of keys however long the context is).
-    // "Few" is relative to the sequence: a row's rounding error falls as 1/sqrt(keys) while the scale its
-    // sequence's outputs are judged on falls with the sequence length, so the bound grows as len / 8 (the rows
-    // below it see at most 1/64 of a causal sequence's tile work).
     // (a document mask can leave a row a handful of keys out of any context)
-    const bool few_keys = nk_wg - k_lo <= max(kPreciseKeys, len >> 3) ||
+    int32_t n_first = len;                                   // keys the tile's first row sees
+    if (causal) n_first = min(len, len - q_len + (m0 >> lg) + 1);
+    if (window > 0) n_first = min(n_first, causal ? window : 2 * window - 1);
+    const bool few_keys = n_first <= precise_keys ||
                           (M::kScore && plan.mods.alibi_slopes != nullptr) || (M::kDoc && plan.mods.doc_ids != nullptr);
     if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
@@ -600,10 +644,13 @@ __global__ __launch_bounds__(kThreads, D > 128 ? 1 : 2) void paged_prefill_mfma_
     __shared__ __attribute__((aligned(1024))) char buf1[RowGeo<D>::kBufB];
     __shared__ __attribute__((aligned(16))) int32_t docs0[kBN + 4];
     __shared__ __attribute__((aligned(16))) int32_t docs1[kBN + 4];
+    const int32_t precise_keys = precise_key_bound(cu_q_lens, seq_lens, batch, causal,
+                                                   (M::kWindow && plan.mods.window > 0) ? plan.mods.window : 0,
+                                                   (int)(threadIdx.x & 63));
     prefill_body<false, UNIFORM, E, M, D>(buf0, buf1, docs0, docs1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
-                                 num_q_heads, max_blocks, scale, causal, plan);
+                                 num_q_heads, max_blocks, scale, causal, plan, precise_keys);
     prefill_body<true, UNIFORM, E, M, D>(buf0, buf1, docs0, docs1, cache, q, out, lse, cu_q_lens, block_table, seq_lens, batch, num_tiles,
-                                num_q_heads, max_blocks, scale, causal, plan);
+                                num_q_heads, max_blocks, scale, causal, plan, precise_keys);
 }
 
 }  // namespace
