@@ -40,7 +40,8 @@ typedef enum {
     PA_ERR_UNSUPPORTED = 2,          /* dtype / head_dim / stride combination no kernel is written for            */
     PA_ERR_WORKSPACE_TOO_SMALL = 3,  /* workspace_bytes < paged_attention_workspace_bytes(...)                    */
     PA_ERR_HIP = 4,                  /* a HIP call reported an error                                              */
-    PA_ERR_OUT_OF_PAGES = 5          /* the page pool cannot satisfy a reservation (nothing was changed)          */
+    PA_ERR_OUT_OF_PAGES = 5,         /* the page pool cannot satisfy a reservation (nothing was changed)          */
+    PA_ERR_SCRATCH_LIMIT = 6         /* paged_attention_decode_static: the call needs more scratch than the array holds */
 } pa_status;
 
 typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1, PA_DTYPE_F16 = 2 } pa_dtype;
@@ -125,6 +126,22 @@ pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, v
                                  const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
                                  int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * paged_attention_decode for callers that can neither allocate device memory nor bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * paged_attention_decode (bit-identical: the same kernels and the same plan), without the workspace: the split-KV
+ * partials go to a 16 MiB array that lives in the library's device image (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing.  A call whose plan needs more than the array holds (partials are
+ * (workgroups + batch) * Hq * (head_dim + 1) floats; about one workgroup per compute unit) is rejected with
+ * PA_ERR_SCRATCH_LIMIT before anything is launched.  Every call on a GPU shares that GPU's array: calls that
+ * overlap on one GPU (different streams, different host threads) race and must be serialised by the caller.
+ * Nothing in the array needs to start at zero: the kernels write every partial they later read.
+ */
+pa_status paged_attention_decode_static(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                        int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                        void* stream);
 
 /*
  * Prefill / general ragged form: sequence s contributes q_len_s =

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     pa_set_option,
     paged_attention_decode,
     paged_attention_decode_mod,
+    paged_attention_decode_static,
     paged_attention_prefill,
     paged_attention_prefill_mod,
     paged_attention_workspace_bytes,

@@ -22,7 +22,7 @@ PA_DTYPE = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
     "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "paged_decode_step",
-    "pa_debug_check",
+    "paged_attention_decode_static", "pa_debug_check",
     "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
     "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
@@ -207,6 +207,27 @@ def prepare_decode(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int,
     return PreparedCall(lib.paged_attention_decode, args,
                         (d, k_cache, v_cache, q, out, lse, block_table, seq_lens, workspace), "paged_attention_decode",
                         out)
+
+
+def paged_attention_decode_static(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
+                                  out, lse=None, head_major=False, stream=None):
+    """paged_attention_decode without a workspace: the split-KV partials go to the library's static scratch array.
+    Nothing is allocated here either: ``out`` ([B, Hq, d], dtype of q) must be passed in and is returned."""
+    lib = load_library()
+    d = cache_desc(k_cache, v_cache, head_major)
+    _dense(q, "q", k_cache.dtype)
+    B, Hq, hd = q.shape
+    if hd != d.head_dim or seq_lens.shape[0] != B or block_table.shape[0] != B:
+        raise PagedAttnError("q must be [B, Hq, d] with B matching seq_lens and block_table")
+    _i32(block_table, "block_table"), _i32(seq_lens, "seq_lens")
+    _dense(out, "out", q.dtype)
+    if lse is not None:
+        _dense(lse, "lse", torch.float32)
+    st = lib.paged_attention_decode_static(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
+                                           ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]),
+                                           ctypes.c_int32(max_seq_len), ctypes.c_float(scale), _stream(stream))
+    _check(st, "paged_attention_decode_static")
+    return out
 
 
 def paged_attention_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,

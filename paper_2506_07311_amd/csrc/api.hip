@@ -8,6 +8,12 @@
 
 #include "common.h"
 
+// Scratch of paged_attention_decode_static: the split-KV partials of a decode call, for callers that cannot bring
+// a workspace.  One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels receive the address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace pa {
 
 namespace {
@@ -266,7 +272,8 @@ size_t part_lse_bytes(int64_t rows, int32_t hq, int32_t nsplit)
 }
 
 // The workspace of a call.  The public entry points promise the bound paged_attention_workspace_bytes() and are
-// checked against it (bound = true); bound = false checks against what the call's plan really uses.
+// checked against it (bound = true); the entry point that brings its own scratch array is checked against what the
+// call's plan really uses.
 struct Workspace {
     void* ptr;
     size_t bytes;
@@ -434,6 +441,25 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     return launch_attention_generic(a, s);
 }
 
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+pa_status static_scratch(void** ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PA_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return PA_OK;
+}
+
 }  // namespace
 
 
@@ -551,6 +577,22 @@ pa_status paged_attention_decode_mod(const pa_kv_cache_desc* cache, const void* 
                          max_seq_len, scale, 0, mods, Workspace{workspace, workspace_bytes, true}, stream, true);
 }
 
+pa_status paged_attention_decode_static(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
+                                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
+                                        int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
+                                        void* stream)
+{
+    void* ptr = nullptr;
+    if (batch > 0) {
+        const pa_status st = static_scratch(&ptr);
+        if (st != PA_OK) return st;
+    }
+    const pa_status st = run_attention(cache, q, out, lse, nullptr, batch, 1, block_table, seq_lens, batch, num_q_heads,
+                                       max_blocks, max_seq_len, scale, 0, nullptr,
+                                       Workspace{ptr, kStaticScratchBytes, false}, stream, true);
+    return st == PA_ERR_WORKSPACE_TOO_SMALL ? PA_ERR_SCRATCH_LIMIT : st;
+}
+
 pa_status paged_decode_step(const pa_kv_cache_desc* cache, const void* k_new, const void* v_new, const void* q,
                             void* out, float* lse, const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
                             int32_t num_q_heads, int32_t max_blocks, int32_t max_seq_len, float scale,
@@ -592,6 +634,7 @@ const char* pa_status_string(pa_status status)
         case PA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case PA_ERR_HIP: return "HIP call failed";
         case PA_ERR_OUT_OF_PAGES: return "page pool exhausted";
+        case PA_ERR_SCRATCH_LIMIT: return "the call's split-KV partials exceed the 16 MiB static scratch array";
     }
     return "unknown status";
 }
