@@ -50,6 +50,9 @@ WORKLOADS = {
     "speculative_4_tokens_b64_mixed": (8, 16, None),
     # plain paged copy of known size (Algorithm 1 Gather over 16 x 65536 tokens): calibrates HBM byte counters
     "gather_copy_calibration": (5, 16, 65536),
+    # plain contiguous read of as many bytes as the 16 x 131072 decode step streams (2 x 4 GiB): the rate the memory
+    # system gives the simplest reader, the yardstick for the decode kernel's fraction of the 8 TB/s peak
+    "contiguous_read_calibration": (5, 16, None),
     # host-side KV page manager under serving churn (Algorithm 1 Reserve; Sec. III-B): not an attention workload
     "page_manager_serving": (None, 16, None),
 }
@@ -164,6 +167,36 @@ def run_gather_calibration(torch, pa, binding, w, args):
                      "algorithmic_bytes": nbytes, "note": "achieved counts bytes read; as many are written"}}))
 
 
+def run_read_calibration(torch, binding, w, args):
+    """Time pa_stream_read over the first 4 GiB of each pool of the 16 x 131072 workload (8 589 934 592 bytes in all,
+    the bytes one decode step of that workload streams)."""
+    each = 4 << 30
+    sink = torch.zeros(16, dtype=torch.uint8, device=w.q.device)
+
+    def step():
+        binding.pa_stream_read(w.k_cache, w.v_cache, each, sink)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    time_steps(torch, step, args.steps, 0)
+    binding.pa_profile_enable(False)
+    n, ms = binding.pa_profile_read("pa_stream_read_kernel")
+    sec = time_steps(torch, step, args.steps, 0)
+    ach = 2 * each / (ms / n * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "contiguous_read_us_per_step", "value": round(sec * 1e6, 2), "unit": "us/step", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": args.workload, "bytes_read": 2 * each, "buffers": 2, "launch": "2048 workgroups x 512 "
+                   "threads, 16 bytes per lane, 8 loads in flight per lane"},
+        "kernels": {"pa_stream_read_kernel": {"launches": n, "avg_us": ms * 1e3 / n}},
+        "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "pa_stream_read_kernel",
+                     "algorithmic_bytes": 2 * each}}))
+
+
 def run_page_manager(torch, binding, args, P):
     """Serving churn through pa_pool_*: 256 live sequences grow by one token per step (one page pop every P
     steps per sequence, its row entry copied to the device table on the stream); every step four sequences end
@@ -261,6 +294,8 @@ def main():
     is_prefill = cfg in (3, 6, 7, 8)
     if args.workload == "gather_copy_calibration":
         return run_gather_calibration(torch, pa, binding, w, args)
+    if args.workload == "contiguous_read_calibration":
+        return run_read_calibration(torch, binding, w, args)
     seqs = list(range(min(args.oracle_seqs, w.batch)))
     sub = None if args.no_oracle else W.restrict(w, seqs, device="cpu")
 
@@ -269,36 +304,37 @@ def main():
     out = torch.empty_like(w.q)
 
     # cold runs: as many copies of the two pools as it takes to exceed 512 MB, used round-robin
-    pools = [(w.k_cache, w.v_cache)]
+    # (the queries rotate with them: a prefill's Q is as large as its K)
+    pools = [(w.k_cache, w.v_cache, w.q)]
     if args.cold:
         per_copy = 2 * w.k_cache.numel() * w.k_cache.element_size()
-        while len(pools) * per_copy < (512 << 20) and len(pools) < 64:
-            pools.append((w.k_cache.clone(), w.v_cache.clone()))
+        while len(pools) * per_copy < (512 << 20) and len(pools) < 256:
+            pools.append((w.k_cache.clone(), w.v_cache.clone(), w.q.clone()))
     # One step = append + attention (+ merge).  The arguments of the two calls are marshalled once per pool copy
     # (binding.prepare_*): the small workloads' steps are shorter on the GPU than converting the arguments again.
     fused = args.step == "fused" and not is_prefill and w.k_new.shape[0] == w.batch
 
-    def make_step(kc, vc):
+    def make_step(kc, vc, qq):
         if fused:   # one new token per sequence at its last position, then decode: one call
-            return pa.prepare_decode_step(kc, vc, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+            return pa.prepare_decode_step(kc, vc, w.k_new, w.v_new, qq, w.block_table, w.seq_lens, w.max_seq_len,
                                           w.scale, out=out, workspace=ws, **mods)
         app = pa.prepare_kv_append(kc, vc, w.k_new, w.v_new, w.seq_ids, w.positions, w.block_table)
         if is_prefill and mods:
-            return lambda: (app(), pa.paged_attention_prefill_mod(kc, vc, w.q, w.cu_q_lens, w.max_q_len, w.block_table,
+            return lambda: (app(), pa.paged_attention_prefill_mod(kc, vc, qq, w.cu_q_lens, w.max_q_len, w.block_table,
                                                                  w.seq_lens, w.max_seq_len, w.scale, w.causal, out=out,
                                                                  workspace=ws, **mods))
         if is_prefill:
-            att = pa.prepare_prefill(kc, vc, w.q, w.cu_q_lens, w.max_q_len, w.block_table, w.seq_lens, w.max_seq_len,
+            att = pa.prepare_prefill(kc, vc, qq, w.cu_q_lens, w.max_q_len, w.block_table, w.seq_lens, w.max_seq_len,
                                      w.scale, w.causal, out=out, workspace=ws)
         elif mods:
-            return lambda: (app(), pa.paged_attention_decode_mod(kc, vc, w.q, w.block_table, w.seq_lens, w.max_seq_len,
+            return lambda: (app(), pa.paged_attention_decode_mod(kc, vc, qq, w.block_table, w.seq_lens, w.max_seq_len,
                                                                 w.scale, out=out, workspace=ws, **mods))
         else:
-            att = pa.prepare_decode(kc, vc, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale, out=out,
+            att = pa.prepare_decode(kc, vc, qq, w.block_table, w.seq_lens, w.max_seq_len, w.scale, out=out,
                                     workspace=ws)
         return lambda: (app(), att())
 
-    steps_by_pool = [make_step(kc, vc) for kc, vc in pools]
+    steps_by_pool = [make_step(*p) for p in pools]
     turn = [0]
 
     def step():

@@ -257,6 +257,15 @@ const char* pa_status_string(pa_status status);
 pa_status pa_set_option(const char* name, int64_t value);
 
 /*
+ * Measurement yardstick (no part of the method): reads bytes_each bytes of each of the two device buffers a and b
+ * once, contiguously, 16 bytes per lane, and writes nothing -- the rate the memory system gives the plainest reader,
+ * against which the achieved bandwidth of the decode kernels (Sec. IV measures the same step end to end) is judged.
+ * bytes_each must be a positive multiple of 64 MiB; a, b and sink (16 bytes of device memory, never written) are
+ * 16-byte aligned.  Timed like every other kernel through pa_profile_* under the name "pa_stream_read_kernel".
+ */
+pa_status pa_stream_read(const void* a, const void* b, size_t bytes_each, void* sink, void* stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the
  * library is bracketed by a pair of HIP events recorded on the launch stream.
  * pa_profile_read synchronises those events and returns, for the kernel whose

@@ -23,7 +23,7 @@ EXPORTS = (
     "paged_kv_append", "paged_kv_gather", "paged_attention_workspace_bytes", "paged_attention_decode",
     "paged_attention_prefill", "paged_attention_decode_mod", "paged_attention_prefill_mod", "paged_decode_step",
     "paged_attention_decode_static", "pa_debug_check",
-    "pa_status_string", "pa_set_option", "pa_profile_enable", "pa_profile_reset",
+    "pa_status_string", "pa_set_option", "pa_stream_read", "pa_profile_enable", "pa_profile_reset",
     "pa_profile_read",
     "pa_pool_create", "pa_pool_destroy", "pa_pool_set_growth", "pa_pool_reserve", "pa_pool_release", "pa_pool_share_prefix",
     "pa_pool_make_writable", "pa_pool_num_free", "pa_pool_num_blocks", "pa_pool_get_row", "pa_pool_refcount",
@@ -397,6 +397,14 @@ def pa_debug_check(k_cache, v_cache, block_table, seq_lens, seq_ids=None, positi
 
 def pa_set_option(name: str, value: int) -> None:
     _check(load_library().pa_set_option(name.encode(), ctypes.c_int64(value)), f"pa_set_option({name})")
+
+
+def pa_stream_read(a: torch.Tensor, b: torch.Tensor, bytes_each: int, sink: torch.Tensor, *, stream=None) -> None:
+    """Plain contiguous read of the first ``bytes_each`` bytes of two device tensors (bandwidth yardstick)."""
+    if a.numel() * a.element_size() < bytes_each or b.numel() * b.element_size() < bytes_each:
+        raise PagedAttnError("pa_stream_read: buffers shorter than bytes_each")
+    _check(load_library().pa_stream_read(_p(a), _p(b), ctypes.c_size_t(bytes_each), _p(sink), _stream(stream)),
+           "pa_stream_read")
 
 
 def pa_profile_enable(on: bool) -> None:

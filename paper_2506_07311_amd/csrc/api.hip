@@ -680,6 +680,12 @@ pa_status pa_set_option(const char* name, int64_t value)
     return PA_ERR_INVALID_ARG;
 }
 
+pa_status pa_stream_read(const void* a, const void* b, size_t bytes_each, void* sink, void* stream)
+{
+    if (!a || !b || !sink || (((uintptr_t)a | (uintptr_t)b | (uintptr_t)sink) & 15)) return PA_ERR_INVALID_ARG;
+    return launch_stream_read(a, b, bytes_each, sink, reinterpret_cast<hipStream_t>(stream));
+}
+
 pa_status pa_profile_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lock(g_profile_mutex);

@@ -91,6 +91,7 @@ pa_status launch_kv_gather(const pa_kv_cache_desc* c, void* out_k, void* out_v, 
 pa_status launch_debug_check(const pa_kv_cache_desc* c, const int32_t* block_table, const int32_t* seq_lens,
                              int32_t batch, int32_t max_blocks, const int32_t* seq_ids, const int32_t* positions,
                              int32_t T, void* scratch, hipStream_t stream);
+pa_status launch_stream_read(const void* a, const void* b, size_t bytes_each, void* sink, hipStream_t stream);
 pa_status launch_kv_copy_page(const pa_kv_cache_desc* c, int32_t src_page, int32_t dst_page, hipStream_t stream);
 
 // Mask / score modifications of a call (pa_attn_mods with the "off" values normalised).  The kernels take a
