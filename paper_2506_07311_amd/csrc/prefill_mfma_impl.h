@@ -227,10 +227,12 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        // (up to head_dim 128 the region also holds the 4 * T transpose loads of the half's V fragments)
 #pragma unroll
         for (int i = 0; i < KS; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (i < KS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (T <= 4) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 72 / KS, 0);
         }
     }
@@ -257,54 +259,79 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
     l += psum;
 }
 
-// O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps).  vbuf = V part of the tile buffer,
-// vx[2t], vx[2t+1] = this lane's swizzled transpose-load offsets (slots 0-3 / 4-7) for the 32 columns t.  P^T as B operand of a step:
+// V^T operand fragments of half tile `half` (two 16-key steps x T column blocks), read ahead of their use: the
+// transpose loads do not depend on the weights, so they are issued a phase early (under the score products and the
+// softmax) and their latency never stands in front of the value product.
+// vx[2t], vx[2t+1] = this lane's swizzled transpose-load offsets (slots 0-3 / 4-7) for the 32 columns t.
+template <int T>
+__device__ __forceinline__ void load_v_frags(uint4 (&va)[T], uint4 (&vb)[T], const char* vbuf, int half,
+                                             const uint32_t (&vx)[2 * T])
+{
+    constexpr int RB = 256;
+    const char* v0 = vbuf + (32 * half) * RB;
+#pragma unroll
+    for (int t = 0; t < T; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
+#pragma unroll
+    for (int t = 0; t < T; ++t) vb[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
+}
+
+// The weights of 8 keys as a B operand (and their second 16-bit term: p = hi + lo, lo = round(p - hi)).
+template <bool PRECISE, typename E>
+__device__ __forceinline__ void pack_weights(uint4& w, uint4& wl, const f32x16& s, int r0)
+{
+    w.x = E::pack(s[r0 + 0], s[r0 + 1]);
+    w.y = E::pack(s[r0 + 2], s[r0 + 3]);
+    w.z = E::pack(s[r0 + 4], s[r0 + 5]);
+    w.w = E::pack(s[r0 + 6], s[r0 + 7]);
+    if (PRECISE) {
+        wl.x = E::pack(s[r0 + 0] - E::lo_of(w.x), s[r0 + 1] - E::hi_of(w.x));
+        wl.y = E::pack(s[r0 + 2] - E::lo_of(w.y), s[r0 + 3] - E::hi_of(w.y));
+        wl.z = E::pack(s[r0 + 4] - E::lo_of(w.z), s[r0 + 5] - E::hi_of(w.z));
+        wl.w = E::pack(s[r0 + 6] - E::lo_of(w.w), s[r0 + 7] - E::hi_of(w.w));
+    } else {
+        wl = w;
+    }
+}
+
+// O^T += V^T P^T for the 32 keys of a half tile whose fragments load_v_frags brought.  P^T as B operand of a step:
 // elements e = 0..7 <-> weights 8*step + e.
+template <bool PRECISE, typename E, int T>
+__device__ __forceinline__ void half_pv_frags(f32x16 (&o)[T], const f32x16& s, const uint4 (&va)[T], const uint4 (&vb)[T])
+{
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        uint4 w, wl;
+        pack_weights<PRECISE, E>(w, wl, s, 8 * st);
+        const uint4 (&cur)[T] = st ? vb : va;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            o[t] = E::mfma32(cur[t], w, o[t]);
+            if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
+        }
+    }
+}
+
+// O^T += V^T P^T for the 32 keys of half tile `half` (two 16-key steps), head_dim 256: the second step's fragments
+// take the place of the first step's as those are consumed (the 8 column blocks leave no room to hold both).
+// vbuf = V part of the tile buffer.
 template <bool PRECISE, typename E, int T>
 __device__ __forceinline__ void half_pv(f32x16 (&o)[T], const f32x16& s, const char* vbuf, int half,
                                         const uint32_t (&vx)[2 * T])
 {
-    constexpr int RB = T > 4 ? 512 : 256;
-    constexpr int TF = T > 4 ? 1 : T;                       // fragments read ahead of the first step
-    uint4 va[T], vb[TF];
+    constexpr int RB = 512;
+    uint4 va[T];
     const char* v0 = vbuf + (32 * half) * RB;
 #pragma unroll
     for (int t = 0; t < T; ++t) va[t] = lds_frag_tr(v0 + vx[2 * t], v0 + vx[2 * t + 1]);
-    if (T <= 4) {
-#pragma unroll
-        for (int t = 0; t < TF; ++t) vb[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
-    }
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
-        const int r0 = 8 * st;
         uint4 w, wl;
-        w.x = E::pack(s[r0 + 0], s[r0 + 1]);
-        w.y = E::pack(s[r0 + 2], s[r0 + 3]);
-        w.z = E::pack(s[r0 + 4], s[r0 + 5]);
-        w.w = E::pack(s[r0 + 6], s[r0 + 7]);
-        if (PRECISE) {   // second 16-bit term of the weights: p = hi + lo, lo = round(p - hi)
-            wl.x = E::pack(s[r0 + 0] - E::lo_of(w.x), s[r0 + 1] - E::hi_of(w.x));
-            wl.y = E::pack(s[r0 + 2] - E::lo_of(w.y), s[r0 + 3] - E::hi_of(w.y));
-            wl.z = E::pack(s[r0 + 4] - E::lo_of(w.z), s[r0 + 5] - E::hi_of(w.z));
-            wl.w = E::pack(s[r0 + 6] - E::lo_of(w.w), s[r0 + 7] - E::hi_of(w.w));
-        } else {
-            wl = w;
-        }
-        if constexpr (T <= 4) {
-            const uint4 (&cur)[T] = st ? vb : va;
+        pack_weights<PRECISE, E>(w, wl, s, 8 * st);
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                o[t] = E::mfma32(cur[t], w, o[t]);
-                if (PRECISE) o[t] = E::mfma32(cur[t], wl, o[t]);
-            }
-        } else {
-            // wide rows: the second step's fragments take the place of the first step's as those are consumed
-#pragma unroll
-            for (int t = 0; t < T; ++t) {
-                o[t] = E::mfma32(va[t], w, o[t]);
-                if (PRECISE) o[t] = E::mfma32(va[t], wl, o[t]);
-                if (st == 0) va[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
-            }
+        for (int t = 0; t < T; ++t) {
+            o[t] = E::mfma32(va[t], w, o[t]);
+            if (PRECISE) o[t] = E::mfma32(va[t], wl, o[t]);
+            if (st == 0) va[t] = lds_frag_tr(v0 + 16 * RB + vx[2 * t], v0 + 16 * RB + vx[2 * t + 1]);
         }
     }
 }
@@ -340,13 +367,25 @@ __device__ __forceinline__ void attend_tile(const char* buf, const uint32_t (&kx
                                             int32_t key0, int32_t nk, const RowMods& rm, const int32_t* docs)
 {
     f32x16 s0, s1, p;
-    half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
-    half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
-    half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm, docs);
     constexpr int TB = kBN * (T > 4 ? 512 : 256);
-    half_pv<PRECISE, E, T>(o, p, buf + TB, 0, vx);
-    half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm, docs + 32);
-    half_pv<PRECISE, E, T>(o, p, buf + TB, 1, vx);
+    if constexpr (T <= 4) {
+        uint4 va[T], vb[T];
+        half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
+        half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
+        load_v_frags<T>(va, vb, buf + TB, 0, vx);
+        half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm, docs);
+        half_pv_frags<PRECISE, E, T>(o, p, va, vb);
+        load_v_frags<T>(va, vb, buf + TB, 1, vx);
+        half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm, docs + 32);
+        half_pv_frags<PRECISE, E, T>(o, p, va, vb);
+    } else {
+        half_scores<E, 2 * T>(s0, buf, 0, kx, qf);
+        half_scores<E, 2 * T>(s1, buf, 1, kx, qf);
+        half_softmax<MASK, true, M, T>(p, s0, o, m, l, sc, key0, nk, rm, docs);
+        half_pv<PRECISE, E, T>(o, p, buf + TB, 0, vx);
+        half_softmax<MASK, false, M, T>(p, s1, o, m, l, sc, key0 + 32, nk, rm, docs + 32);
+        half_pv<PRECISE, E, T>(o, p, buf + TB, 1, vx);
+    }
 }
 
 template <bool PRECISE, bool UNIFORM, typename E, typename M, int D>

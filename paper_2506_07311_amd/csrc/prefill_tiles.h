@@ -70,11 +70,19 @@ __device__ __forceinline__ void fetch_rows(char* dst, const CacheView& cache, in
                                            int32_t last_key, uint32_t lane_off)
 {
     const int32_t slot = min(key, last_key) & (cache.page_size - 1);
-    int64_t off;
-    if (UNIFORM)
-        off = (int64_t)page * cache.page_stride * 2 + ((uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off);
-    else
-        off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
+    if (UNIFORM) {
+        // scalar page base + 32-bit lane offset: the loads take the scalar-base form and a row group costs a handful
+        // of 32-bit vector operations instead of 64-bit multiply-adds per lane
+        int64_t page_off = (int64_t)page * cache.page_stride * 2;
+        asm volatile("" : "+s"(page_off));                 // stays in scalar registers
+        const uint32_t off32 = (uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off;
+        const char* kp = reinterpret_cast<const char*>(cache.k) + page_off;
+        const char* vp = reinterpret_cast<const char*>(cache.v) + page_off;
+        __builtin_amdgcn_global_load_lds((glb_void*)(kp + off32), (lds_void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(vp + off32), (lds_void*)(dst + kTileBytes), 16, 0, 0);
+        return;
+    }
+    const int64_t off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
     __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.k) + off), (lds_void*)dst, 16, 0, 0);
     __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.v) + off),
                                      (lds_void*)(dst + kTileBytes), 16, 0, 0);
