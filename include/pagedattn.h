@@ -247,6 +247,8 @@ const char* pa_status_string(pa_status status);
  *   "decode_short"         the one-launch decode kernel for short contexts (a workgroup per sequence and KV head,
  *                          no workspace, no merge launch): 0 = taken while the step is small enough for it to
  *                          pay (the default), 1 = whenever it supports the call, -1 = never
+ *   "decode_short_splits"  workgroups per (sequence, KV head) of the one-launch decode kernel, 1 .. 16 (0 = as many
+ *                          as fill the machine, at least 256 keys each); size the workspace AFTER setting it
  *   "step_append_kernel"   1 = paged_decode_step on the tile-stream kernel appends with a kernel launch of its own
  *                          instead of inside the decode kernel (for comparison)
  *   "no_small_q_route"     1 = the prefill entry point keeps sequences with few queries (q_len * G <= 16) on

@@ -27,6 +27,7 @@ struct Options {
     int64_t step_append_kernel = 0;   // 1 = paged_decode_step on the tile stream appends with a kernel of its own
                                       // (0: every decode kernel performs the step's append itself)
     int64_t decode_short = 0;      // 0 = heuristic, 1 = whenever the one-launch kernel supports the call, -1 = never
+    int64_t decode_short_splits = 0;   // workgroups per (sequence, KV head) of the one-launch kernel; 0 = heuristic
 };
 thread_local Options g_opt;       // per host thread: a thread's knobs shape only the calls it makes itself
 
@@ -195,20 +196,55 @@ int32_t plan_stream_wgs(int32_t batch, int32_t max_seq_len, int32_t head_groups,
 }
 
 // One launch instead of tile stream + merge: pays while a step is bound by launches and memory round trips.  A
-// workgroup of the one-launch kernel streams its (sequence, KV head) at about 55 GB/s, so its time is about
-// 4 us + 9 us per 512 KB, against a floor of 12-16 us for tile stream + merge: measured on 1..256 sequences of
-// 128..2048 tokens, it wins up to 1024 tokens (512 at head_dim 256: rows twice as long) as long as its grid is
-// at most two workgroups per compute unit; beyond that the tile stream's whole-row reads and equal split use the
-// memory system better.
-constexpr int64_t kShortMaxRowBytes = 1024 * 512;   // context tokens x bytes of a K row and a V row (>= 512)
+// workgroup of the one-launch kernel streams its share of a (sequence, KV head) at about 55 GB/s, so its time is
+// about 4 us + 9 us per 512 KB, against a floor of 12-16 us for tile stream + merge.  With few sequences the
+// kernel puts several workgroups on a (sequence, KV head) -- as many as fill the machine once (a compute unit holds
+// one workgroup of this kernel: its eight waves take the whole register file), at least 256 keys each -- which
+// merge through the workspace inside the same launch; the route is taken while a workgroup's share stays within
+// 512 KB of K and V rows (1024 tokens at head_dim <= 128, 512 at head_dim 256: rows twice as long).  Beyond that
+// the tile stream's whole-row reads and equal split use the memory system better.  Measured, 32 / 8 heads, one box:
+// 8 x 1024 tokens 10.6 us with 4 workgroups per (sequence, KV head) against 14.3 with one (15.5 tile stream + merge),
+// 8 x 2048 16.9 against 23.6 (20.7), 8 x 4096 26.7 against 41.9 (29.5), 1 x 8192 19.9 against 75 (20.2).
+constexpr int64_t kShortMaxRowBytes = 1024 * 512;   // context tokens x bytes of a K row and a V row (>= 512) per workgroup
 constexpr int64_t kShortMaxWGsPerCU = 2;
+constexpr int32_t kShortMinSplitKeys = 256;
 
-bool short_decode_pays(const AttnArgs& a)
+int64_t short_units(const AttnArgs& a)
+{
+    return (int64_t)a.batch * a.cache.num_kv_heads * ((a.num_q_heads / a.cache.num_kv_heads + 15) / 16);
+}
+
+// Workgroups per (sequence, KV head, slice of 16 heads) of the one-launch kernel.
+int32_t plan_short_splits(const AttnArgs& a)
+{
+    const int64_t units = short_units(a);
+    if (units > kShortMaxUnits) return 1;
+    int64_t n = g_opt.decode_short_splits;
+    if (n <= 0) {
+        n = device_cus() / units;
+        const int64_t by_keys = a.max_seq_len / kShortMinSplitKeys;
+        if (n > by_keys) n = by_keys;
+    }
+    if (n > kShortMaxSplit) n = kShortMaxSplit;
+    return n < 1 ? 1 : (int32_t)n;
+}
+
+bool short_decode_pays(const AttnArgs& a, int32_t nsplit)
 {
     if (g_opt.decode_workgroups > 0) return false;     // the caller shapes the tile stream: keep it
     const int64_t row_bytes = 4LL * (a.cache.head_dim > 128 ? a.cache.head_dim : 128);
-    const int64_t wgs = (int64_t)a.batch * a.cache.num_kv_heads * ((a.num_q_heads / a.cache.num_kv_heads + 15) / 16);
-    return a.max_seq_len * row_bytes <= kShortMaxRowBytes && wgs <= kShortMaxWGsPerCU * device_cus();
+    const int64_t share = ((int64_t)a.max_seq_len + nsplit - 1) / nsplit;
+    return share * row_bytes <= kShortMaxRowBytes && short_units(a) * nsplit <= kShortMaxWGsPerCU * device_cus();
+}
+
+// Partials of the one-launch kernel's workgroups when a call splits: at most kShortMaxWGsPerCU per compute unit
+// (or the forced number per unit), 16 rows of head_dim floats plus maxima and sums each.
+size_t short_split_workspace_bytes(int32_t batch, int32_t hq, int32_t d)
+{
+    // units <= batch * hq (group size 1, one slice); the heuristic never exceeds two workgroups per compute unit
+    int64_t wgs = kShortMaxWGsPerCU * device_cus();
+    if (g_opt.decode_short_splits > 1) wgs = (int64_t)batch * hq * g_opt.decode_short_splits;
+    return align256(decode_short_part_floats(wgs, d) * sizeof(float));
 }
 
 size_t stream_workspace_bytes(int32_t batch, int32_t hq, int32_t d, int32_t wgs)
@@ -344,6 +380,9 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.has_mods = m.window > 0 || m.softcap > 0.f || m.alibi_slopes || m.doc_ids;
     a.k_new = k_new;
     a.v_new = v_new;
+    a.short_nsplit = 1;
+    a.short_part = nullptr;
+    a.short_arrive = nullptr;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     char* const base = reinterpret_cast<char*>(ws.ptr);
     const int32_t d = cache->head_dim;
@@ -360,9 +399,17 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     };
 
     if (decode) {
-        if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a) &&
-            (g_opt.decode_short > 0 || short_decode_pays(a)))
-            return launch_decode_short(a, s);              // with k_new / v_new: the append happens in this launch
+        if (!g_opt.force_generic && g_opt.decode_short >= 0 && decode_short_supported(a)) {
+            const int32_t nsplit = plan_short_splits(a);
+            if (g_opt.decode_short > 0 || short_decode_pays(a, nsplit)) {
+                a.short_nsplit = nsplit;
+                a.short_part = reinterpret_cast<float*>(base);
+                if (nsplit > 1 &&
+                    ws.bytes < decode_short_part_floats(short_units(a) * nsplit, d) * sizeof(float))
+                    return PA_ERR_WORKSPACE_TOO_SMALL;
+                return launch_decode_short(a, s);          // with k_new / v_new: the append happens in this launch
+            }
+        }
         const bool stream_route = !g_opt.force_generic && decode_mfma_supported(a);
         if (stream_route) {
             const int32_t head_groups = cache->num_kv_heads / decode_mfma_heads_per_wg(cache->num_kv_heads, d);
@@ -550,7 +597,9 @@ size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32
         const size_t chunked = part_o_bytes(batch, num_q_heads, head_dim, ns) + part_lse_bytes(batch, num_q_heads, ns);
         const size_t stream = stream_workspace_bytes(batch, num_q_heads, head_dim,
                                                      stream_wgs_bound(batch, num_q_heads, max_seq_len));
-        return chunked > stream ? chunked : stream;
+        const size_t split = short_split_workspace_bytes(batch, num_q_heads, head_dim);
+        const size_t need = chunked > stream ? chunked : stream;
+        return need > split ? need : split;
     }
     // prefill: partials of the context split, when the sizes make it split, and of the few-query route
     const int32_t np = prefill_nsplit_bound(batch, num_q_heads, total_q, max_seq_len);
@@ -670,6 +719,11 @@ pa_status pa_set_option(const char* name, int64_t value)
     if (!strcmp(name, "decode_short")) {
         if (value < -1 || value > 1) return PA_ERR_INVALID_ARG;
         g_opt.decode_short = value;
+        return PA_OK;
+    }
+    if (!strcmp(name, "decode_short_splits")) {
+        if (value < 0 || value > kShortMaxSplit) return PA_ERR_INVALID_ARG;
+        g_opt.decode_short_splits = value;
         return PA_OK;
     }
     if (!strcmp(name, "force_generic")) {

@@ -147,6 +147,11 @@ struct AttnArgs {
     // rows of the cache dtype, or null
     const void* k_new;
     const void* v_new;
+    // one-launch decode with several workgroups per (sequence, KV head, slice): their number, their partials (a
+    // part of the workspace) and the arrival counters (zero on entry, zero again on exit)
+    int32_t short_nsplit;
+    float* short_part;
+    uint32_t* short_arrive;
 };
 
 // Portable VALU kernel: any dtype / head_dim / page size / group size; decode and ragged prefill.
@@ -159,6 +164,11 @@ pa_status launch_decode_mfma(const AttnArgs& a, hipStream_t stream);
 // and merge through LDS; no workspace.
 bool decode_short_supported(const AttnArgs& a);
 pa_status launch_decode_short(const AttnArgs& a, hipStream_t stream);
+// Floats of the partials of that kernel for `wgs` workgroups (several per sequence and KV head), and the most
+// workgroups one call may split into.
+inline size_t decode_short_part_floats(int64_t wgs, int32_t head_dim) { return (size_t)wgs * (16 * (size_t)head_dim + 32); }
+constexpr int32_t kShortMaxSplit = 16;
+constexpr int32_t kShortMaxUnits = 4096;   // (sequence, KV head, slice) units of a split call: one arrival counter each
 // MFMA prefill kernel: bf16, head_dim 128.
 bool prefill_mfma_supported(const AttnArgs& a);
 int32_t prefill_mfma_log2_pack(int32_t num_q_heads, int32_t num_kv_heads);

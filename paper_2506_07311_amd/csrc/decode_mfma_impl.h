@@ -607,15 +607,23 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
 // a quad land on distinct banks), NW x 16 maxima and NW x 16 sums: 66 KiB at head_dim 128 and 256.
 // ---------------------------------------------------------------------------------------------------
 // FUSED: the kernel also performs the step's append (Algorithm 1, Assign) of one new token per sequence at position
-// len - 1: the wave that owns the sequence's last tile (always the last wave) stores the token's K / V rows of
-// this KV head into their slot, and reads those rows from k_new / v_new instead of the pool, so nothing waits for
-// the store.  (Workgroups of other head slices of the same KV head read the new rows the same way and store nothing.)
+// len - 1: the wave that owns the sequence's last tile (always the last wave of the last workgroup) stores the
+// token's K / V rows of this KV head into their slot, and reads those rows from k_new / v_new instead of the pool, so
+// nothing waits for the store.  (Workgroups of other head slices of the same KV head read the new rows the same way
+// and store nothing.)
+// nsplit > 1 (contexts of a few thousand tokens with few sequences, where one workgroup per (sequence, KV head)
+// would stream its context through a single compute unit): nsplit workgroups share a (sequence, KV head, slice), each
+// takes a contiguous share of the tiles, leaves its merged partial (unnormalised accumulator rows, maxima, sums) in
+// `part` and counts itself in on the unit's arrival counter; the workgroup that arrives last merges the nsplit
+// partials in split order -- the result does not depend on who that is -- and sets the counter back to zero, so the
+// counters are zero again when the kernel ends: still one launch, no merge kernel, nothing to clear beforehand.
+// part: nsplit blocks of 16 * D + 32 floats per unit; arrive: one counter per unit, zero on entry.
 template <int NW, bool UNIFORM, bool FUSED, typename E, typename M, typename GE>
 __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
     CacheView cache, const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float* __restrict__ lse,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, int32_t num_q_heads,
     int32_t max_blocks, float scale, ModArgs mods, const uint16_t* __restrict__ k_new,
-    const uint16_t* __restrict__ v_new)
+    const uint16_t* __restrict__ v_new, int32_t nsplit, float* __restrict__ part, uint32_t* __restrict__ arrive)
 {
     constexpr int kD = GE::kD;
     constexpr int kTileKeys = GE::kTileKeys;
@@ -623,11 +631,13 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
     __shared__ __attribute__((aligned(16))) float sm_o[NW * 16 * kRow];
     __shared__ float sm_m[NW * 16];
     __shared__ float sm_l[NW * 16];
+    __shared__ uint32_t sm_last;
 
     const int32_t window = M::kWindow ? mods.window : 0;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform: a scalar
-    const int32_t s = blockIdx.x;
+    const int32_t s = (int32_t)blockIdx.x / nsplit;
+    const int32_t split = (int32_t)blockIdx.x - s * nsplit;
     const int32_t kvh = blockIdx.y;
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t h0 = 16 * (int32_t)blockIdx.z;
@@ -638,8 +648,10 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
     const int32_t len = seq_lens[s];
     const int32_t key0 = first_key_of<kTileKeys>(len, 1, window);
     const int32_t nt = tiles_of<kTileKeys>(len - key0);
-    const int32_t t_begin = (int32_t)(((int64_t)wave * nt) / NW);
-    const int32_t t_end = (int32_t)(((int64_t)(wave + 1) * nt) / NW);
+    const int32_t wt0 = (int32_t)(((int64_t)split * nt) / nsplit);               // this workgroup's share of the tiles
+    const int32_t wtn = (int32_t)(((int64_t)(split + 1) * nt) / nsplit) - wt0;
+    const int32_t t_begin = wt0 + (int32_t)(((int64_t)wave * wtn) / NW);
+    const int32_t t_end = wt0 + (int32_t)(((int64_t)(wave + 1) * wtn) / NW);
     const int32_t c0 = key0 + t_begin * kTileKeys;
     const int32_t c1 = min(len, key0 + t_end * kTileKeys);
     const int32_t pos = len - 1;
@@ -680,7 +692,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
             a.knew = reinterpret_cast<const char*>(k_new) + new_row;
             a.vnew = reinterpret_cast<const char*>(v_new) + new_row;
             a.new_pos = pos;
-            if (wave == NW - 1 && blockIdx.z == 0) {
+            if (wave == NW - 1 && split == nsplit - 1 && blockIdx.z == 0) {
                 constexpr int kPieces = kD / 8;              // 16-byte pieces of a row; K then V: at most 64 lanes
                 if (lane < 2 * kPieces) {
                     const bool is_v = lane >= kPieces;
@@ -760,6 +772,9 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
 
     // merge: thread -> (row, 4 columns); weights 2^(m_p - M), a partial without any visible key weighs nothing
     const int64_t out_row0 = (int64_t)s * num_q_heads + kvh * G + h0;
+    const int64_t unit = ((int64_t)s * gridDim.y + kvh) * gridDim.z + blockIdx.z;
+    constexpr int kPartFloats = 16 * kD + 32;                // accumulator rows, then 16 maxima, then 16 sums
+    float* const my_part = part + (unit * nsplit + split) * kPartFloats;
     for (int it = threadIdx.x; it < 16 * (kD / 4); it += NW * 64) {
         const int row = it / (kD / 4), c4 = it % (kD / 4);
         if (row >= rows) continue;
@@ -779,7 +794,71 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
             acc.z = __builtin_fmaf(wgt, v.z, acc.z);
             acc.w = __builtin_fmaf(wgt, v.w, acc.w);
         }
+        if (nsplit > 1) {                                    // this workgroup's partial, relative to its own maximum
+            // component-major ([4][16 rows][D / 4]): consecutive lanes store consecutive words
+            float* po = my_part + row * (kD / 4) + c4;
+            __hip_atomic_store(po + 0 * 4 * kD, acc.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(po + 1 * 4 * kD, acc.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(po + 2 * 4 * kD, acc.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(po + 3 * 4 * kD, acc.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (c4 == 0) {
+                __hip_atomic_store(my_part + 16 * kD + row, mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(my_part + 16 * kD + 16 + row, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            continue;
+        }
         const float inv = sum > 0.f ? 1.f / sum : 0.f;       // sum == 0: an empty sequence (or no visible key)
+        uint2 wv;
+        wv.x = E::pack(acc.x * inv, acc.y * inv);
+        wv.y = E::pack(acc.z * inv, acc.w * inv);
+        *reinterpret_cast<uint2*>(out + (out_row0 + row) * kD + 4 * c4) = wv;
+        if (lse && c4 == 0) lse[out_row0 + row] = sum > 0.f ? (mx + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
+    }
+    if (nsplit == 1) return;
+
+    // Arrival.  The partials are written and read with device-scope atomic accesses (write-through stores, loads
+    // that bypass the caches that are not coherent across the chip), so publishing them needs no cache write-back
+    // or invalidation -- a release fence per workgroup costs about as much here as the context split gains -- only
+    // order: every wave waits until its stores have been acknowledged, the barrier collects the waves, then one thread
+    // counts the workgroup in; the workgroup that finds nsplit - 1 earlier arrivals reads the partials after its
+    // counting has returned.  It merges them in split order and hands the counter back as it found it.  (Every
+    // workgroup of the unit gets here exactly once, with or without tiles.)
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t before = __hip_atomic_fetch_add(arrive + unit, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t last = before == (uint32_t)(nsplit - 1) ? 1u : 0u;
+        if (last) __hip_atomic_store(arrive + unit, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = last;
+    }
+    __syncthreads();
+    if (sm_last == 0u) return;
+    const float* const unit_part = part + unit * nsplit * kPartFloats;
+    for (int it = threadIdx.x; it < 16 * (kD / 4); it += NW * 64) {
+        const int row = it / (kD / 4), c4 = it % (kD / 4);
+        if (row >= rows) continue;
+        float mx = -INFINITY;
+        for (int p = 0; p < nsplit; ++p)
+            mx = fmaxf(mx, __hip_atomic_load(unit_part + p * kPartFloats + 16 * kD + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        float sum = 0.f;
+        float4 acc = float4{0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < nsplit; ++p) {
+            const float* pp = unit_part + p * kPartFloats;
+            const float mp = __hip_atomic_load(pp + 16 * kD + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float wgt = mp == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mp - mx);
+            float4 v;
+            const float* pv = pp + row * (kD / 4) + c4;
+            v.x = __hip_atomic_load(pv + 0 * 4 * kD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v.y = __hip_atomic_load(pv + 1 * 4 * kD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v.z = __hip_atomic_load(pv + 2 * 4 * kD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v.w = __hip_atomic_load(pv + 3 * 4 * kD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sum = __builtin_fmaf(wgt, __hip_atomic_load(pp + 16 * kD + 16 + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), sum);
+            acc.x = __builtin_fmaf(wgt, v.x, acc.x);
+            acc.y = __builtin_fmaf(wgt, v.y, acc.y);
+            acc.z = __builtin_fmaf(wgt, v.z, acc.z);
+            acc.w = __builtin_fmaf(wgt, v.w, acc.w);
+        }
+        const float inv = sum > 0.f ? 1.f / sum : 0.f;
         uint2 wv;
         wv.x = E::pack(acc.x * inv, acc.y * inv);
         wv.y = E::pack(acc.z * inv, acc.w * inv);
@@ -792,7 +871,8 @@ template <int NW, typename E, typename M, typename GE>
 void launch_short_nw(const AttnArgs& a, hipStream_t stream)
 {
     const int32_t G = a.num_q_heads / a.cache.num_kv_heads;
-    const dim3 grid((uint32_t)a.batch, (uint32_t)a.cache.num_kv_heads, (uint32_t)((G + 15) / 16));
+    const int32_t nsplit = a.short_nsplit > 1 ? a.short_nsplit : 1;
+    const dim3 grid((uint32_t)(a.batch * nsplit), (uint32_t)a.cache.num_kv_heads, (uint32_t)((G + 15) / 16));
     const bool uniform = a.cache.page_size >= 16;
     auto kern = a.k_new ? (uniform ? paged_decode_short_kernel<NW, true, true, E, M, GE>
                                    : paged_decode_short_kernel<NW, false, true, E, M, GE>)
@@ -800,7 +880,7 @@ void launch_short_nw(const AttnArgs& a, hipStream_t stream)
                                    : paged_decode_short_kernel<NW, false, false, E, M, GE>);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), 0, stream, a.cache, (const uint16_t*)a.q, (uint16_t*)a.out, a.lse,
                        a.block_table, a.seq_lens, a.num_q_heads, a.max_blocks, a.scale, a.mods,
-                       (const uint16_t*)a.k_new, (const uint16_t*)a.v_new);
+                       (const uint16_t*)a.k_new, (const uint16_t*)a.v_new, nsplit, a.short_part, a.short_arrive);
 }
 
 template <int NW, typename E, typename M, typename GE>

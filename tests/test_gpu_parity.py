@@ -175,6 +175,63 @@ def test_decode_in_one_launch(pa, oracle, Hq, Hkv, dtype, d, P):
         binding.pa_set_option("decode_short", 0)
 
 
+@pytest.mark.parametrize("splits", [2, 3, 7, 16])
+@pytest.mark.parametrize("Hq,Hkv,dtype,d,P", [(32, 8, torch.bfloat16, 128, 16), (40, 2, torch.bfloat16, 128, 4),
+                                              (8, 8, torch.float16, 64, 16), (24, 8, torch.bfloat16, 256, 64)])
+@pytest.mark.parametrize("case", [None, dict(window=300), dict(docs=True, alibi=True, softcap=3.0)],
+                         ids=["plain", "window", "hooks"])
+def test_one_launch_decode_with_several_workgroups_per_sequence(pa, oracle, splits, Hq, Hkv, dtype, d, P, case):
+    """The one-launch kernel with its context cut over several workgroups that merge through the workspace inside
+    the launch: sequences shorter than the number of workgroups (workgroups without tiles),
+    ragged tails, hooks; as the pair of calls and as the step call (the last workgroup's last wave appends)."""
+    from paper_2506_07311_amd import binding
+    lens = [300, 77, 1025, 16, 15, 2049, 1, 3000, 33]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=P, dtype=dtype,
+                        seed=136, device=DEV)
+    mods = build_mods(case, Hq, lens) if case else None
+    binding.pa_set_option("decode_short", 1)
+    binding.pa_set_option("decode_short_splits", splits)
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    try:
+        for step_call in (False, True):
+            parity.check_step(pa, oracle, w, f"split one-launch decode x{splits} d={d} {case} step={step_call}",
+                              mods=mods, step_call=step_call)
+        torch.cuda.synchronize()
+        assert binding.pa_profile_read("paged_decode_short_kernel")[0] == 2
+        assert binding.pa_profile_read("paged_attention_merge_kernel")[0] == 0
+        assert binding.pa_profile_read("paged_decode_mfma_kernel")[0] == 0
+    finally:
+        binding.pa_profile_enable(False)
+        binding.pa_profile_reset()
+        binding.pa_set_option("decode_short_splits", 0)
+        binding.pa_set_option("decode_short", 0)
+
+
+def test_split_one_launch_decode_is_stable_over_many_calls(pa):
+    """300 calls in a row on the same inputs, the workspace poisoned between them: every call must give the bits of
+    the first (the workgroup that merges changes from call to call; the merge order and the counters' state may
+    not)."""
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[2048] * 8, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=137, device=DEV, poison=False)
+    ws = torch.empty(pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.batch, w.max_seq_len),
+                     dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(w.q)
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device=DEV)
+    first = None
+    for it in range(300):
+        ws.fill_(0xFF if it % 2 else 0x7F)
+        out.zero_()
+        pa.paged_attention_decode(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
+                                  out=out, lse=lse, workspace=ws)
+        if first is None:
+            torch.cuda.synchronize()
+            first = (out.clone(), lse.clone())
+        else:
+            assert torch.equal(out, first[0]) and torch.equal(lse, first[1]), f"call {it} differs from the first"
+
+
 @pytest.mark.parametrize("d", [64, 128, 256])
 def test_decode_entry_with_an_empty_sequence(pa, decode_route, d):
     """seq_lens[s] == 0 through the decode entry point itself: zeros and lse = -inf for that sequence; the other
@@ -269,7 +326,11 @@ def test_decode_step_on_the_tile_stream_with_and_without_an_append_kernel(pa, ow
         w = W.make_workload("t", seq_lens=lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=P,
                             dtype=torch.bfloat16, seed=41, device=DEV)
         k0, v0 = w.k_cache.clone(), w.v_cache.clone()
-        out_pair, lse_pair = parity.gpu_step(pa, w)
+        binding.pa_set_option("decode_short", -1)                 # both sides on the tile stream
+        try:
+            out_pair, lse_pair = parity.gpu_step(pa, w)
+        finally:
+            binding.pa_set_option("decode_short", 0)
         k_pair, v_pair = w.k_cache.clone(), w.v_cache.clone()
         w.k_cache.copy_(k0)
         w.v_cache.copy_(v0)
@@ -344,8 +405,10 @@ def test_decode_route_follows_the_size_of_the_step(pa):
 
     assert kernels_of(128) == (1, 0, 0)
     assert kernels_of(1024) == (1, 0, 0)
-    assert kernels_of(1025) == (0, 1, 1)
+    assert kernels_of(4096) == (1, 0, 0)                    # 64 (sequence, KV head) pairs: four workgroups each
+    assert kernels_of(4097) == (0, 1, 1)
     assert kernels_of(1024, wgs=16) == (0, 1, 1)
+    assert kernels_of(1025, batch=32) == (0, 1, 1)          # 256 pairs fill the machine: no split, 1024 tokens at most
     assert kernels_of(512, batch=64) == (1, 0, 0)
     assert kernels_of(512, batch=65) == (0, 1, 1)
 
