@@ -175,6 +175,10 @@ pa_status paged_attention_prefill(const pa_kv_cache_desc* cache, const void* q, 
  *                    int32 [batch, doc_stride], indexed by logical position, doc_stride >= max_seq_len
  *   softcap > 0      score x = scale * <q, k> becomes softcap * tanh(x / softcap)
  *   alibi_slopes     then x becomes x + alibi_slopes[h] * (j - pos);  device float[Hq]
+ *   user_mod != 0    then the visible() / score() pair of the user modification with that id, compiled into
+ *                    every attention kernel from include/pagedattn_mods.h (the extension point: a mask or score
+ *                    family is added there, in one header, without touching a kernel); an id the library
+ *                    was not built with is PA_ERR_INVALID_ARG
  * A query left without any visible key gets out = 0, lse = -inf.  The kernels
  * are instantiated per combination of hooks at compile time: a call with
  * mods == NULL, or with every field off, runs exactly the unmodified kernels.
@@ -186,6 +190,8 @@ typedef struct {
     const float*   alibi_slopes;
     const int32_t* doc_ids;
     int64_t        doc_stride;
+    int32_t        user_mod;    /* 0 = none, else the kId of a modification listed in pagedattn_mods.h */
+    const void*    user_data;   /* handed to that modification's hooks (device memory the hooks read) */
 } pa_attn_mods;
 
 /* paged_attention_decode / paged_attention_prefill with modifications; all other arguments as there. */

@@ -133,11 +133,13 @@ def kv_gather(k_cache, v_cache, block_table, seq_lens, head_major=False):
 
 class _Mods(ctypes.Structure):
     _fields_ = [("window", ctypes.c_int32), ("softcap", ctypes.c_double), ("alibi_slopes", ctypes.c_void_p),
-                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64)]
+                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64), ("prefix_lens", ctypes.c_void_p),
+                ("prefix_bias", ctypes.c_double)]
 
 
 def attention(k_cache, v_cache, q, block_table, seq_lens, scale, causal=False, cu_q_lens=None,
-              head_major=False, return_weights=False, window=0, softcap=0.0, alibi_slopes=None, doc_ids=None):
+              head_major=False, return_weights=False, window=0, softcap=0.0, alibi_slopes=None, doc_ids=None,
+              prefix_lens=None, prefix_bias=0.0):
     """Masked softmax attention over the paged cache by the direct definition, in fp64.
 
     q: ``[total_q, Hq, d]`` (same dtype as the cache).  ``cu_q_lens`` defaults to
@@ -147,7 +149,8 @@ def attention(k_cache, v_cache, q, block_table, seq_lens, scale, causal=False, c
     Modifications (FlexAttention's mask_mod / score_mod families): ``window`` > 0 keeps keys with
     |j - pos| < window; ``doc_ids`` int32 ``[batch, >= max len]`` keeps keys of the query's document;
     ``softcap`` > 0 replaces a score x by softcap * tanh(x / softcap); ``alibi_slopes`` ``[Hq]`` adds
-    slope[h] * (j - pos).
+    slope[h] * (j - pos); ``prefix_lens`` int32 ``[batch]`` is the prefix-LM family: keys j <= pos or
+    j < prefix_lens[s] stay visible, and ``prefix_bias`` is added to the scores of the prefix keys.
     """
     lib = _load()
     c = _desc(k_cache, v_cache, head_major)
@@ -173,8 +176,12 @@ def attention(k_cache, v_cache, q, block_table, seq_lens, scale, causal=False, c
         assert slopes.shape == (Hq,)
     if docs is not None:
         assert docs.ndim == 2 and docs.shape[0] == B and (B == 0 or docs.shape[1] >= int(lens.max()))
+    prefix = None if prefix_lens is None else _i32(prefix_lens)
+    if prefix is not None:
+        assert prefix.shape == (B,)
     mods = _Mods(int(window), float(softcap), None if slopes is None else slopes.ctypes.data,
-                 None if docs is None else docs.ctypes.data, 0 if docs is None else docs.shape[1])
+                 None if docs is None else docs.ctypes.data, 0 if docs is None else docs.shape[1],
+                 None if prefix is None else prefix.ctypes.data, float(prefix_bias))
     rc = lib.oracle_attention_mod(ctypes.byref(c), _ptr(q), _ptr(out), _ptr(lse), _ptr(weights),
                                   ctypes.c_int64(wstride), _ptr(cu), _ptr(bt), _ptr(lens),
                                   ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(bt.shape[1]),

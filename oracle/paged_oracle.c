@@ -156,15 +156,17 @@ static int visible(const oracle_mods *mods, int32_t s, int64_t pos, int64_t j)
         const int32_t *doc = mods->doc_ids + (int64_t)s * mods->doc_stride;
         if (doc[j] != doc[pos]) return 0;
     }
+    if (mods->prefix_lens && !(j <= pos || j < mods->prefix_lens[s])) return 0;
     return 1;
 }
 
 /* score_mod: soft cap first, then the linear position bias. */
-static double modded(const oracle_mods *mods, double x, int32_t h, int64_t pos, int64_t j)
+static double modded(const oracle_mods *mods, double x, int32_t s, int32_t h, int64_t pos, int64_t j)
 {
     if (!mods) return x;
     if (mods->softcap > 0.0) x = mods->softcap * tanh(x / mods->softcap);
     if (mods->alibi_slopes) x += mods->alibi_slopes[h] * (double)(j - pos);
+    if (mods->prefix_lens && j < mods->prefix_lens[s]) x += mods->prefix_bias;
     return x;
 }
 
@@ -227,7 +229,7 @@ int oracle_attention_mod(const oracle_cache *c, const void *q, double *out, doub
                     const double *kr = Ks + (j * Hkv + kvh) * d;
                     double acc = 0.0;
                     for (int32_t e = 0; e < d; ++e) acc += widen(q, row * d + e, c->dtype) * kr[e];
-                    x[j] = modded(mods, scale * acc, h, pos, j);
+                    x[j] = modded(mods, scale * acc, s, h, pos, j);
                     if (x[j] > m) m = x[j];
                 }
                 if (m == -INFINITY) { if (lse) lse[row] = -INFINITY; free(x); continue; }   /* nothing visible */

@@ -102,6 +102,10 @@ int oracle_attention(const oracle_cache *c, const void *q, double *out, double *
  *   score:  x_j = scale * <q, k_j>
  *           x_j <- softcap * tanh(x_j / softcap)       if softcap > 0
  *           x_j <- x_j + alibi_slopes[h] * (j - pos)   if alibi_slopes (double[Hq])
+ * and one user-defined pair (mask_mod / score_mod as a caller may write them, Sec. II-C), the prefix-LM family:
+ *   mask:   j <= pos  or  j < prefix_lens[s]           if prefix_lens (int32[batch]): the first prefix_lens[s]
+ *                                   tokens see each other in both directions, the rest is causal
+ *   score:  x_j <- x_j + prefix_bias                   for the keys j < prefix_lens[s] (after the two above)
  * then softmax over the visible keys as above.  mods == NULL: no modification. */
 typedef struct {
     int32_t window;
@@ -109,6 +113,8 @@ typedef struct {
     const double *alibi_slopes;
     const int32_t *doc_ids;
     int64_t doc_stride;
+    const int32_t *prefix_lens;
+    double prefix_bias;
 } oracle_mods;
 
 int oracle_attention_mod(const oracle_cache *c, const void *q, double *out, double *lse,

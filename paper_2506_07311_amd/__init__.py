@@ -7,6 +7,7 @@ Nothing here computes attention on the CPU: without the HIP library the calls ra
 from .binding import (  # noqa: F401
     PA_GROW_EXACT,
     PA_GROW_POW2,
+    PA_MOD_PREFIX_LM,
     PagedAttnError,
     library_path,
     load_library,
@@ -36,4 +37,5 @@ from .binding import (  # noqa: F401
     prepare_decode_step,
     prepare_kv_append,
     prepare_prefill,
+    prefix_lm_data,
 )

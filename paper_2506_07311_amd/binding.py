@@ -267,10 +267,23 @@ def prepare_prefill(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table,
 
 class _Mods(ctypes.Structure):
     _fields_ = [("window", ctypes.c_int32), ("softcap", ctypes.c_float), ("alibi_slopes", ctypes.c_void_p),
-                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64)]
+                ("doc_ids", ctypes.c_void_p), ("doc_stride", ctypes.c_int64), ("user_mod", ctypes.c_int32),
+                ("user_data", ctypes.c_void_p)]
 
 
-def _mods(window, softcap, alibi_slopes, doc_ids, Hq, B):
+PA_MOD_PREFIX_LM = 1   # kId of pa_mod_prefix_lm in include/pagedattn_mods.h
+
+
+def prefix_lm_data(prefix_len: torch.Tensor, prefix_bias: float = 0.0) -> torch.Tensor:
+    """A pa_prefix_lm_data struct in device memory (pointer to int32[batch] prefix lengths, then the bias), to pass as
+    ``user_data`` with ``user_mod=PA_MOD_PREFIX_LM``.  The caller keeps ``prefix_len`` alive while the struct is in use."""
+    import struct
+    _i32(prefix_len, "prefix_len")
+    raw = struct.pack("<Qfi", prefix_len.data_ptr(), float(prefix_bias), 0)
+    return torch.tensor(list(raw), dtype=torch.uint8).to(prefix_len.device)
+
+
+def _mods(window, softcap, alibi_slopes, doc_ids, Hq, B, user_mod=0, user_data=None):
     if alibi_slopes is not None:
         _dense(alibi_slopes, "alibi_slopes", torch.float32)
         if tuple(alibi_slopes.shape) != (Hq,):
@@ -279,12 +292,16 @@ def _mods(window, softcap, alibi_slopes, doc_ids, Hq, B):
         _i32(doc_ids, "doc_ids")
         if doc_ids.dim() != 2 or doc_ids.shape[0] != B:
             raise PagedAttnError("doc_ids must be int32[batch, doc_stride]")
+    if user_mod and (user_data is None or not user_data.is_cuda):
+        raise PagedAttnError("a user modification needs its user_data in device memory")
     return _Mods(int(window), float(softcap), None if alibi_slopes is None else alibi_slopes.data_ptr(),
-                 None if doc_ids is None else doc_ids.data_ptr(), 0 if doc_ids is None else doc_ids.shape[1])
+                 None if doc_ids is None else doc_ids.data_ptr(), 0 if doc_ids is None else doc_ids.shape[1],
+                 int(user_mod), None if user_data is None else user_data.data_ptr())
 
 
 def paged_attention_decode_mod(k_cache, v_cache, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
                                window: int = 0, softcap: float = 0.0, alibi_slopes=None, doc_ids=None,
+                               user_mod: int = 0, user_data=None,
                                out=None, lse=None, workspace=None, head_major=False, stream=None):
     """paged_attention_decode with mask / score modifications (see pa_attn_mods in the header)."""
     lib = load_library()
@@ -297,7 +314,7 @@ def paged_attention_decode_mod(k_cache, v_cache, q, block_table, seq_lens, max_s
     out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
     if lse is not None:
         _dense(lse, "lse", torch.float32)
-    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B, user_mod, user_data)
     workspace = _workspace(workspace, paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len), q.device)
     st = lib.paged_attention_decode_mod(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
                                         ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]),
@@ -309,8 +326,9 @@ def paged_attention_decode_mod(k_cache, v_cache, q, block_table, seq_lens, max_s
 
 
 def prepare_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, max_seq_len: int, scale: float, *,
-                        window: int = 0, softcap: float = 0.0, alibi_slopes=None, doc_ids=None, out=None, lse=None,
-                        workspace=None, head_major=False, stream=None) -> PreparedCall:
+                        window: int = 0, softcap: float = 0.0, alibi_slopes=None, doc_ids=None, user_mod: int = 0,
+                        user_data=None, out=None, lse=None, workspace=None, head_major=False,
+                        stream=None) -> PreparedCall:
     """paged_decode_step (append of one new token per sequence + decode, one call) with its arguments marshalled once;
     the call returns ``out``."""
     lib = load_library()
@@ -328,14 +346,14 @@ def prepare_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens
         _dense(lse, "lse", torch.float32)
     if workspace is None:
         workspace = _workspace(None, paged_attention_workspace_bytes(B, Hq, hd, B, max_seq_len), q.device)
-    m = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    m = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B, user_mod, user_data)
     args = (ctypes.byref(d), _p(k_new), _p(v_new), _p(q), _p(out), _p(lse), _p(block_table), _p(seq_lens),
             ctypes.c_int32(B), ctypes.c_int32(Hq), ctypes.c_int32(block_table.shape[1]), ctypes.c_int32(max_seq_len),
             ctypes.c_float(scale), ctypes.byref(m), _p(workspace),
             ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     return PreparedCall(lib.paged_decode_step, args,
                         (d, m, k_cache, v_cache, k_new, v_new, q, out, lse, block_table, seq_lens, workspace,
-                         alibi_slopes, doc_ids), "paged_decode_step", out)
+                         alibi_slopes, doc_ids, user_data), "paged_decode_step", out)
 
 
 def paged_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, max_seq_len: int, scale: float,
@@ -347,8 +365,8 @@ def paged_decode_step(k_cache, v_cache, k_new, v_new, q, block_table, seq_lens, 
 
 def paged_attention_prefill_mod(k_cache, v_cache, q, cu_q_lens, max_q_len: int, block_table, seq_lens,
                                 max_seq_len: int, scale: float, causal: bool, *, window: int = 0,
-                                softcap: float = 0.0, alibi_slopes=None, doc_ids=None, out=None, lse=None,
-                                workspace=None, head_major=False, stream=None):
+                                softcap: float = 0.0, alibi_slopes=None, doc_ids=None, user_mod: int = 0,
+                                user_data=None, out=None, lse=None, workspace=None, head_major=False, stream=None):
     """paged_attention_prefill with mask / score modifications (see pa_attn_mods in the header)."""
     lib = load_library()
     d = cache_desc(k_cache, v_cache, head_major)
@@ -361,7 +379,7 @@ def paged_attention_prefill_mod(k_cache, v_cache, q, cu_q_lens, max_q_len: int, 
     out = torch.empty_like(q) if out is None else _dense(out, "out", q.dtype)
     if lse is not None:
         _dense(lse, "lse", torch.float32)
-    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B)
+    mods = _mods(window, softcap, alibi_slopes, doc_ids, Hq, B, user_mod, user_data)
     workspace = _workspace(workspace, paged_attention_workspace_bytes(B, Hq, hd, total_q, max_seq_len), q.device)
     st = lib.paged_attention_prefill_mod(ctypes.byref(d), _p(q), _p(out), _p(lse), _p(cu_q_lens),
                                          ctypes.c_int32(total_q), ctypes.c_int32(max_q_len), _p(block_table),

@@ -18,7 +18,7 @@ SOURCES = ["api.hip", "kv_copy.hip", "attention_generic.hip", "merge.hip", "deco
            "page_pool.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "prefill_tiles.h"),
            os.path.join(CSRC, "decode_mfma_impl.h"), os.path.join(CSRC, "prefill_mfma_impl.h"),
-           os.path.join(HERE, "..", "include", "pagedattn.h")]
+           os.path.join(HERE, "..", "include", "pagedattn.h"), os.path.join(HERE, "..", "include", "pagedattn_mods.h")]
 # packed-fp32 VALU forms are disabled on purpose (they have produced wrong results on these machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

@@ -69,6 +69,15 @@ inline int elem_bytes(pa_dtype t) { return t == PA_DTYPE_F32 ? 4 : 2; }
 
 bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 
+// Is `id` the kId of a user modification the library was built with?
+bool user_mod_known(int32_t id)
+{
+#define PA_USER_CASE(U) if (id == U::kId) return true;
+    PA_USER_MODS(PA_USER_CASE)
+#undef PA_USER_CASE
+    return false;
+}
+
 }  // namespace
 
 pa_status check_cache(const pa_kv_cache_desc* c)
@@ -332,10 +341,13 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     if (((uintptr_t)q | (uintptr_t)out) & 15) return PA_ERR_UNSUPPORTED;
     if ((int64_t)max_blocks * cache->page_size < max_seq_len) return PA_ERR_INVALID_ARG;
     if (!(scale == scale)) return PA_ERR_INVALID_ARG;
-    ModArgs m = {0, 0.f, nullptr, nullptr, 0};
+    ModArgs m = {0, 0.f, nullptr, nullptr, 0, 0, nullptr};
     if (mods) {
         if (mods->window < 0 || !(mods->softcap >= 0.f) || mods->softcap > 3.0e38f) return PA_ERR_INVALID_ARG;
         if (mods->doc_ids && mods->doc_stride < max_seq_len) return PA_ERR_INVALID_ARG;
+        if (mods->user_mod != 0 && !user_mod_known(mods->user_mod)) return PA_ERR_INVALID_ARG;
+        m.user_mod = mods->user_mod;
+        m.user_data = mods->user_mod ? mods->user_data : nullptr;
         m.window = mods->window;
         m.softcap = mods->softcap;
         m.alibi_slopes = mods->alibi_slopes;
@@ -377,7 +389,7 @@ pa_status run_attention(const pa_kv_cache_desc* cache, const void* q, void* out,
     a.seg_first = a.seg_last = nullptr;
     a.skip_small = 0;
     a.mods = m;
-    a.has_mods = m.window > 0 || m.softcap > 0.f || m.alibi_slopes || m.doc_ids;
+    a.has_mods = m.window > 0 || m.softcap > 0.f || m.alibi_slopes || m.doc_ids || m.user_mod != 0;
     a.k_new = k_new;
     a.v_new = v_new;
     a.short_nsplit = 1;

@@ -161,6 +161,8 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
         my_doc = doc[ri.pos];
     }
 
+    const pa_mod_ctx uc = {mods.user_data, s, h, ri.pos, ri.len};   // what a user modification's hooks are told
+    (void)uc;
     const int32_t G = num_q_heads / cache.num_kv_heads;
     const int32_t kvh = h / G;
     for (int e = tid; e < d; e += kThreads) q_s[e] = V::load1(q, o_idx * d + e);
@@ -225,6 +227,7 @@ __global__ __launch_bounds__(kThreads) void paged_attention_generic_kernel(
                 sj += (score_t)slope * (score_t)(j - ri.pos);
             }
             if (M::kDoc && doc && doc[j] != my_doc) sj = -INFINITY;
+            if (M::kUser) sj = user_score<M>(uc, j, sj);   // in the score type: fp64 for fp32 pools
             sc[jj] = sj;
             lmax = sj > lmax ? sj : lmax;
         }
@@ -296,7 +299,18 @@ pa_status launch_attention_generic(const AttnArgs& a, hipStream_t stream)
                  int32_t, int32_t, float, int32_t, float*, float*, int32_t, int32_t, ModArgs, const void*,
                  const void*) = nullptr;
     typedef Mods<true, true, false> WindowScore;
-    if (a.dtype == PA_DTYPE_F32)
+    if (a.mods.user_mod) {                                // a user modification: one instantiation per listed struct
+#define PA_USER_CASE(U)                                                                                 \
+        if (a.mods.user_mod == U::kId) {                                                                \
+            typedef Mods<true, true, true, U> UM;                                                       \
+            kern = a.dtype == PA_DTYPE_F32    ? paged_attention_generic_kernel<float, UM>               \
+                   : a.dtype == PA_DTYPE_BF16 ? paged_attention_generic_kernel<bf16_tag, UM>            \
+                                              : paged_attention_generic_kernel<f16_tag, UM>;            \
+        }
+        PA_USER_MODS(PA_USER_CASE)
+#undef PA_USER_CASE
+        if (!kern) return PA_ERR_INVALID_ARG;
+    } else if (a.dtype == PA_DTYPE_F32)
         kern = hooks == 0   ? paged_attention_generic_kernel<float, NoMods>
                : hooks == 1 ? paged_attention_generic_kernel<float, WindowScore>
                             : paged_attention_generic_kernel<float, AllMods>;

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/pagedattn.h"
+#include "../../include/pagedattn_mods.h"
 
 namespace pa {
 
@@ -102,14 +103,23 @@ struct ModArgs {
     const float* alibi_slopes;   // null = off
     const int32_t* doc_ids;      // null = off
     int64_t doc_stride;
+    int32_t user_mod;            // kId of a user modification (pagedattn_mods.h), 0 = off
+    const void* user_data;
 };
 
-template <bool WINDOW, bool SCORE, bool DOC>
+// U: a user modification struct of pagedattn_mods.h, or NoUser.  A user modification comes with every built-in hook
+// compiled in (its instantiation is Mods<true, true, true, U>); a hook whose argument is absent does nothing.
+struct NoUser {
+    static constexpr int32_t kId = 0;
+};
+template <bool WINDOW, bool SCORE, bool DOC, typename U = NoUser>
 struct Mods {
     static constexpr bool kWindow = WINDOW;   // sliding window
     static constexpr bool kScore = SCORE;     // soft cap and / or linear position bias
     static constexpr bool kDoc = DOC;         // document mask
-    static constexpr bool kAny = WINDOW || SCORE || DOC;
+    static constexpr bool kUser = U::kId != 0;
+    static constexpr bool kAny = WINDOW || SCORE || DOC || kUser;
+    typedef U User;
 };
 typedef Mods<false, false, false> NoMods;
 typedef Mods<true, true, true> AllMods;
@@ -261,6 +271,19 @@ struct ElemF16 {
                                                       0);
     }
 };
+
+// User hooks of a policy M on the score x (natural units) of key j; the key handed to the hooks is clamped to the
+// context (tiles are padded with clamped keys whose scores the length mask removes anyway).
+template <typename M, typename F>
+__device__ __forceinline__ F user_score(const pa_mod_ctx& c, int32_t j, F x)
+{
+    if constexpr (M::kUser) {
+        const int32_t jc = min(j, c.len - 1);
+        return M::User::visible(c, jc) ? M::User::score(c, jc, x) : (F)-INFINITY;
+    } else {
+        return x;
+    }
+}
 
 // Which sequence a packed query row belongs to and how many keys it may see.  cu_q_lens is the
 // prefix-sum vector of Sec. III-B (null for decode, where row == sequence).  Query i of a sequence with

@@ -102,7 +102,8 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
 #pragma unroll
         for (int mt = 0; mt < GE::kBlocks; ++mt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) t.doc[mt][i] = a.doc[min(t0 + 16 * mt + 4 * a.quad + i, c1 - 1)];
+            for (int i = 0; i < 4; ++i)
+                t.doc[mt][i] = a.doc ? a.doc[min(t0 + 16 * mt + 4 * a.quad + i, c1 - 1)] : 0;   // no ids: one document
     }
     if constexpr (UNIFORM) {
         if (t0 + kTileKeys <= c1) {   // full tile: 16-key blocks, each inside one page
@@ -181,6 +182,7 @@ struct RowMods {
     float cap_out;      // score: softcap * log2(e)
     float scale;        // score: plain scale (the unmodified path folds log2(e) into it)
     int32_t doc;        // document mask: the row's own document id
+    pa_mod_ctx uc;      // user modification: what its hooks are told about the row
 };
 
 // lim = first key this lane's row may not see (the segment end, or less under a per-row causal bound);
@@ -224,6 +226,7 @@ __device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, c
             } else {
                 x = s[mt][i] * sc;
             }
+            if (M::kUser) x = user_score<M>(rm.uc, key, x * kLn2) * kLog2e;   // hooks work in natural units
             if (partial && key >= lim) x = -INFINITY;   // mask by selection
             if (below && key < rm.lo) x = -INFINITY;
             if (M::kDoc && t.doc[mt][i] != rm.doc) x = -INFINITY;
@@ -475,7 +478,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         rm.cap_out = 0.f;
         rm.scale = scale;
         rm.doc = 0;
-        if (M::kDoc) {
+        if (M::kDoc && mods.doc_ids) {
             a.doc = mods.doc_ids + (int64_t)s * mods.doc_stride;
             rm.doc = a.doc[max(pos, 0)];
         }
@@ -494,6 +497,7 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_mfma_kernel(
         }
         const int32_t mask_from = RAGGED ? c1 - 16 : c1;   // q_len <= 16: no bound lies further below the end
         const int32_t h = kvh * G + (RAGGED ? min(r16, rows - 1) - qi * G : h0 + min(r16, rows - 1));
+        rm.uc = pa_mod_ctx{mods.user_data, s, h, pos, len};
         const int64_t o_idx = (int64_t)q_row * num_q_heads + h;
         a.table = block_table + (int64_t)s * max_blocks;
         if constexpr (FUSED) {
@@ -714,10 +718,11 @@ __global__ __launch_bounds__(NW * 64) void paged_decode_short_kernel(
         rm.cap_out = 0.f;
         rm.scale = scale;
         rm.doc = 0;
-        if (M::kDoc) {
+        if (M::kDoc && mods.doc_ids) {
             a.doc = mods.doc_ids + (int64_t)s * mods.doc_stride;
             rm.doc = a.doc[pos];
         }
+        rm.uc = pa_mod_ctx{mods.user_data, s, kvh * G + h0 + min(r16, rows - 1), pos, len};
         if (M::kWindow && window > 0) {
             rm.lo = pos - window + 1;
             rm.lo_until = len - window;
@@ -924,6 +929,17 @@ void launch_decode_short_dim(const AttnArgs& a, hipStream_t stream)
     typedef Geo<D> GE;
     constexpr int NW = D > 128 ? 4 : 8;                 // head_dim 256: two tiles take about 250 registers
     const bool docs = a.has_mods && a.mods.doc_ids;
+    if (a.mods.user_mod) {                              // a user modification: one instantiation per listed struct
+#define PA_USER_CASE(U)                                                                        \
+        if (a.mods.user_mod == U::kId) {                                                       \
+            if (a.dtype == PA_DTYPE_BF16) launch_short_nw<NW, ElemBf16, Mods<true, true, true, U>, GE>(a, stream);  \
+            else launch_short_nw<NW, ElemF16, Mods<true, true, true, U>, GE>(a, stream);       \
+            return;                                                                            \
+        }
+        PA_USER_MODS(PA_USER_CASE)
+#undef PA_USER_CASE
+        return;
+    }
     if (a.dtype == PA_DTYPE_BF16) {
         if (docs) launch_short_nw<NW, ElemBf16, AllMods, GE>(a, stream);
         else if (a.has_mods) launch_short_nw<NW, ElemBf16, WindowScore, GE>(a, stream);
@@ -941,6 +957,17 @@ void launch_decode_mfma_dim(const AttnArgs& a, hipStream_t stream)
     typedef Mods<true, true, false> WindowScore;
     typedef Geo<D> GE;
     const bool docs = a.has_mods && a.mods.doc_ids;
+    if (a.mods.user_mod) {
+#define PA_USER_CASE(U)                                                                        \
+        if (a.mods.user_mod == U::kId) {                                                       \
+            if (a.dtype == PA_DTYPE_BF16) launch_em<ElemBf16, Mods<true, true, true, U>, GE>(a, stream);  \
+            else launch_em<ElemF16, Mods<true, true, true, U>, GE>(a, stream);                 \
+            return;                                                                            \
+        }
+        PA_USER_MODS(PA_USER_CASE)
+#undef PA_USER_CASE
+        return;
+    }
     if (a.dtype == PA_DTYPE_BF16) {
         if (docs) launch_em<ElemBf16, AllMods, GE>(a, stream);
         else if (a.has_mods) launch_em<ElemBf16, WindowScore, GE>(a, stream);

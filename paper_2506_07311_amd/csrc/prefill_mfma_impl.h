@@ -167,6 +167,7 @@ struct RowMods {
     float cap_in;       // score: scale / softcap, 0 without a cap
     float cap_out;      // score: softcap * log2(e)
     int32_t doc;        // document mask: the row's own document id
+    pa_mod_ctx uc;      // user modification: what its hooks are told about the row
 };
 
 // M: compile-time policy of the hooks.  With score hooks the scores are first rewritten in place as
@@ -195,6 +196,11 @@ __device__ __forceinline__ void half_softmax(f32x16& p, f32x16& s, f32x16 (&o)[T
             s[r] = x + __builtin_fmaf(rm.slope2, (float)(8 * (r / 4) + (r % 4)), b0);
         }
         sc = 1.f;
+    }
+    if (M::kUser) {   // (a user modification is compiled with the score hooks: the scores are in the log2 domain here)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            s[r] = user_score<M>(rm.uc, key0 + 8 * (r / 4) + (r % 4), s[r] * kLn2) * kLog2e;
     }
     const bool below = M::kWindow && key0 < rm.lo_until;      // wave-uniform up to the lane's 4-key offset
 #pragma unroll
@@ -442,7 +448,8 @@ __device__ __forceinline__ void prefill_body(
     if (causal) n_first = min(len, len - q_len + (m0 >> lg) + 1);
     if (window > 0) n_first = min(n_first, causal ? window : 2 * window - 1);
     const bool few_keys = n_first <= precise_keys ||
-                          (M::kScore && plan.mods.alibi_slopes != nullptr) || (M::kDoc && plan.mods.doc_ids != nullptr);
+                          (M::kScore && plan.mods.alibi_slopes != nullptr) || (M::kDoc && plan.mods.doc_ids != nullptr) ||
+                          M::kUser;
     if (few_keys != PRECISE) return;                        // the other instantiation handles this tile
     // this workgroup's chunk of the context; with a split, chunks without keys leave nothing behind (the merge
     // reads only the chunks that hold keys of a row)
@@ -490,10 +497,11 @@ __device__ __forceinline__ void prefill_body(
     rm.cap_out = 0.f;
     rm.doc = 0;
     const int32_t* doc_row = nullptr;
-    if (M::kDoc) {
+    if (M::kDoc && plan.mods.doc_ids) {
         doc_row = plan.mods.doc_ids + (int64_t)s * plan.mods.doc_stride;
         rm.doc = doc_row[max(pos, 0)];
     }
+    rm.uc = pa_mod_ctx{plan.mods.user_data, s, h, pos, len};
     int32_t lo_wave = 0;                                     // tiles that end at or before it hold nothing for the wave
     if (window > 0) {
         rm.lo = pos - window + 1;
@@ -589,7 +597,7 @@ __device__ __forceinline__ void prefill_body(
         const int32_t mx = __builtin_amdgcn_readfirstlane(d[kBN + 1]);
         return mx >= row_doc_min && mn <= row_doc_max;
     };
-    auto tile_ids = [&](int32_t t0) -> int32_t { return doc_row[min(t0 + lane, last_key)]; };
+    auto tile_ids = [&](int32_t t0) -> int32_t { return doc_row ? doc_row[min(t0 + lane, last_key)] : 0; };
     if (M::kDoc) wave_range(rm.doc, row_doc_min, row_doc_max);
     PageIds ids;
     const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
@@ -705,7 +713,23 @@ pa_status launch_prefill_mfma_dim(const AttnArgs& a, const PrefillPlan& plan, in
     if (D > 128 && !uniform) return PA_ERR_UNSUPPORTED;   // 512-byte rows: two rows per load must share a page
     typedef Mods<true, true, false> WindowScore;
     auto kern = paged_prefill_mfma_kernel<true, ElemBf16, NoMods, D>;
-    if (a.has_mods && a.mods.doc_ids) {
+    if (a.mods.user_mod) {                                // a user modification: one instantiation per listed struct
+        bool found = false;
+#define PA_USER_CASE(U)                                                                                     \
+        if (a.mods.user_mod == U::kId) {                                                                    \
+            typedef Mods<true, true, true, U> UM;                                                           \
+            found = true;                                                                                   \
+            if (a.dtype == PA_DTYPE_BF16)                                                                   \
+                kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, UM, D>                           \
+                               : paged_prefill_mfma_kernel<false, ElemBf16, UM, D>;                         \
+            else                                                                                            \
+                kern = uniform ? paged_prefill_mfma_kernel<true, ElemF16, UM, D>                            \
+                               : paged_prefill_mfma_kernel<false, ElemF16, UM, D>;                          \
+        }
+        PA_USER_MODS(PA_USER_CASE)
+#undef PA_USER_CASE
+        if (!found) return PA_ERR_INVALID_ARG;
+    } else if (a.has_mods && a.mods.doc_ids) {
         if (a.dtype == PA_DTYPE_BF16)
             kern = uniform ? paged_prefill_mfma_kernel<true, ElemBf16, AllMods, D>
                            : paged_prefill_mfma_kernel<false, ElemBf16, AllMods, D>;

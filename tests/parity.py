@@ -40,7 +40,8 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 
 def oracle_step(oracle, w: W.PagedWorkload, append=True, mods=None):
     """Append (Algorithm 1, Assign) then attention on host copies.  Returns (k_cache, v_cache, out, lse).
-    mods: dict with any of window, softcap, alibi_slopes (numpy [Hq]), doc_ids (numpy int32 [B, stride])."""
+    mods: dict with any of window, softcap, alibi_slopes (numpy [Hq]), doc_ids (numpy int32 [B, stride]),
+    prefix_lens (numpy int32 [B]) and prefix_bias (the prefix-LM user modification)."""
     k, v = W.to_numpy(w.k_cache).copy(), W.to_numpy(w.v_cache).copy()
     bt = W.to_numpy(w.block_table)
     if append and w.seq_ids.numel():
@@ -62,6 +63,11 @@ def gpu_step(pa, w: W.PagedWorkload, append=True, prefill=None, with_lse=True, m
             kw["alibi_slopes"] = torch.tensor(np.asarray(mods["alibi_slopes"]), dtype=torch.float32, device=dev)
         if mods.get("doc_ids") is not None:
             kw["doc_ids"] = torch.tensor(np.asarray(mods["doc_ids"]), dtype=torch.int32, device=dev)
+        if mods.get("prefix_lens") is not None:
+            from paper_2506_07311_amd import binding
+            prefix = torch.tensor(np.asarray(mods["prefix_lens"]), dtype=torch.int32, device=dev)
+            kw["user_mod"] = binding.PA_MOD_PREFIX_LM
+            kw["user_data"] = binding.prefix_lm_data(prefix, mods.get("prefix_bias", 0.0))
     if prefill is None:
         prefill = w.causal or w.max_q_len > 1 or w.total_q != w.batch
     step_call = step_call and append and not prefill and w.k_new.shape[0] == w.batch

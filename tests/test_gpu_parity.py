@@ -1048,6 +1048,49 @@ def test_windowed_decode_split_schedules(pa, oracle, wgs):
         binding.pa_set_option("decode_workgroups", 0)
 
 
+# ----------------------------------------------------------------------------- user-defined modifications
+@pytest.mark.parametrize("dtype,d,P", [(torch.bfloat16, 128, 16), (torch.float16, 64, 4), (torch.bfloat16, 256, 64),
+                                       (torch.float32, 64, 16), (torch.bfloat16, 96, 16)])
+@pytest.mark.parametrize("extra", [dict(), dict(window=700, softcap=3.0, alibi=True, docs=True)], ids=["alone", "with_built_ins"])
+@pytest.mark.parametrize("bias", [0.0, 0.8])
+def test_prefix_lm_user_modification_in_prefill(pa, oracle, dtype, d, P, extra, bias):
+    """The prefix-LM pair of include/pagedattn_mods.h -- implemented only through the extension contract -- on every
+    prefill kernel (matrix cores for head_dim 64 / 128 / 256, portable kernel for fp32 and head_dim 96): prefixes
+    inside a sequence, empty, covering it, and past the queries' first position; ragged query counts."""
+    lens = [700, 130, 1500, 64, 333]
+    q_lens = [700, 100, 600, 64, 1]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=16, num_kv_heads=4, head_dim=d, page_size=P,
+                        dtype=dtype, causal=False, seed=180, device=DEV)
+    mods = build_mods(extra, 16, lens) if extra else {}
+    mods["prefix_lens"] = np.array([256, 0, 1200, 64, 100], dtype=np.int32)
+    mods["prefix_bias"] = bias
+    tol = (2e-2, 2e-2) if dtype == torch.bfloat16 else None   # rows concentrated on few keys: bf16 ulp at |out| >= 4
+    parity.check_step(pa, oracle, w, f"prefix-LM prefill {dtype} d={d} {extra} bias={bias}", mods=mods, tol=tol)
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float16, 64), (torch.bfloat16, 256), (torch.float32, 64)])
+def test_prefix_lm_user_modification_in_decode(pa, oracle, dtype, d, decode_route):
+    """The same pair through the decode entry points (tile stream, one launch with and without a split context,
+    portable kernel) and the step call: every key is visible to the last position, the score hook still acts."""
+    lens = [700, 130, 2500, 64, 333, 1]
+    w = W.make_workload("t", seq_lens=lens, num_q_heads=16, num_kv_heads=4, head_dim=d, page_size=16, dtype=dtype,
+                        seed=181, device=DEV)
+    mods = dict(prefix_lens=np.array([256, 0, 1200, 64, 100, 1], dtype=np.int32), prefix_bias=-1.5)
+    for step_call in (False, True):
+        parity.check_step(pa, oracle, w, f"prefix-LM decode {dtype} d={d} step={step_call}", mods=mods,
+                          step_call=step_call)
+
+
+def test_unknown_user_modification_is_rejected(pa):
+    from paper_2506_07311_amd import binding
+    w = W.make_workload("t", seq_lens=[64, 64], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                        dtype=torch.bfloat16, seed=182, device=DEV)
+    data = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.PagedAttnError, match="invalid argument"):
+        pa.paged_attention_decode_mod(w.k_cache, w.v_cache, w.q, w.block_table, w.seq_lens, w.max_seq_len, w.scale,
+                                      user_mod=77, user_data=data)
+
+
 def test_hooks_switched_off_equal_the_plain_entry_points(pa):
     w = W.make_workload("t", seq_lens=[700, 64, 300], num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
                         dtype=torch.bfloat16, seed=73, device=DEV)

@@ -39,7 +39,7 @@ def test_binary16_widening_matches_numpy_on_every_bit_pattern(oracle):
     assert (np.signbit(got[~nan]) == np.signbit(ref[~nan])).all()
 
 
-def dense_reference(w, window=0, softcap=0.0, slopes=None, docs=None):
+def dense_reference(w, window=0, softcap=0.0, slopes=None, docs=None, prefix=None, prefix_bias=0.0):
     """Contiguous-layout reference: identity pages, so sequence s occupies pool rows [start_s, start_s + len)."""
     assert w.page_size * w.num_pages >= sum(w.seq_lens_host)
     Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -62,12 +62,16 @@ def dense_reference(w, window=0, softcap=0.0, slopes=None, docs=None):
         if docs is not None:
             dd = np.asarray(docs[s][:L])
             mask &= dd[None, :] == dd[np.arange(L - Tq, L)][:, None]
+        if prefix is not None:                                # prefix-LM: bidirectional prefix, causal remainder
+            mask &= (j <= pos) | (j < prefix[s])
         for h in range(Hq):
             x = w.scale * Q[q0:q0 + Tq, h] @ K[start:start + L, h // G].T
             if softcap > 0:
                 x = softcap * np.tanh(x / softcap)
             if slopes is not None:
                 x = x + slopes[h] * (j - pos)
+            if prefix is not None:
+                x = x + prefix_bias * (j < prefix[s])
             x = np.where(mask, x, -np.inf)
             any_key = mask.any(axis=1)
             p = np.zeros_like(x)
@@ -125,6 +129,46 @@ def test_oracle_matches_dense_numpy_reference(oracle, dtype, causal, mods):
     finite = np.isfinite(ref_l)
     assert (np.isfinite(lse) == finite).all()
     np.testing.assert_allclose(lse[finite], ref_l[finite], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("extra", [dict(), dict(window=9, softcap=2.0, slopes=True, docs=True)])
+@pytest.mark.parametrize("bias", [0.0, 0.75])
+def test_prefix_lm_family_matches_dense_numpy_reference(oracle, dtype, extra, bias):
+    """The user-defined pair of the extension point (visible: j <= pos or j < prefix_len; score: + bias on prefix
+    keys), alone and on top of the built-in hooks, against explicit mask and bias matrices."""
+    w = contiguous_workload(dtype, False, seed=12)
+    prefix = np.array([20, 0, 50], dtype=np.int32)           # inside, empty, and covering the whole sequence
+    slopes = np.array([2.0 ** -(h + 1) for h in range(w.num_q_heads)]) if extra.get("slopes") else None
+    docs = doc_ids_for(w, 6) if extra.get("docs") else None
+    kw = dict(window=extra.get("window", 0), softcap=extra.get("softcap", 0.0), alibi_slopes=slopes, doc_ids=docs)
+    out, lse = run(oracle, w, prefix_lens=prefix, prefix_bias=bias, **kw)
+    ref_o, ref_l = dense_reference(w, window=kw["window"], softcap=kw["softcap"], slopes=slopes, docs=docs,
+                                   prefix=prefix, prefix_bias=bias)
+    np.testing.assert_allclose(out, ref_o, rtol=0, atol=1e-12)
+    finite = np.isfinite(ref_l)
+    assert (np.isfinite(lse) == finite).all()
+    np.testing.assert_allclose(lse[finite], ref_l[finite], rtol=0, atol=1e-12)
+
+
+def test_prefix_lm_special_cases(oracle):
+    """A prefix of length 0 is the causal mask; a prefix that covers the sequence is no mask at all; a bias on a
+    prefix that covers every visible key shifts lse by the bias and leaves the output alone."""
+    w = contiguous_workload(torch.float32, False, seed=13)
+    causal_w = contiguous_workload(torch.float32, True, seed=13)
+    zero = np.zeros(w.batch, dtype=np.int32)
+    full = np.array(w.seq_lens_host, dtype=np.int32)
+    o_causal, l_causal = run(oracle, causal_w)
+    o_zero, l_zero = run(oracle, w, prefix_lens=zero)
+    np.testing.assert_array_equal(o_zero, o_causal)
+    np.testing.assert_array_equal(l_zero, l_causal)
+    o_plain, l_plain = run(oracle, w)
+    o_full, l_full = run(oracle, w, prefix_lens=full)
+    np.testing.assert_array_equal(o_full, o_plain)
+    np.testing.assert_array_equal(l_full, l_plain)
+    o_b, l_b = run(oracle, w, prefix_lens=full, prefix_bias=1.25)
+    np.testing.assert_allclose(o_b, o_plain, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(l_b, l_plain + 1.25, rtol=0, atol=1e-12)
 
 
 def test_neutral_modifications_change_nothing(oracle):
