@@ -37,16 +37,21 @@ namespace {
 typedef mfma_f32x4 f32x4;
 
 // Tile geometry per head_dim.  A wave's tile is kBlocks blocks of 16 keys; a K row is read in KS steps of 32
-// elements; a lane's V loads cover 4 keys per block and kPasses 16-byte column pieces (piece = lane%16 + 16*pass).
-//   D = 64:  rows hold 8 pieces, so lanes 8-15 of each 16 repeat the loads of lanes 0-7 and the matching half of
-//            every P.V result (output rows 8-15) is unused -- the matrix cores idle in this kernel anyway.
+// elements; a lane's V loads cover 4 keys of each of kVBlocks blocks and kPasses 16-byte column pieces (piece =
+// lane%16 + 16*pass).
+//   D = 64:  rows hold 8 pieces, so only 8 of every 16 lanes can differ in piece.  Lanes 8-15 therefore load the V rows
+//            of a SECOND pair of blocks (a tile is 64 keys: blocks 0, 1 for lanes 0-7, blocks 2, 3 for lanes 8-15) --
+//            every load brings bytes nobody else loads -- and the value product runs twice per column, once as loaded
+//            with the weights of blocks 0, 1 and once with the two lane halves swapped (a DPP rotate by 8) with the
+//            weights of blocks 2, 3; accumulator rows 8-15 gather products of mismatched halves and are never stored.
 //   D = 256: two column passes; tiles of 16 keys keep two tiles in registers (the second block's contraction slots
 //            carry zero weights and zero values).
 template <int D>
 struct Geo {
     static constexpr int kD = D;
     static constexpr int kKS = D / 32;
-    static constexpr int kBlocks = D == 256 ? 1 : 2;
+    static constexpr int kBlocks = D == 256 ? 1 : D == 64 ? 4 : 2;
+    static constexpr int kVBlocks = D == 256 ? 1 : 2;
     static constexpr int kTileKeys = 16 * kBlocks;
     static constexpr int kPasses = D == 256 ? 2 : 1;
     static constexpr int kPieceMask = D == 64 ? 7 : 15;
@@ -64,7 +69,7 @@ __device__ __forceinline__ uint32_t word(const uint4& v, int w)
 template <typename GE>
 struct Tile {
     uint4 k[GE::kBlocks][GE::kKS];        // [16-key block][32-element step of head_dim]: lane%16 = key, lane/16 = 8-element piece
-    uint4 v[GE::kPasses][4 * GE::kBlocks];   // 4 keys per block x 8 head_dim columns per lane and pass
+    uint4 v[GE::kPasses][4 * GE::kVBlocks];  // 4 keys per block x 8 head_dim columns per lane and pass
     int32_t doc[GE::kBlocks][4];             // document ids of the lane's 4 score keys per block (document masks only)
 };
 
@@ -105,8 +110,12 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
             for (int i = 0; i < 4; ++i)
                 t.doc[mt][i] = a.doc ? a.doc[min(t0 + 16 * mt + 4 * a.quad + i, c1 - 1)] : 0;   // no ids: one document
     }
+    // which of the tile's blocks this lane's V loads belong to: block mt for lanes 0-7 of 16 and, at head_dim 64,
+    // block mt + 2 for lanes 8-15
+    const int32_t vshift = (GE::kD == 64) ? 2 * (a.r16 >> 3) : 0;
     if constexpr (UNIFORM) {
         if (t0 + kTileKeys <= c1) {   // full tile: 16-key blocks, each inside one page
+            int64_t blk[GE::kBlocks];                          // byte offset of each block's first row in its pool
 #pragma unroll
             for (int mt = 0; mt < GE::kBlocks; ++mt) {
                 const int32_t kb = t0 + 16 * mt;
@@ -116,28 +125,30 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
                     page = __builtin_amdgcn_readlane(a.ids, rel);
                 else
                     page = __builtin_amdgcn_readfirstlane(a.table[kb >> a.log2_page]);
-                const int64_t blk = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
-                const char* kp = a.kbase + blk;
-                const char* vp = a.vbase + blk;
-                if constexpr (FUSED) {
-                    const char* kl = kb + a.r16 == a.new_pos ? a.knew + a.quad * 16 : kp + a.koff;
+                blk[mt] = page * a.page_bytes + (int64_t)(kb & a.pmask) * a.token_bytes;
+            }
 #pragma unroll
-                    for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kl + 64 * ks);
+            for (int mt = 0; mt < GE::kBlocks; ++mt) {
+                const int32_t kb = t0 + 16 * mt;
+                const char* kp = a.kbase + blk[mt];
+                const char* kl = (FUSED && kb + a.r16 == a.new_pos) ? a.knew + a.quad * 16 : kp + a.koff;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const char* vl = kb + 4 * a.quad + i == a.new_pos ? a.vnew + (a.r16 & GE::kPieceMask) * 16
-                                                                          : vp + a.voff[i];
+                for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kl + 64 * ks);
+            }
 #pragma unroll
-                        for (int c = 0; c < GE::kPasses; ++c) t.v[c][4 * mt + i] = load16(vl + 256 * c);
-                    }
-                    continue;
+            for (int mt = 0; mt < GE::kVBlocks; ++mt) {
+                const char* vp = a.vbase + blk[mt];
+                if constexpr (GE::kD == 64) {
+                    if (vshift) vp = a.vbase + blk[mt + 2];
                 }
+                const int32_t kb = t0 + 16 * (mt + vshift);
 #pragma unroll
-                for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + a.koff + 64 * ks);
+                for (int i = 0; i < 4; ++i) {
+                    const char* vl = (FUSED && kb + 4 * a.quad + i == a.new_pos) ? a.vnew + (a.r16 & GE::kPieceMask) * 16
+                                                                                 : vp + a.voff[i];
 #pragma unroll
-                for (int c = 0; c < GE::kPasses; ++c)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) t.v[c][4 * mt + i] = load16(vp + a.voff[i] + 256 * c);
+                    for (int c = 0; c < GE::kPasses; ++c) t.v[c][4 * mt + i] = load16(vl + 256 * c);
+                }
             }
             return;
         }
@@ -152,9 +163,12 @@ __device__ __forceinline__ void load_tile(Tile<GE>& t, const Addr& a, int32_t t0
         if (FUSED && key == a.new_pos) kp = a.knew + a.quad * 16;
 #pragma unroll
         for (int ks = 0; ks < GE::kKS; ++ks) t.k[mt][ks] = load16(kp + 64 * ks);
+    }
+#pragma unroll
+    for (int mt = 0; mt < GE::kVBlocks; ++mt) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int32_t vkey = min(t0 + 16 * mt + 4 * a.quad + i, last);
+            const int32_t vkey = min(t0 + 16 * (mt + vshift) + 4 * a.quad + i, last);
             const int64_t vpage = a.table[vkey >> a.log2_page];
             const char* vp = a.vbase + vpage * a.page_bytes + (int64_t)(vkey & a.pmask) * a.token_bytes +
                              (a.r16 & GE::kPieceMask) * 16;
@@ -194,7 +208,7 @@ __device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, c
 {
     constexpr int kTileKeys = GE::kTileKeys;
     constexpr int kBlocks = GE::kBlocks;
-    f32x4 s[2];
+    f32x4 s[kBlocks < 2 ? 2 : kBlocks];
     s[1] = f32x4{0.f, 0.f, 0.f, 0.f};                  // a block the tile does not have: zero weights
 #pragma unroll
     for (int mt = 0; mt < kBlocks; ++mt) {
@@ -257,19 +271,25 @@ __device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, c
 #pragma unroll
             for (int j = 0; j < 8; ++j) st.o[c][j] *= alpha;
     }
-    // Probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4).
-    // They are carried as TWO bf16 terms (p = hi + lo, lo = bf16(p - hi)): the matrix cores idle most of the
-    // time in this HBM-bound kernel, so the second product is free and removes the 2^-9 weight rounding that
+    // Probabilities as the B operand: contraction slot 8*quad + e <-> key (e<4 ? 4*quad+e : 16+4*quad+e-4) of a pair
+    // of blocks.  They are carried as TWO bf16 terms (p = hi + lo, lo = bf16(p - hi)): the matrix cores idle most of
+    // the time in this HBM-bound kernel, so the second product is free and removes the 2^-9 weight rounding that
     // would otherwise dominate the error of short contexts.
-    uint4 pb, pl;
-    pb.x = E::pack(s[0][0], s[0][1]);
-    pb.y = E::pack(s[0][2], s[0][3]);
-    pb.z = E::pack(s[1][0], s[1][1]);
-    pb.w = E::pack(s[1][2], s[1][3]);
-    pl.x = E::pack(s[0][0] - E::lo_of(pb.x), s[0][1] - E::hi_of(pb.x));
-    pl.y = E::pack(s[0][2] - E::lo_of(pb.y), s[0][3] - E::hi_of(pb.y));
-    pl.z = E::pack(s[1][0] - E::lo_of(pb.z), s[1][1] - E::hi_of(pb.z));
-    pl.w = E::pack(s[1][2] - E::lo_of(pb.w), s[1][3] - E::hi_of(pb.w));
+    constexpr int kPairs = kBlocks < 2 ? 1 : kBlocks / 2;   // pairs of blocks: 2 at head_dim 64, else 1
+    uint4 pb[kPairs], pl[kPairs];
+#pragma unroll
+    for (int pr = 0; pr < kPairs; ++pr) {
+        const f32x4& s0 = s[2 * pr];
+        const f32x4& s1 = s[2 * pr + 1];
+        pb[pr].x = E::pack(s0[0], s0[1]);
+        pb[pr].y = E::pack(s0[2], s0[3]);
+        pb[pr].z = E::pack(s1[0], s1[1]);
+        pb[pr].w = E::pack(s1[2], s1[3]);
+        pl[pr].x = E::pack(s0[0] - E::lo_of(pb[pr].x), s0[1] - E::hi_of(pb[pr].x));
+        pl[pr].y = E::pack(s0[2] - E::lo_of(pb[pr].y), s0[3] - E::hi_of(pb[pr].y));
+        pl[pr].z = E::pack(s1[0] - E::lo_of(pb[pr].z), s1[1] - E::hi_of(pb[pr].z));
+        pl[pr].w = E::pack(s1[2] - E::lo_of(pb[pr].w), s1[3] - E::hi_of(pb[pr].w));
+    }
     // in-register 8x8 transpose of V, one head_dim column (j) at a time, feeding the A operand
 #pragma unroll
     for (int c = 0; c < GE::kPasses; ++c)
@@ -279,15 +299,26 @@ __device__ __forceinline__ void compute_tile(State<GE>& st, const Tile<GE>& t, c
             uint4 a;   // columns j of rows (0,1), (2,3), (4,5), (6,7): word j/2 of each row, low or high half
             a.x = __builtin_amdgcn_perm(word(t.v[c][1], j / 2), word(t.v[c][0], j / 2), sel);
             a.y = __builtin_amdgcn_perm(word(t.v[c][3], j / 2), word(t.v[c][2], j / 2), sel);
-            if constexpr (kBlocks == 2) {
+            if constexpr (GE::kVBlocks == 2) {
                 a.z = __builtin_amdgcn_perm(word(t.v[c][5], j / 2), word(t.v[c][4], j / 2), sel);
                 a.w = __builtin_amdgcn_perm(word(t.v[c][7], j / 2), word(t.v[c][6], j / 2), sel);
             } else {
                 a.z = 0u;   // the absent block: zero values under zero weights
                 a.w = 0u;
             }
-            st.o[c][j] = E::mfma16(a, pb, st.o[c][j]);
-            st.o[c][j] = E::mfma16(a, pl, st.o[c][j]);
+            st.o[c][j] = E::mfma16(a, pb[0], st.o[c][j]);
+            st.o[c][j] = E::mfma16(a, pl[0], st.o[c][j]);
+            if constexpr (kPairs == 2) {
+                // head_dim 64: lanes 8-15 of every 16 hold the V rows of blocks 2, 3; rotate the halves (DPP
+                // row_ror:8) so that rows 0-7 of the operand carry them, and multiply by those blocks' weights
+                uint4 b;
+                b.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.x, 0x128, 0xF, 0xF, false);
+                b.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.y, 0x128, 0xF, 0xF, false);
+                b.z = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.z, 0x128, 0xF, 0xF, false);
+                b.w = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.w, 0x128, 0xF, 0xF, false);
+                st.o[c][j] = E::mfma16(b, pb[1], st.o[c][j]);
+                st.o[c][j] = E::mfma16(b, pl[1], st.o[c][j]);
+            }
         }
 }
 
