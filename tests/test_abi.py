@@ -134,6 +134,33 @@ def test_host_validation_rejects_before_launch(lib):
     assert lib.pa_set_option(b"decode_chunk_tokens", ctypes.c_int64(0)) == 0
 
 
+def test_options_are_kept_per_host_thread(lib):
+    """A knob set on one thread shapes that thread's calls only: the workspace bound of another thread (and of the
+    main thread) does not move when a worker forces a context split."""
+    import threading
+    args = (4, 32, 128, 8192, 2048)
+    before = binding.paged_attention_workspace_bytes(*args)
+    seen = {}
+
+    def worker():
+        assert lib.pa_set_option(b"prefill_chunk_tokens", ctypes.c_int64(256)) == 0
+        seen["forced"] = binding.paged_attention_workspace_bytes(*args)
+
+    t = threading.Thread(target=worker)
+    t.start()
+    t.join()
+    assert seen["forced"] > before                       # the worker's bound grew with its forced split
+    assert binding.paged_attention_workspace_bytes(*args) == before
+
+
+def test_decode_workspace_bound_is_what_the_planner_can_use(lib):
+    """The decode bound follows what the planners may choose -- the tile stream's largest grid (one workgroup per
+    compute unit, 256 without a device: 9 MB of partials at 16 x 131072 with 64 heads) and the portable kernel's 64
+    chunks per sequence (34 MB) -- not a fixed maximum of workgroups (it was 143 MB)."""
+    n = binding.paged_attention_workspace_bytes(16, 64, 128, 16, 131072)
+    assert 30_000_000 < n < 40_000_000
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
