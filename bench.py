@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # (FETCH_SIZE, WRITE_SIZE) and scaled by what the same counters read for the plain gather copy of known size
 # (FETCH_SIZE x1.998, WRITE_SIZE x1.000); the summaries are under profiles/.
 MEASURED_TRAFFIC = {
-    "decode_b16_ctx131072_p16": {"read_bytes": 8588449000, "write_bytes": 8454300,
+    "decode_b16_ctx131072_p16": {"read_bytes": 8588269000, "write_bytes": 9568500,
                                  "source": "profiles/decode_b16_ctx131072_p16.md"},
-    "prefill_b4_s2048_causal": {"read_bytes": 150699000, "write_bytes": 67128000,
+    "prefill_b4_s2048_causal": {"read_bytes": 154348000, "write_bytes": 67200000,
                                 "source": "profiles/prefill_b4_s2048_causal.md"},
 }
 
