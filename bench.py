@@ -73,7 +73,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="decode_b16_ctx131072_p16", choices=sorted(WORKLOADS))
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU-oracle baseline / parity leg")
-    ap.add_argument("--no-prefill", action="store_true", help="skip the extra prefill measurement")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the extra measurements of the default run (prefill workload, other configurations)")
     ap.add_argument("--oracle-seqs", type=int, default=12, help="sequences of the workload the oracle is timed on")
     ap.add_argument("--dtype", choices=["default", "bf16", "fp16"], default="default",
                     help="16-bit element type of the pools (fp16 is the paper's own precision)")
@@ -195,6 +195,64 @@ def run_read_calibration(torch, binding, w, args):
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "pa_stream_read_kernel",
                      "algorithmic_bytes": 2 * each}}))
+
+
+def run_other_configs(torch, pa, binding, W, dev):
+    """The other decode configurations and the plain-read yardstick, briefly, for the default run's line: step time
+    (30 steps without events), the dominant kernel's time (30 steps with the library's events) and its fraction of
+    the HBM peak.  No oracle leg here: `bench_all.py` has every configuration with oracle time and parity."""
+    res = {}
+    names = ["decode_fp32_single", "decode_b8_ctx128", "decode_b8_ctx256", "decode_b8_ctx512", "decode_b8_ctx1024",
+             "decode_b8_ctx2048", "decode_mixed64_shared_prefix"]
+    for wl in names:
+        cfg, P, ctx = WORKLOADS[wl]
+        w = W.config(cfg, device=dev, page_size=P, context=ctx, poison=False)
+        ws = torch.empty(pa.paged_attention_workspace_bytes(w.batch, w.num_q_heads, w.head_dim, w.total_q,
+                                                            w.max_seq_len), dtype=torch.uint8, device=dev)
+        out = torch.empty_like(w.q)
+        step = pa.prepare_decode_step(w.k_cache, w.v_cache, w.k_new, w.v_new, w.q, w.block_table, w.seq_lens,
+                                      w.max_seq_len, w.scale, out=out, workspace=ws)
+        binding.pa_profile_enable(True)
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        binding.pa_profile_reset()
+        time_steps(torch, step, 30, 0)
+        binding.pa_profile_enable(False)
+        sec = time_steps(torch, step, 30, 0)
+        dom = None
+        for name in ("paged_decode_mfma_kernel", "paged_decode_short_kernel", "paged_attention_generic_kernel"):
+            n, ms = binding.pa_profile_read(name)
+            if n:
+                dom = (name, ms * 1e3 / n)
+                break
+        binding.pa_profile_reset()
+        nbytes = w.logical_kv_bytes()
+        res[wl] = {"us_per_step": round(sec * 1e6, 2), "tokens_per_s": round(w.total_q / sec, 1), "kernel": dom[0],
+                   "kernel_avg_us": round(dom[1], 2), "kv_bytes_per_step": nbytes,
+                   "cache": "warm (fits the 256 MB last-level cache)" if nbytes < (200 << 20) else "HBM-resident",
+                   "hbm_frac_kernel": round(nbytes / (dom[1] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del w, ws, out, step
+        torch.cuda.empty_cache()
+    each = 4 << 30
+    a, b = (torch.empty(each, dtype=torch.uint8, device=dev) for _ in range(2))
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+
+    def read():
+        binding.pa_stream_read(a, b, each, sink)
+    for _ in range(3):
+        read()
+    torch.cuda.synchronize()
+    binding.pa_profile_reset()
+    binding.pa_profile_enable(True)
+    time_steps(torch, read, 10, 0)
+    binding.pa_profile_enable(False)
+    n, ms = binding.pa_profile_read("pa_stream_read_kernel")
+    binding.pa_profile_reset()
+    res["contiguous_read_calibration"] = {"kernel": "pa_stream_read_kernel", "kernel_avg_us": round(ms * 1e3 / n, 1),
+                                          "bytes": 2 * each,
+                                          "hbm_frac_kernel": round(2 * each / (ms / n * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    return res
 
 
 def run_page_manager(torch, binding, args, P):
@@ -513,6 +571,10 @@ def main():
                              "kernel_avg_us": round(pk[1], 1), "useful_flops": flops,
                              "mfma_tflops": round(flops / (pk[1] * 1e-6) / 1e12, 1),
                              "mfma_frac": round(flops / (pk[1] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        if args.workload == "decode_b16_ctx131072_p16" and not args.option and not args.cold:
+            del wp, wsp, outp
+            torch.cuda.empty_cache()
+            result["other_configs"] = run_other_configs(torch, pa, binding, W, dev)
     print(json.dumps(result))
 
 
