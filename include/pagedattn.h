@@ -121,6 +121,12 @@ size_t paged_attention_workspace_bytes(int32_t batch, int32_t num_q_heads, int32
  * seq_lens, used to size the grid.  workspace : at least
  * paged_attention_workspace_bytes(batch, Hq, d, batch, max_seq_len) bytes,
  * 256-byte aligned; its contents need not be initialised.
+ * Concurrency: calls on different streams may overlap when each has a workspace
+ * of its own.  Calls whose plan splits a (sequence, KV head) over several
+ * workgroups of one launch (few sequences, contexts of about 1 k - 8 k tokens)
+ * also count arrivals in a ring of 16 counter windows inside the library, one
+ * window per call in issue order: at most 16 such calls may be in flight on one
+ * GPU at a time (a captured HIP graph keeps the window of the call it captured).
  */
 pa_status paged_attention_decode(const pa_kv_cache_desc* cache, const void* q, void* out, float* lse,
                                  const int32_t* block_table, const int32_t* seq_lens, int32_t batch,
