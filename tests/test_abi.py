@@ -166,3 +166,31 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(binding.PagedAttnError):
         binding.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box of this build has one GPU: bench.py says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_product_sources_never_reach_for_the_oracle():
+    """The oracle is test infrastructure: nothing under the package (binding, build, kernels) or include/ names it."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hits = []
+    for top in ("paper_2506_07311_amd", "include"):
+        for dirpath, _, files in os.walk(os.path.join(root, top)):
+            if "_build" in dirpath or "__pycache__" in dirpath:
+                continue
+            for name in files:
+                if not name.endswith((".py", ".h", ".hip", ".c", ".cpp")):
+                    continue
+                text = open(os.path.join(dirpath, name), errors="replace").read()
+                if re.search(r"^\s*(import|from)\s+oracle\b|paged_oracle|libpaged_oracle", text, re.M):
+                    hits.append(os.path.join(dirpath, name))
+    assert not hits, hits
