@@ -33,6 +33,11 @@ RUNS = [
     ("decode_mixed64_shared_prefix", ["--oracle-seqs", "64"], False, "4 bf16 decode, 64 seqs 64..32768, shared prefixes"),
     ("decode_b16_ctx131072_p16", ["--oracle-seqs", "16"], False, "5 bf16 decode 16 x 131072, 64/8 heads, P 16"),
     ("decode_b16_ctx131072_p64", ["--oracle-seqs", "16"], False, "5 same, P 64"),
+    ("decode_b16_ctx131072_p16", ["--dtype", "fp16", "--oracle-seqs", "4"], False, "5 with fp16 pools"),
+    ("decode_b16_ctx131072_p16", ["--head-dim", "64", "--oracle-seqs", "4"], False, "5 with head_dim 64"),
+    ("decode_b16_ctx131072_p16", ["--head-dim", "256", "--oracle-seqs", "2"], False, "5 with head_dim 256"),
+    ("prefill_b4_s2048_causal", ["--head-dim", "64"], False, "3 with head_dim 64"),
+    ("prefill_b4_s2048_causal", ["--head-dim", "256"], False, "3 with head_dim 256"),
     ("contiguous_read_calibration", [], False, "yardstick: plain contiguous read of 8.59 GB"),
 ]
 
@@ -79,7 +84,8 @@ def main():
         steps = min(args.steps, 20) if big else args.steps
         j = run_one(workload, extra, False, steps, args.warmup)
         lines.append(j)
-        rows.append(fmt_row(label, "cold (HBM-resident)" if not both else "warm", j))
+        rows.append(fmt_row(label, "cold (HBM-resident)" if big or not workload.startswith("prefill") else "warm", j)
+                    if not both else fmt_row(label, "warm", j))
         if both:
             j = run_one(workload, extra, True, steps, args.warmup)
             lines.append(j)
