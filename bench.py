@@ -538,46 +538,49 @@ def main():
                                    "within_1e-2_plus_2e-2_of_ref_elementwise": unfloored, "sequences": seqs}
 
     if not is_prefill and not args.no_prefill:
-        del w, ws, out
-        torch.cuda.empty_cache()
-        wp = W.config(3, device=dev, poison=False)
-        wsp = torch.empty(pa.paged_attention_workspace_bytes(wp.batch, wp.num_q_heads, wp.head_dim, wp.total_q,
-                                                             wp.max_seq_len), dtype=torch.uint8, device=dev)
-        outp = torch.empty_like(wp.q)
-
-        def pstep():
-            pa.paged_kv_append(wp.k_cache, wp.v_cache, wp.k_new, wp.v_new, wp.seq_ids, wp.positions, wp.block_table)
-            pa.paged_attention_prefill(wp.k_cache, wp.v_cache, wp.q, wp.cu_q_lens, wp.max_q_len, wp.block_table,
-                                       wp.seq_lens, wp.max_seq_len, wp.scale, wp.causal, out=outp, workspace=wsp)
-        for _ in range(2):
-            pstep()
-        torch.cuda.synchronize()
-        binding.pa_profile_reset()
-        binding.pa_profile_enable(True)             # kernel durations: a pass with the per-kernel events ...
-        time_steps(torch, pstep, max(3, args.steps // 2), 0)
-        binding.pa_profile_enable(False)
-        psec = time_steps(torch, pstep, max(3, args.steps // 2), 0)   # ... step time: the same steps without them
-        S = wp.max_seq_len
-        flops = 4 * wp.batch * wp.num_q_heads * wp.head_dim * S * (S + 1) // 2
-        pk = None
-        for name in ("paged_prefill_mfma_kernel", "paged_attention_generic_kernel"):
-            n, ms = binding.pa_profile_read(name)
-            if n:
-                pk = (name, ms * 1e3 / n)
-                break
-        binding.pa_profile_reset()
-        result["prefill"] = {"workload": "prefill_b4_s2048_causal", "us_per_step": round(psec * 1e6, 1),
-                             "tokens_per_s": round(wp.total_q / psec, 1), "kernel": pk[0],
-                             "kernel_avg_us": round(pk[1], 1), "useful_flops": flops,
-                             "mfma_tflops": round(flops / (pk[1] * 1e-6) / 1e12, 1),
-                             "mfma_frac": round(flops / (pk[1] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
-        if args.workload == "decode_b16_ctx131072_p16" and not args.option and not args.cold:
-            del wp, wsp, outp
+        try:     # extras: a failure here must not cost the line of the workload that was asked for
+            del w, ws, out
             torch.cuda.empty_cache()
-            try:     # extras: a failure here must not cost the line of the workload that was asked for
-                result["other_configs"] = run_other_configs(torch, pa, binding, W, dev)
-            except Exception as e:   # noqa: BLE001
-                result["other_configs"] = {"error": repr(e)[:300]}
+            wp = W.config(3, device=dev, poison=False)
+            wsp = torch.empty(pa.paged_attention_workspace_bytes(wp.batch, wp.num_q_heads, wp.head_dim, wp.total_q,
+                                                                 wp.max_seq_len), dtype=torch.uint8, device=dev)
+            outp = torch.empty_like(wp.q)
+
+            def pstep():
+                pa.paged_kv_append(wp.k_cache, wp.v_cache, wp.k_new, wp.v_new, wp.seq_ids, wp.positions, wp.block_table)
+                pa.paged_attention_prefill(wp.k_cache, wp.v_cache, wp.q, wp.cu_q_lens, wp.max_q_len, wp.block_table,
+                                           wp.seq_lens, wp.max_seq_len, wp.scale, wp.causal, out=outp, workspace=wsp)
+            for _ in range(2):
+                pstep()
+            torch.cuda.synchronize()
+            binding.pa_profile_reset()
+            binding.pa_profile_enable(True)             # kernel durations: a pass with the per-kernel events ...
+            time_steps(torch, pstep, max(3, args.steps // 2), 0)
+            binding.pa_profile_enable(False)
+            psec = time_steps(torch, pstep, max(3, args.steps // 2), 0)   # ... step time: the same steps without them
+            S = wp.max_seq_len
+            flops = 4 * wp.batch * wp.num_q_heads * wp.head_dim * S * (S + 1) // 2
+            pk = None
+            for name in ("paged_prefill_mfma_kernel", "paged_attention_generic_kernel"):
+                n, ms = binding.pa_profile_read(name)
+                if n:
+                    pk = (name, ms * 1e3 / n)
+                    break
+            binding.pa_profile_reset()
+            result["prefill"] = {"workload": "prefill_b4_s2048_causal", "us_per_step": round(psec * 1e6, 1),
+                                 "tokens_per_s": round(wp.total_q / psec, 1), "kernel": pk[0],
+                                 "kernel_avg_us": round(pk[1], 1), "useful_flops": flops,
+                                 "mfma_tflops": round(flops / (pk[1] * 1e-6) / 1e12, 1),
+                                 "mfma_frac": round(flops / (pk[1] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            if args.workload == "decode_b16_ctx131072_p16" and not args.option and not args.cold:
+                del wp, wsp, outp
+                torch.cuda.empty_cache()
+                try:     # extras: a failure here must not cost the line of the workload that was asked for
+                    result["other_configs"] = run_other_configs(torch, pa, binding, W, dev)
+                except Exception as e:   # noqa: BLE001
+                    result["other_configs"] = {"error": repr(e)[:300]}
+        except Exception as e:   # noqa: BLE001
+            result.setdefault("prefill", {"error": repr(e)[:300]})
     print(json.dumps(result))
 
 
