@@ -63,7 +63,7 @@ __device__ __forceinline__ int piece_pos(int L, int r) { return 16 * ((L & 16) |
 // 2*w*512; row = 2*w + lane/32; lane_off[i & 1] = kv-head offset + this lane's logical piece, which depends on the
 // parity of i through the swizzle of row 8*i + row.
 template <bool UNIFORM>
-__device__ __forceinline__ void fetch_tile512(char* dst, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
+__device__ __forceinline__ void fetch_tile512(uint32_t lds, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
                                               int32_t last_key, const uint32_t (&lane_off)[2])
 {
     constexpr int TB = RowGeo<256>::kTileB;
@@ -78,10 +78,8 @@ __device__ __forceinline__ void fetch_tile512(char* dst, const PageIds& p, const
                   ((uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off[i & 1]);
         else
             off = ((int64_t)pg[i >> 1] * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off[i & 1];
-        char* d = dst + i * (8 * 512);
-        __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.k) + off), (lds_void*)d, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.v) + off), (lds_void*)(d + TB),
-                                         16, 0, 0);
+        load_to_lds16(lds, i * (8 * 512), reinterpret_cast<const char*>(cache.k) + off);
+        load_to_lds16(lds, i * (8 * 512) + TB, reinterpret_cast<const char*>(cache.v) + off);
     }
 }
 
@@ -558,9 +556,10 @@ __device__ __forceinline__ void prefill_body(
         lane_off2[par] = head_off + 16 * ((lane & 16) | ((lane & 15) ^ swz(8 * par + frow)));
     const int32_t wrow = __builtin_amdgcn_readfirstlane(D > 128 ? 2 * wave * 512 : 4 * wave * 256);
     const int32_t last_key = len - 1;
-    auto fetch = [&](char* buf, const PageIds& pg, int32_t t0) {
-        if constexpr (D > 128) fetch_tile512<UNIFORM>(buf + wrow, pg, cache, t0, frow, last_key, lane_off2);
-        else fetch_tile<UNIFORM>(buf + wrow, pg, cache, t0, frow, last_key, lane_off);
+    const uint32_t lds0 = lds_address(buf0 + wrow), lds1 = lds_address(buf1 + wrow);
+    auto fetch = [&](uint32_t lds, const PageIds& pg, int32_t t0) {
+        if constexpr (D > 128) fetch_tile512<UNIFORM>(lds, pg, cache, t0, frow, last_key, lane_off2);
+        else fetch_tile<UNIFORM>(lds, pg, cache, t0, frow, last_key, lane_off);
     };
 
     // Document masks: wave 0 brings the 64 ids of the next tile (one per lane) and stores them next to the tile
@@ -603,18 +602,19 @@ __device__ __forceinline__ void prefill_body(
     const int32_t n_tiles = (max(k_end - k_begin, 0) + kBN - 1) / kBN;
     if (n_tiles > 0) {
         load_ids<UNIFORM>(ids, cache, table, k_begin, frow, last_key);
-        fetch(buf0, ids, k_begin);
+        fetch(lds0, ids, k_begin);
         if (doc_lane) put_docs(docs0, tile_ids(k_begin));
         if (n_tiles > 1) load_ids<UNIFORM>(ids, cache, table, k_begin + kBN, frow, last_key);
-        __syncthreads();                                     // own loads landed (vmcnt) + everyone's (barrier)
     }
+    wait_tile_loads();                                       // (outside the test: the loop below must start from a
+    __syncthreads();                                         //  state without pending loads on every path)
     // Two tiles per trip so that each buffer is a distinct LDS object for the compiler: while the matrix cores
     // read one, the load unit fills the other with the next tile; the page ids of the tile after that are requested
     // at the same time.  The barrier at the end of a tile waits for this wave's loads first.
     for (int32_t t = 0; t < n_tiles; t += 2) {
         const int32_t t0 = k_begin + t * kBN;
         if (t + 1 < n_tiles) {
-            fetch(buf1, ids, t0 + kBN);
+            fetch(lds1, ids, t0 + kBN);
             if (doc_lane) doc_next = tile_ids(t0 + kBN);
             if (t + 2 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t0 + 2 * kBN, frow, last_key);
         }
@@ -625,11 +625,12 @@ __device__ __forceinline__ void prefill_body(
                 attend_tile<PRECISE, false, E, M, T>(buf0, kx, vx, qf, o, m, l, sc, t0 + 4 * hh, nk, rm, docs0 + 4 * hh);
         }
         if (doc_lane && t + 1 < n_tiles) put_docs(docs1, doc_next);
+        wait_tile_loads();
         __syncthreads();
         if (t + 1 >= n_tiles) break;
         const int32_t t1 = t0 + kBN;
         if (t + 2 < n_tiles) {
-            fetch(buf0, ids, t1 + kBN);
+            fetch(lds0, ids, t1 + kBN);
             if (doc_lane) doc_next = tile_ids(t1 + kBN);
             if (t + 3 < n_tiles) load_ids<UNIFORM>(ids, cache, table, t1 + 2 * kBN, frow, last_key);
         }
@@ -640,6 +641,7 @@ __device__ __forceinline__ void prefill_body(
                 attend_tile<PRECISE, false, E, M, T>(buf1, kx, vx, qf, o, m, l, sc, t1 + 4 * hh, nk, rm, docs1 + 4 * hh);
         }
         if (doc_lane && t + 2 < n_tiles) put_docs(docs0, doc_next);
+        wait_tile_loads();
         __syncthreads();
     }
 

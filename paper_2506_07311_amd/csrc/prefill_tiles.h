@@ -32,6 +32,45 @@ constexpr float kLn2 = 0.6931471805599453f;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
+// 16 bytes per lane from global memory straight into LDS (lane i lands at lds_addr + 16 i; lds_addr wave-uniform),
+// written as ONE OPAQUE STATEMENT.  Issued through the compiler's builtin, a load that writes LDS is booked as an
+// access that may complete out of order with LDS reads, and while one is in flight -- here: for the whole tile --
+// every wait for an LDS read becomes a wait for ALL of them, which drains the operand pipeline of the matrix
+// instructions (reads kept four ahead) at every step.  The compiler does not look inside this statement, so its
+// LDS waits count exactly; the loads are waited for by hand (wait_tile_loads) in front of the barrier that
+// publishes a tile.  Two forms: scalar 64-bit base + 32-bit lane offset, and a 64-bit lane address.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is written on purpose: it carries the LDS address of the load
+// lds = wave-uniform LDS byte address, lds_imm = compile-time constant added to it
+__device__ __forceinline__ void load_to_lds16(uint32_t lds, int lds_imm, const char* base, uint32_t off)
+{
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds), "v"(off), "s"(base), "n"(lds_imm)
+                 : "memory", "m0", "scc");
+}
+__device__ __forceinline__ void load_to_lds16(uint32_t lds, int lds_imm, const char* addr)
+{
+    asm volatile("s_add_u32 m0, %0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds), "v"(addr), "n"(lds_imm)
+                 : "memory", "m0", "scc");
+}
+#pragma clang diagnostic pop
+// LDS byte address of a (wave-uniform) pointer into a __shared__ array, as a scalar
+__device__ __forceinline__ uint32_t lds_address(const char* p)
+{
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p);
+}
+// This wave's loads to LDS have landed (to be followed by the workgroup barrier).  The wait is the compiler's own
+// instruction, not text: it also tells the compiler's bookkeeping that none of ITS loads is pending any more
+// (otherwise the query fragments loaded in front of the tile loop would be waited for again inside the loop, with
+// counts that the tile loads in flight turn into waits for the next tile).
+__device__ __forceinline__ void wait_tile_loads()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), the other counters left alone
+}
+
 // How the launch cuts the work: head packing and the context split.
 struct PrefillPlan {
     int32_t log2_pack;    // query heads of one KV head packed into a row tile (1 << log2_pack divides the group size)
@@ -64,9 +103,9 @@ __device__ __forceinline__ void load_ids(PageIds& p, const CacheView& cache, con
     }
 }
 
-// K row and V row of `key` (clamped to a live slot) in page `page` -> LDS rows at `dst` (K) and dst + kTileBytes (V).
-template <bool UNIFORM>
-__device__ __forceinline__ void fetch_rows(char* dst, const CacheView& cache, int32_t page, int32_t key,
+// K row and V row of `key` (clamped to a live slot) in page `page` -> LDS rows at lds + IMM (K) and kTileBytes further (V).
+template <bool UNIFORM, int IMM>
+__device__ __forceinline__ void fetch_rows(uint32_t lds, const CacheView& cache, int32_t page, int32_t key,
                                            int32_t last_key, uint32_t lane_off)
 {
     const int32_t slot = min(key, last_key) & (cache.page_size - 1);
@@ -78,25 +117,25 @@ __device__ __forceinline__ void fetch_rows(char* dst, const CacheView& cache, in
         const uint32_t off32 = (uint32_t)slot * (uint32_t)(cache.token_stride * 2) + lane_off;
         const char* kp = reinterpret_cast<const char*>(cache.k) + page_off;
         const char* vp = reinterpret_cast<const char*>(cache.v) + page_off;
-        __builtin_amdgcn_global_load_lds((glb_void*)(kp + off32), (lds_void*)dst, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)(vp + off32), (lds_void*)(dst + kTileBytes), 16, 0, 0);
+        load_to_lds16(lds, IMM, kp, off32);
+        load_to_lds16(lds, IMM + kTileBytes, vp, off32);
         return;
     }
     const int64_t off = ((int64_t)page * cache.page_stride + (int64_t)slot * cache.token_stride) * 2 + lane_off;
-    __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.k) + off), (lds_void*)dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_void*)(reinterpret_cast<const char*>(cache.v) + off),
-                                     (lds_void*)(dst + kTileBytes), 16, 0, 0);
+    load_to_lds16(lds, IMM, reinterpret_cast<const char*>(cache.k) + off);
+    load_to_lds16(lds, IMM + kTileBytes, reinterpret_cast<const char*>(cache.v) + off);
 }
 
-// dst = buffer + 4*w*kRow (this wave's first row); row = 4*w + lane/16 (this lane's row within a 16-row group).
+// lds = LDS address of buffer + 4*w*kRow (this wave's first row); row = 4*w + lane/16 (this lane's row within a
+// 16-row group).
 template <bool UNIFORM>
-__device__ __forceinline__ void fetch_tile(char* dst, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
+__device__ __forceinline__ void fetch_tile(uint32_t lds, const PageIds& p, const CacheView& cache, int32_t t0, int32_t row,
                                            int32_t last_key, uint32_t lane_off)
 {
-    fetch_rows<UNIFORM>(dst, cache, p.p0, t0 + row, last_key, lane_off);
-    fetch_rows<UNIFORM>(dst + 16 * kRow, cache, p.p1, t0 + row + 16, last_key, lane_off);
-    fetch_rows<UNIFORM>(dst + 32 * kRow, cache, p.p2, t0 + row + 32, last_key, lane_off);
-    fetch_rows<UNIFORM>(dst + 48 * kRow, cache, p.p3, t0 + row + 48, last_key, lane_off);
+    fetch_rows<UNIFORM, 0>(lds, cache, p.p0, t0 + row, last_key, lane_off);
+    fetch_rows<UNIFORM, 16 * kRow>(lds, cache, p.p1, t0 + row + 16, last_key, lane_off);
+    fetch_rows<UNIFORM, 32 * kRow>(lds, cache, p.p2, t0 + row + 32, last_key, lane_off);
+    fetch_rows<UNIFORM, 48 * kRow>(lds, cache, p.p3, t0 + row + 48, last_key, lane_off);
 }
 
 
