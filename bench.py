@@ -48,6 +48,11 @@ WORKLOADS = {
     "prefill_chunk1024_on_ctx31744": (6, 16, None),
     "mixed_60_decode_4_prefill512": (7, 16, None),
     "speculative_4_tokens_b64_mixed": (8, 16, None),
+    # the paper's own setting (Sec. IV): one LLaMA-7B layer (32 heads, no grouping, head_dim 128, fp16), 64-token pages,
+    # one sequence; a decode step at the two ends of its 128 ... 2048-token range and the longest prompt's prefill
+    "paper_llama7b_decode_ctx128": (9, 64, 128),
+    "paper_llama7b_decode_ctx2048": (9, 64, 2048),
+    "paper_llama7b_prefill_s2048": (10, 64, 2048),
     # plain paged copy of known size (Algorithm 1 Gather over 16 x 65536 tokens): calibrates HBM byte counters
     "gather_copy_calibration": (5, 16, 65536),
     # plain contiguous read of as many bytes as the 16 x 131072 decode step streams (2 x 4 GiB): the rate the memory
@@ -349,7 +354,7 @@ def main():
         mods["alibi_slopes"] = torch.tensor([2.0 ** (-8.0 * (h + 1) / w.num_q_heads) for h in range(w.num_q_heads)],
                                             dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
-    is_prefill = cfg in (3, 6, 7, 8)
+    is_prefill = cfg in (3, 6, 7, 8, 10)
     if args.workload == "gather_copy_calibration":
         return run_gather_calibration(torch, pa, binding, w, args)
     if args.workload == "contiguous_read_calibration":

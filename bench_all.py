@@ -38,6 +38,9 @@ RUNS = [
     ("decode_b16_ctx131072_p16", ["--head-dim", "256", "--oracle-seqs", "2"], False, "5 with head_dim 256"),
     ("prefill_b4_s2048_causal", ["--head-dim", "64"], False, "3 with head_dim 64"),
     ("prefill_b4_s2048_causal", ["--head-dim", "256"], False, "3 with head_dim 256"),
+    ("paper_llama7b_decode_ctx128", [], True, "paper's setting: LLaMA-7B layer (32/32 heads, fp16, P 64), decode 1 x 128"),
+    ("paper_llama7b_decode_ctx2048", [], True, "same, decode 1 x 2048"),
+    ("paper_llama7b_prefill_s2048", [], True, "same, causal prefill of a 2048-token prompt"),
     ("contiguous_read_calibration", [], False, "yardstick: plain contiguous read of 8.59 GB"),
 ]
 

@@ -244,7 +244,7 @@ def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> List[int]:
 def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_size: Optional[int] = None,
            shrink: int = 1, poison: bool = True, head_dim: Optional[int] = None,
            heads: Optional[tuple] = None) -> PagedWorkload:
-    """The five benchmark workloads (1-based), then three jagged-batch workloads (6-8).  ``shrink`` divides context lengths
+    """The five benchmark workloads (1-based), three jagged-batch workloads (6-8) and the paper's own model shape (9-10).  ``shrink`` divides context lengths
     (and config 4's length range) for cases the CPU oracle must finish in seconds; ``head_dim`` overrides the 128 of
     the 16-bit workloads (2-8); ``heads`` = (query heads, KV heads) overrides workload 5's 64 / 8 (the per-GPU shape
     of a tensor-parallel shard has few KV heads)."""
@@ -292,4 +292,12 @@ def config(n: int, *, device: str = "cpu", context: Optional[int] = None, page_s
         return make_workload(f"cfg{n}_bf16_jagged_max{hi}", seq_lens=lens, q_lens=q_lens, num_q_heads=32,
                              num_kv_heads=8, head_dim=hd, page_size=page_size or 16, causal=True, seed=n,
                              device=device, poison=poison)
+    # The model the paper measures on (Sec. IV-A): one LLaMA-7B layer -- 32 heads without grouping, head_dim 128, fp16 --
+    # with the page size the paper settles on (64 tokens, Sec. III-B) and one sequence, prompts of 128 to 2048 tokens
+    # (Sec. IV-B).  9: one decode step at context L; 10: the prompt's causal prefill.
+    if n in (9, 10):
+        L = context or max(16, 2048 // shrink)
+        return make_workload(f"cfg{n}_fp16_llama7b_layer_L{L}", seq_lens=[L], q_lens=[L] if n == 10 else None,
+                             num_q_heads=32, num_kv_heads=32, head_dim=hd, page_size=page_size or 64,
+                             dtype=torch.float16, causal=(n == 10), seed=n, device=device, poison=poison)
     raise ValueError(f"no config {n}")

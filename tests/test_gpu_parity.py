@@ -708,6 +708,16 @@ def test_config5_full_size_every_sequence(pa, oracle, P):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("L", [128, 333, 2048])
+@pytest.mark.parametrize("n", [9, 10], ids=["decode", "prefill"])
+def test_paper_model_shape_full_size(pa, oracle, n, L):
+    """The paper's own setting (Sec. IV): one LLaMA-7B layer -- 32 heads without grouping, head_dim 128, fp16 pools --
+    with 64-token pages and a single sequence, at the ends of its 128 ... 2048-token prompt range (and one ragged
+    length): a decode step at that context, and the prompt's causal prefill; every row against the oracle."""
+    parity.check_step(pa, oracle, W.config(n, device=DEV, context=L), f"paper shape config {n} L={L}",
+                      step_call=(n == 9))
+
+
 # ----------------------------------------------------------------------------- HIP graph replay
 @pytest.mark.parametrize("how", ["pair_of_calls", "step_call_one_launch", "step_call_tile_stream"])
 def test_decode_step_replays_in_a_hip_graph(pa, oracle, how):
