@@ -20,32 +20,66 @@ __device__ __forceinline__ void store_out(void* out, int64_t i, float r)
         reinterpret_cast<float*>(out)[i] = r;
 }
 
+// Four consecutive output elements of one row.
+template <int OUT>
+__device__ __forceinline__ void store_out4(void* out, int64_t i, float4 r)
+{
+    if (OUT == PA_DTYPE_F32) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + i) = r;
+    } else {
+        uint2 w;
+        if (OUT == PA_DTYPE_BF16) {
+            w.x = float_to_bf16_bits(r.x) | (float_to_bf16_bits(r.y) << 16);
+            w.y = float_to_bf16_bits(r.z) | (float_to_bf16_bits(r.w) << 16);
+        } else {
+            w.x = float_to_f16_bits(r.x) | (float_to_f16_bits(r.y) << 16);
+            w.y = float_to_f16_bits(r.z) | (float_to_f16_bits(r.w) << 16);
+        }
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + i) = w;
+    }
+}
+
+// A workgroup of 256 threads merges kMergePairs (query row, head) pairs: 32 lanes per pair, four consecutive output
+// columns per lane and pass (head_dim is a multiple of 4 for every supported element type), 16-byte loads of the
+// partial rows.  (One small workgroup per pair, as this kernel once was, is bound by the rate at which workgroups are
+// dispatched: 65536 of them for a 2048-token prompt with 32 heads.)
+constexpr int kMergePairs = 8;
+
 template <int OUT>
 __global__ __launch_bounds__(256) void paged_attention_merge_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_lse, void* __restrict__ out,
     float* __restrict__ lse, const int32_t* __restrict__ cu_q_lens, const int32_t* __restrict__ seq_lens,
-    int32_t batch, int32_t num_q_heads, int32_t d, int32_t causal, int32_t chunk, int32_t nsplit)
+    int32_t batch, int32_t num_q_heads, int32_t d, int32_t causal, int32_t chunk, int32_t nsplit, int64_t pairs)
 {
-    const int32_t row = blockIdx.x / num_q_heads;
-    const int64_t o_idx = blockIdx.x;
+    const int64_t o_idx = (int64_t)blockIdx.x * kMergePairs + (threadIdx.x >> 5);
+    if (o_idx >= pairs) return;
+    const int lane = threadIdx.x & 31;
+    const int32_t row = (int32_t)(o_idx / num_q_heads);
     const RowInfo ri = locate_row(cu_q_lens, seq_lens, batch, row, causal);
     const int32_t n = (ri.n_keys + chunk - 1) / chunk;   // chunks that hold keys
     const float* pl = part_lse + o_idx * nsplit;
     const float* po = part_o + o_idx * nsplit * d;
-    const int e = threadIdx.x;
 
     float M = -INFINITY;
     for (int32_t c = 0; c < n; ++c) M = fmaxf(M, pl[c]);
     const bool none = M == -INFINITY;            // no chunk holds a visible key (masks can empty every chunk)
-    float wsum = 0.f, acc = 0.f;
-    for (int32_t c = 0; c < n && !none; ++c) {
-        const float w = expf(pl[c] - M);
-        wsum += w;
-        if (e < d) acc = fmaf(w, po[(int64_t)c * d + e], acc);
+    float wsum = 0.f;
+    for (int32_t c = 0; c < n && !none; ++c) wsum += expf(pl[c] - M);
+    for (int e = 4 * lane; e < d; e += 128) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t c = 0; c < n && !none; ++c) {
+            const float w = expf(pl[c] - M);
+            const float4 v = *reinterpret_cast<const float4*>(po + (int64_t)c * d + e);
+            acc.x = fmaf(w, v.x, acc.x);
+            acc.y = fmaf(w, v.y, acc.y);
+            acc.z = fmaf(w, v.z, acc.z);
+            acc.w = fmaf(w, v.w, acc.w);
+        }
+        const float4 r = none ? make_float4(0.f, 0.f, 0.f, 0.f)
+                              : make_float4(acc.x / wsum, acc.y / wsum, acc.z / wsum, acc.w / wsum);
+        store_out4<OUT>(out, o_idx * d + e, r);
     }
-    const float r = !none ? acc / wsum : 0.f;
-    if (e < d) store_out<OUT>(out, o_idx * d + e, r);
-    if (lse && e == 0) lse[o_idx] = !none ? M + logf(wsum) : -INFINITY;
+    if (lse && lane == 0) lse[o_idx] = !none ? M + logf(wsum) : -INFINITY;
 }
 
 // Tile-stream layout: sequence s was cut by the workgroups seg_first[s] .. seg_last[s]; workgroup w left its
@@ -135,7 +169,6 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
 {
     const int64_t blocks = (int64_t)a.total_q * a.num_q_heads;
     if (blocks > 0x7fffffffLL) return PA_ERR_UNSUPPORTED;
-    const int threads = ((a.cache.head_dim + 63) / 64) * 64;
     ProfileScope prof("paged_attention_merge_kernel", stream);
     if (a.stream_split) {
         // tile-stream partials of the MFMA decode kernel (16-bit pools only); with cu_q_lens: the few-query
@@ -156,9 +189,10 @@ pa_status launch_merge(const AttnArgs& a, hipStream_t stream)
     auto kern = a.dtype == PA_DTYPE_BF16  ? paged_attention_merge_kernel<PA_DTYPE_BF16>
                 : a.dtype == PA_DTYPE_F16 ? paged_attention_merge_kernel<PA_DTYPE_F16>
                                           : paged_attention_merge_kernel<PA_DTYPE_F32>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(threads), 0, stream, a.part_o, a.part_lse, a.out, a.lse,
-                       a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads, a.cache.head_dim, a.causal, a.plan.chunk,
-                       a.plan.nsplit);
+    if (a.cache.head_dim % 4 != 0) return PA_ERR_UNSUPPORTED;   // (16-byte rows: every supported element type has it)
+    hipLaunchKernelGGL(kern, dim3((uint32_t)((blocks + kMergePairs - 1) / kMergePairs)), dim3(256), 0, stream, a.part_o,
+                       a.part_lse, a.out, a.lse, a.cu_q_lens, a.seq_lens, a.batch, a.num_q_heads, a.cache.head_dim,
+                       a.causal, a.plan.chunk, a.plan.nsplit, blocks);
     return launch_status();
 }
 
