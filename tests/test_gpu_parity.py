@@ -442,6 +442,29 @@ def test_portable_decode_chunk_schedules(pa, oracle, chunk):
         binding.pa_set_option("force_generic", 0)
 
 
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [(torch.float32, 72, 3, 3), (torch.float32, 256, 5, 1),
+                                            (torch.bfloat16, 200, 6, 2), (torch.float16, 64, 7, 7)])
+@pytest.mark.parametrize("mode", ["decode", "prefill"])
+def test_chunk_merge_shapes(pa, oracle, dtype, d, Hq, Hkv, mode):
+    """The merge of fixed-size context chunks (eight (row, head) pairs per workgroup, four columns per lane): pair
+    counts that do not fill the last workgroup, head_dims that leave lanes idle or need two passes, every output type,
+    rows without keys in some chunks."""
+    from paper_2506_07311_amd import binding
+    lens = [1000, 3, 0, 257, 700]
+    q_lens = None if mode == "decode" else [5, 3, 0, 1, 130]
+    w = W.make_workload("t", seq_lens=lens, q_lens=q_lens, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, page_size=16,
+                        dtype=dtype, causal=(mode == "prefill"), seed=34, device=DEV)
+    binding.pa_set_option("decode_chunk_tokens", 128)
+    binding.pa_set_option("prefill_chunk_tokens", 128)
+    binding.pa_set_option("force_generic", 1)
+    try:
+        parity.check_step(pa, oracle, w, f"chunk merge {mode} {dtype} d={d} {Hq}/{Hkv}")
+    finally:
+        binding.pa_set_option("decode_chunk_tokens", 0)
+        binding.pa_set_option("prefill_chunk_tokens", 0)
+        binding.pa_set_option("force_generic", 0)
+
+
 def test_many_sequences_decode(pa, oracle):
     """More sequences than lanes in a wave: the tile-stream schedule scans the lengths in blocks of 64."""
     rng = np.random.default_rng(5)
